@@ -1,0 +1,194 @@
+/*
+ * helios.h -- C ABI of the MI355X (gfx950) library for the mini-batch
+ * preparation path of Helios (arXiv 2310.00837): k-hop uniform neighbour
+ * sampling over a CSR graph, de-duplication of the sampled IDs, lookup in a
+ * GPU-managed two-tier feature cache, gather of feature rows and the miss
+ * list for the storage tier.
+ *
+ * General rules
+ * -------------
+ *  - Every function returns a helios_status.  Errors that the host can see
+ *    (null pointer, negative size, call order) are returned at once and
+ *    nothing is launched.  helios_last_error() gives a text for the last one.
+ *  - All work is asynchronous on the context's HIP stream.  Errors that only
+ *    the device can see (a node ID outside [0, N), an output that does not
+ *    fit its capacity) are recorded on the device and returned by the next
+ *    helios_sync(); nothing is written beyond a capacity.
+ *  - "device" pointers are HIP device memory.  "device-accessible" pointers
+ *    may be device memory or pinned, GPU-mapped host memory (hipHostMalloc);
+ *    their contents are valid after helios_sync().
+ *  - "host" pointers are ordinary host memory, read during the call only.
+ *  - All caller buffers are BORROWED: the library never frees or reallocates
+ *    them.  Graph and cache tables must outlive the context (or the next
+ *    helios_csr_load / helios_cache_build).
+ *  - Node IDs, positions and slots are int32; edge offsets and counts int64.
+ *    A single call handles fewer than 2^31 IDs; a CSR row holds fewer than
+ *    2^31 entries.
+ *  - The library allocates its own scratch (hash table, scan state, position
+ *    lists) and grows it when a call needs more than any call before;
+ *    helios_reserve() does that ahead of time.
+ *  - One context serves one stream; calls on one context must not overlap
+ *    from several host threads.
+ */
+#ifndef HELIOS_H
+#define HELIOS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct helios_ctx helios_ctx;
+
+typedef enum {
+    HELIOS_OK = 0,
+    HELIOS_EINVAL = -1,    /* bad argument seen by the host                         */
+    HELIOS_ECAPACITY = -2, /* an output did not fit its capacity (from helios_sync)  */
+    HELIOS_EHIP = -3,      /* a HIP runtime call failed                              */
+    HELIOS_ESTATE = -4,    /* call order: graph or cache not loaded yet              */
+    HELIOS_EDATA = -5      /* a node ID outside [0, N), or an order that is not a
+                              permutation (from helios_sync)                         */
+} helios_status;
+
+#define HELIOS_MAX_HOPS 8
+#define HELIOS_MAX_FANOUT 1024
+
+/* Context on `device`, working on `hip_stream` (a hipStream_t, borrowed;
+ * NULL = the default stream).  helios_destroy waits for the stream and frees
+ * the library's own memory only. */
+int helios_create(helios_ctx **out, int device, void *hip_stream);
+int helios_destroy(helios_ctx *ctx);
+const char *helios_last_error(const helios_ctx *ctx);
+
+/* Grow the scratch so that calls with up to max_ids IDs allocate nothing. */
+int helios_reserve(helios_ctx *ctx, int64_t max_ids);
+
+/* Wait for the stream; return the first device-side error since the last
+ * helios_sync (and clear it), else HELIOS_OK. */
+int helios_sync(helios_ctx *ctx);
+
+/* Graph topology (Sec. 3.2.1: the whole topology is kept where GPU threads
+ * read it directly).  offsets: int64[n_nodes+1], indices: int32[n_edges];
+ * row v = indices[offsets[v] .. offsets[v+1]) = the IDs that can be sampled
+ * as neighbours of v.  Both are device-accessible, borrowed. */
+int helios_csr_load(helios_ctx *ctx, int64_t n_nodes, int64_t n_edges,
+                    const int64_t *offsets, const int32_t *indices);
+
+/* Cache placement (Sec. 3.2.2 "Cache Initialization": vertices sorted by
+ * hotness, the hottest rows fill GPU memory, the next-hottest fill CPU
+ * memory).  hotness_order: device int32[n_nodes], a permutation;
+ * hotness_order[r] is the node of rank r.  The library builds and owns
+ * rank[] (rank[hotness_order[r]] = r).  hbm_rows / host_rows are clamped to
+ * what is left of n_nodes.  The three tables are borrowed, laid out in rank
+ * order, row_bytes per row (a multiple of 16):
+ *   hbm_table     device memory,       row r <-> rank r
+ *   host_table    pinned mapped host,  row s <-> rank hbm_rows + s
+ *   standin_table pinned mapped host,  row t <-> rank hbm_rows + host_rows + t
+ * (the stand-in replaces the SSD array of Sec. 3.1; it may be NULL if
+ * helios_gather_miss is never called).  A table with zero rows may be NULL.
+ * Requires helios_csr_load first (for n_nodes). */
+int helios_cache_build(helios_ctx *ctx, const int32_t *hotness_order,
+                       int64_t hbm_rows, int64_t host_rows, int32_t row_bytes,
+                       const void *hbm_table, const void *host_table, const void *standin_table);
+
+/* Helper for filling a tier table from a full feature table:
+ * dst[i, :] = src[order[first_rank + i], :] for i in [0, n_rows).
+ * src and dst are device-accessible; order is device int32. */
+int helios_cache_fill(helios_ctx *ctx, const void *src_table, const int32_t *order,
+                      int64_t first_rank, int64_t n_rows, int32_t row_bytes, void *dst);
+
+/* k-hop uniform neighbour sampling without replacement (Sec. 3.2.2 "Cache
+ * Lookup": a GPU kernel for neighbour sampling; Sec. 4.1: 2-hop, fan-outs 25
+ * and 10).  The frontier of hop 0 is `seeds` as given; the frontier of hop
+ * h+1 is the de-duplicated sample list of hop h in first-occurrence order.
+ * Node v at hop h yields min(deg(v), fanouts[h]) neighbours: the whole row in
+ * CSR order if it is no longer than the fan-out, else positions chosen by
+ * Floyd's subset algorithm from Philox4x32-10 draws keyed by
+ * (rng_seed, hop, v), so a node's sample does not depend on its place in the
+ * frontier.
+ *   seeds    device int32[n_seeds]
+ *   fanouts  host int32[n_hops], 0 <= fanout <= HELIOS_MAX_FANOUT
+ *   hops     host array of n_hops descriptors of device output buffers:
+ *            frontier[frontier_cap], indptr[frontier_cap + 1], flat[flat_cap];
+ *            the worst case is frontier_cap(0) = n_seeds,
+ *            flat_cap(h) = frontier_cap(h) * fanouts[h], frontier_cap(h+1) = flat_cap(h)
+ *   sizes    device-accessible int64[2 * n_hops]: sizes[2h] = |frontier h|,
+ *            sizes[2h+1] = |flat h| (the required sizes, also on ECAPACITY)
+ * flat[indptr[i] .. indptr[i+1]) are the samples of frontier[i]. */
+typedef struct {
+    int32_t *frontier;
+    int64_t frontier_cap;
+    int64_t *indptr;
+    int32_t *flat;
+    int64_t flat_cap;
+} helios_hop_out;
+
+int helios_sample(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
+                  const int32_t *fanouts, int32_t n_hops, uint64_t rng_seed,
+                  const helios_hop_out *hops, int64_t *sizes);
+
+/* De-duplication of the sampled ID list (the "sampled vertices' ID list" of
+ * Sec. 3.1.1).  unique = the distinct values of ids in order of first
+ * occurrence; inverse[j] (nullable) = index in unique of ids[j].
+ *   ids device int32[n_ids]; unique device int32[unique_cap];
+ *   inverse device int32[n_ids]; n_unique device-accessible int64[1]. */
+int helios_dedup(helios_ctx *ctx, const int32_t *ids, int64_t n_ids,
+                 int32_t *unique, int64_t unique_cap, int32_t *inverse, int64_t *n_unique);
+
+/* Cache lookup + feature gather + miss list (Sec. 3.2.2 "Cache Lookup": GPU
+ * threads read cached rows directly from GPU memory or, through the mapped
+ * address, from CPU memory; Sec. 3.1.1: the IDs found in neither cache are
+ * the request list of the storage tier).  For j in [0, n_ids): r =
+ * rank[ids[j]]; r < hbm_rows: out[j,:] = hbm_table[r,:]; r < hbm_rows +
+ * host_rows: out[j,:] = host_table[r - hbm_rows,:]; else out[j,:] is left
+ * untouched and (j, ids[j], r - hbm_rows - host_rows) is appended to the
+ * miss list, which is dense and ascending in j.
+ *   ids device int32[n_ids] (duplicates allowed);  out device [n_ids x row_bytes]
+ *   miss_pos / miss_id / miss_slot device int32[miss_cap]
+ *   stats device-accessible; n_hit_hbm + n_hit_host + n_miss = n_ids */
+typedef struct {
+    int64_t n_ids;
+    int64_t n_hit_hbm;
+    int64_t n_hit_host;
+    int64_t n_miss;
+} helios_gather_stats;
+
+int helios_gather(helios_ctx *ctx, const int32_t *ids, int64_t n_ids, void *out,
+                  int32_t *miss_pos, int32_t *miss_id, int32_t *miss_slot, int64_t miss_cap,
+                  helios_gather_stats *stats);
+
+/* Service of the miss list from the storage stand-in (in place of the IO
+ * stack of Sec. 3.1): out[miss_pos[k],:] = standin_table[miss_slot[k],:].
+ * n_miss_max bounds the list; if n_miss_dev (device-accessible int64, e.g.
+ * &stats->n_miss) is not NULL the count is read from it on the device,
+ * otherwise exactly n_miss_max entries are served. */
+int helios_gather_miss(helios_ctx *ctx, const int32_t *miss_pos, const int32_t *miss_slot,
+                       int64_t n_miss_max, const int64_t *n_miss_dev, void *out);
+
+/* The whole path for one mini-batch with no host round trip between the
+ * steps: helios_sample, then helios_dedup of [seeds | flat_0 | ... |
+ * flat_{K-1}], then helios_gather of the unique IDs (Sec. 3.3 decomposes an
+ * iteration into these operators).  Arguments as in the three calls;
+ * inverse (nullable) has room for n_seeds + sum_h flat_cap(h) entries; out has
+ * room for unique_cap rows.  Results equal those of the three calls made one
+ * after the other. */
+int helios_prepare_batch(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
+                         const int32_t *fanouts, int32_t n_hops, uint64_t rng_seed,
+                         const helios_hop_out *hops, int64_t *sizes,
+                         int32_t *unique, int64_t unique_cap, int32_t *inverse, int64_t *n_unique,
+                         void *out, int32_t *miss_pos, int32_t *miss_id, int32_t *miss_slot,
+                         int64_t miss_cap, helios_gather_stats *stats);
+
+/* Timing of the two gather kernels of the last helios_gather /
+ * helios_prepare_batch on this context, from HIP events recorded on the
+ * streams the kernels ran on.  Enable first; when enabled, each such call
+ * records events around the HBM-tier and the host-tier row-copy kernels.
+ * helios_gather_times waits for them and returns milliseconds. */
+int helios_set_timing(helios_ctx *ctx, int enabled);
+int helios_gather_times(helios_ctx *ctx, float *hbm_ms, float *host_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HELIOS_H */

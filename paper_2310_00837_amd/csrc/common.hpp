@@ -1,0 +1,74 @@
+// Shared device-side helpers of the Helios HIP kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace helios {
+
+constexpr int kBlock = 256;          // threads per workgroup in every kernel
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// device-side error codes, same values as helios_status
+constexpr int kErrCapacity = -2;
+constexpr int kErrData = -5;
+
+// A count that is known either on the host (dev == nullptr: the count is
+// `host`) or only on the device (read from *dev by the kernel and clamped to
+// `host`, the most the buffers behind it can hold).
+struct Count {
+    const int64_t* dev;
+    int64_t host;
+    __device__ __forceinline__ int64_t get() const {
+        if (!dev) return host;
+        const int64_t v = *dev;
+        return v < host ? (v < 0 ? 0 : v) : host;
+    }
+};
+
+// First error wins is not needed: any recorded error makes the call fail.
+// err points to pinned, GPU-mapped host memory (int32[2]: code, detail).
+__device__ __forceinline__ void raise(int32_t* err, int code) {
+    *reinterpret_cast<volatile int32_t*>(err) = code;
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    return v;
+}
+
+// inclusive scan over the 64 lanes of a wave
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, kWave);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one value per thread over the block; `total` is the block
+// sum (valid in every thread).  `s_wave` is kWavesPerBlock+1 words of LDS.
+// Contains block barriers: call from uniform control flow.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave, uint32_t& total) {
+    uint32_t inc = wave_inclusive_scan(v);
+    if (lane_id() == kWave - 1) s_wave[wave_id()] = inc;
+    __syncthreads();
+    uint32_t base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        uint32_t t = s_wave[w];
+        if (w < wave_id()) base += t;
+        sum += t;
+    }
+    total = sum;
+    __syncthreads();            // s_wave may be reused by the caller
+    return base + inc - v;
+}
+
+}  // namespace helios

@@ -1,0 +1,167 @@
+// Order-preserving de-duplication of an ID list.
+//
+// unique = the distinct IDs in order of first occurrence.  The order is made
+// independent of thread scheduling by keeping, per distinct ID, the smallest
+// input position that holds it:
+//   1. insert: an open-addressing hash table of 64-bit words {id:32 | pos:32}.
+//      A slot is claimed with one compare-and-swap; later positions of the same
+//      ID fold in with a 64-bit atomic minimum (the ID is in the high half, so
+//      the minimum orders by position).  The slot of every input is remembered.
+//   2. compact: input j is a first occurrence iff its slot's position is j; the
+//      flags are scanned in-workgroup and chained across workgroups, so the
+//      unique list comes out in input order in the same pass.
+//   3. inverse (optional): every input looks up the unique index of its ID's
+//      first occurrence.
+// The table has at least twice as many slots as inputs and is cleared by the
+// same stream before use; at the sizes of one mini-batch it stays in L2 / MALL.
+#include "kernels.hpp"
+
+namespace helios {
+
+namespace {
+
+constexpr unsigned long long kEmpty = ~0ull;
+
+__device__ __forceinline__ uint32_t hash_id(uint32_t id, uint32_t mask) {
+    uint32_t h = id * 0x9E3779B1u;
+    h ^= h >> 15;
+    h *= 0x85EBCA77u;
+    h ^= h >> 13;
+    return h & mask;
+}
+
+__global__ __launch_bounds__(kBlock) void dedup_clear_kernel(unsigned long long* table, uint32_t n_slots) {
+    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n_slots; i += gridDim.x * kBlock) table[i] = kEmpty;
+}
+
+__global__ __launch_bounds__(kBlock) void dedup_insert_kernel(const int32_t* __restrict__ ids, Count n_in, int64_t n_nodes,
+                                                              DedupScratch s, int32_t* err) {
+    const int64_t n = n_in.get();
+    const uint32_t mask = s.n_slots - 1;
+    for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < n;
+         j += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const int32_t id = ids[j];
+        if (id < 0 || static_cast<int64_t>(id) >= n_nodes) {
+            raise(err, kErrData);
+            s.slot_of[j] = -1;
+            continue;
+        }
+        const unsigned long long mine = (static_cast<unsigned long long>(static_cast<uint32_t>(id)) << 32) |
+                                        static_cast<uint32_t>(j);
+        uint32_t slot = hash_id(static_cast<uint32_t>(id), mask);
+        // the table is at most half full, so an empty slot is always reached
+        while (true) {
+            unsigned long long cur = __hip_atomic_load(s.table + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (cur == kEmpty) {
+                cur = atomicCAS(s.table + slot, kEmpty, mine);
+                if (cur == kEmpty) break;                       // claimed
+            }
+            if (static_cast<uint32_t>(cur >> 32) == static_cast<uint32_t>(id)) {
+                if (mine < cur) atomicMin(s.table + slot, mine);
+                break;
+            }
+            slot = (slot + 1) & mask;
+        }
+        s.slot_of[j] = static_cast<int32_t>(slot);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __restrict__ ids, Count n_in, DedupScratch s,
+                                                               int32_t* unique, int64_t unique_cap,
+                                                               int64_t* n_unique_dev, int64_t* n_unique_out,
+                                                               ScanState scan, int32_t* err) {
+    __shared__ uint32_t s_wave[kWavesPerBlock + 1];
+    __shared__ uint32_t s_ticket, s_agg[1], s_excl[1];
+    const uint32_t tile = scan_take_ticket(scan, &s_ticket);
+    const int64_t n = n_in.get();
+    const int64_t n_tiles = (n + kBlock - 1) / kBlock;
+    if (n == 0 && tile == 0 && threadIdx.x == 0) {
+        *n_unique_dev = 0;
+        if (n_unique_out) *n_unique_out = 0;
+    }
+    if (static_cast<int64_t>(tile) >= n_tiles) return;
+    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    uint32_t is_first = 0;
+    int32_t id = 0;
+    if (j < n) {
+        const int32_t slot = s.slot_of[j];
+        if (slot >= 0) {
+            id = ids[j];
+            is_first = static_cast<uint32_t>(s.table[slot]) == static_cast<uint32_t>(j) ? 1u : 0u;
+        }
+    }
+    uint32_t tile_total;
+    const uint32_t local = block_exclusive_scan(is_first, s_wave, tile_total);
+    if (threadIdx.x == 0) s_agg[0] = tile_total;
+    scan_chained_prefix<1>(scan, tile, s_agg, s_excl);
+    const int64_t at = static_cast<int64_t>(s_excl[0]) + local;
+    if (is_first) {
+        s.index_of_first[j] = static_cast<int32_t>(at);
+        if (at < unique_cap) unique[at] = id;
+    }
+    if (static_cast<int64_t>(tile) == n_tiles - 1 && threadIdx.x == 0) {
+        const int64_t total = static_cast<int64_t>(s_excl[0]) + tile_total;
+        *n_unique_dev = total;
+        if (n_unique_out) *n_unique_out = total;
+        if (total > unique_cap) raise(err, kErrCapacity);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void dedup_inverse_kernel(Count n_in, DedupScratch s, int32_t* inverse) {
+    const int64_t n = n_in.get();
+    for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < n;
+         j += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const int32_t slot = s.slot_of[j];
+        int32_t inv = -1;
+        if (slot >= 0) inv = s.index_of_first[static_cast<uint32_t>(s.table[slot])];
+        inverse[j] = inv;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void concat_kernel(ConcatArgs a, int32_t* dst, int64_t* n_total_dev) {
+    int64_t start[HELIOS_KERNELS_MAX_SEG + 1];
+    start[0] = 0;
+#pragma unroll
+    for (int k = 0; k < HELIOS_KERNELS_MAX_SEG; ++k) start[k + 1] = start[k] + (k < a.n_seg ? a.len[k].get() : 0);
+    const int64_t total = start[HELIOS_KERNELS_MAX_SEG];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_total_dev = total;
+    for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < total;
+         j += static_cast<int64_t>(gridDim.x) * kBlock) {
+        int k = 0;
+#pragma unroll
+        for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
+            if (q < a.n_seg && j >= start[q]) k = q;
+        dst[j] = a.src[k][j - start[k]];
+    }
+}
+
+unsigned grid_for(int64_t n_max, unsigned cap_blocks) {
+    int64_t b = (n_max + kBlock - 1) / kBlock;
+    if (b < 1) b = 1;
+    if (b > cap_blocks) b = cap_blocks;
+    return static_cast<unsigned>(b);
+}
+
+}  // namespace
+
+hipError_t launch_dedup(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
+                        const DedupScratch& s, int32_t* unique, int64_t unique_cap, int32_t* inverse,
+                        int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err) {
+    const dim3 block(kBlock);
+    hipLaunchKernelGGL(dedup_clear_kernel, dim3(grid_for(s.n_slots, 2048)), block, 0, stream, s.table, s.n_slots);
+    hipLaunchKernelGGL(dedup_insert_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, ids, n, n_nodes, s, err);
+    int64_t tiles = (n_max + kBlock - 1) / kBlock;
+    if (tiles < 1) tiles = 1;
+    hipLaunchKernelGGL(dedup_compact_kernel, dim3(static_cast<unsigned>(tiles)), block, 0, stream, ids, n, s, unique,
+                       unique_cap, n_unique_dev, n_unique_out, scan, err);
+    if (inverse)
+        hipLaunchKernelGGL(dedup_inverse_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, n, s, inverse);
+    return hipGetLastError();
+}
+
+hipError_t launch_concat(hipStream_t stream, const ConcatArgs& a, int64_t n_max, int32_t* dst, int64_t* n_total_dev) {
+    hipLaunchKernelGGL(concat_kernel, dim3(grid_for(n_max, 4096)), dim3(kBlock), 0, stream, a, dst, n_total_dev);
+    return hipGetLastError();
+}
+
+}  // namespace helios

@@ -1,0 +1,126 @@
+// Row copy: out[pos[k], :] = table[slot[k], :].
+//
+// The rows are 256 B - 2 KB, at random places of a table of tens of GB, so the
+// kernel is bound by memory bandwidth (HBM for the GPU tier, the host link for
+// the pinned-host tier and the storage stand-in).  A group of L lanes owns one
+// row and moves it as 16-byte pieces, so a row is read and written as whole
+// contiguous lines; L is the smallest power of two that covers the row (at most
+// a wave).  Each group takes R list entries per step and issues all their loads
+// before the first store, which keeps R * L * 16 bytes in flight per group; the
+// grid is persistent (a few workgroups per CU, striding over the list) and the
+// count is read on the device, so no host round trip sits between the lookup
+// and the copy.  Source and destination are touched once: non-temporal
+// accesses keep them from displacing the graph and the cache map in L2.
+#include "kernels.hpp"
+
+namespace helios {
+
+namespace {
+
+typedef uint32_t chunk16 __attribute__((ext_vector_type(4)));   // one 16-byte piece of a row
+
+struct GatherArgs {
+    const chunk16* table;
+    const int32_t* pos;     // nullable: identity
+    const int32_t* slot;
+    Count n;
+    int32_t chunks;         // 16-byte pieces per row
+    chunk16* out;
+};
+
+__device__ __forceinline__ chunk16 load16(const chunk16* p) {
+    return __builtin_nontemporal_load(p);
+}
+__device__ __forceinline__ void store16(chunk16* p, const chunk16& v) {
+    __builtin_nontemporal_store(v, p);
+}
+
+// L lanes per row, CPL pieces per lane (L * CPL >= chunks), R rows per step.
+template <int L, int CPL, int R>
+__global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
+    constexpr int kGroups = kBlock / L;
+    const int64_t n = a.n.get();
+    const int l = threadIdx.x % L;
+    const int g = threadIdx.x / L;
+    const int64_t step = static_cast<int64_t>(gridDim.x) * kGroups * R;
+    for (int64_t k0 = (static_cast<int64_t>(blockIdx.x) * kGroups + g) * R; k0 < n; k0 += step) {
+        chunk16 v[R][CPL];
+        int64_t dst[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t k = k0 + r;
+            dst[r] = -1;
+            if (k < n) {
+                const int64_t s = a.slot[k];
+                dst[r] = a.pos ? static_cast<int64_t>(a.pos[k]) : k;
+                const chunk16* src = a.table + s * a.chunks;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const int idx = l + c * L;
+                    if (idx < a.chunks) v[r][c] = load16(src + idx);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (dst[r] >= 0) {
+                chunk16* o = a.out + dst[r] * a.chunks;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const int idx = l + c * L;
+                    if (idx < a.chunks) store16(o + idx, v[r][c]);
+                }
+            }
+        }
+    }
+}
+
+// any row length: a wave per row, looping over the pieces
+__global__ __launch_bounds__(kBlock) void gather_rows_long_kernel(GatherArgs a) {
+    const int64_t n = a.n.get();
+    const int l = lane_id();
+    const int64_t step = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave_id(); k < n; k += step) {
+        const int64_t s = a.slot[k];
+        const int64_t d = a.pos ? static_cast<int64_t>(a.pos[k]) : k;
+        const chunk16* src = a.table + s * a.chunks;
+        chunk16* o = a.out + d * a.chunks;
+        for (int idx = l; idx < a.chunks; idx += kWave) store16(o + idx, load16(src + idx));
+    }
+}
+
+template <int L, int CPL, int R>
+void launch_shape(hipStream_t stream, const GatherArgs& a, int64_t n_max, unsigned max_blocks) {
+    constexpr int kRowsPerBlockStep = (kBlock / L) * R;
+    int64_t blocks = (n_max + kRowsPerBlockStep - 1) / kRowsPerBlockStep;
+    if (blocks < 1) blocks = 1;
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipLaunchKernelGGL((gather_rows_kernel<L, CPL, R>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream, a);
+}
+
+}  // namespace
+
+hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
+                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source) {
+    GatherArgs a{static_cast<const chunk16*>(table), pos, slot, n, row_bytes / 16, static_cast<chunk16*>(out)};
+    // persistent grid: 8 workgroups per CU for HBM sources; a far (host-link) source
+    // saturates with far fewer requests in flight and leaves the CUs to other kernels
+    const unsigned max_blocks = far_source ? 256u : 2048u;
+    const int c = a.chunks;
+    if (c <= 4) launch_shape<4, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 8) launch_shape<8, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 16) launch_shape<16, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 32) launch_shape<32, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 64) launch_shape<64, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 128) launch_shape<64, 2, 2>(stream, a, n_max, max_blocks);
+    else if (c <= 256) launch_shape<64, 4, 1>(stream, a, n_max, max_blocks);
+    else {
+        int64_t blocks = (n_max + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (blocks < 1) blocks = 1;
+        if (blocks > max_blocks) blocks = max_blocks;
+        hipLaunchKernelGGL(gather_rows_long_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace helios

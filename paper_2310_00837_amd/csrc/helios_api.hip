@@ -1,0 +1,503 @@
+// Host runtime and C ABI of the Helios library: context, scratch memory,
+// launch order of the kernels, device-side error word.  See include/helios.h
+// for the contract of every entry point.
+#include "../../include/helios.h"
+#include "kernels.hpp"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+using namespace helios;
+
+namespace {
+
+// device counters (int64 each)
+constexpr int kCntFrontier = 0;     // [HELIOS_MAX_HOPS + 1] frontier sizes
+constexpr int kCntFlat = 16;        // [HELIOS_MAX_HOPS] sample-list sizes
+constexpr int kCntCat = 32;         // length of [seeds | flat_0 | ...]
+constexpr int kCntUnique = 33;
+constexpr int kCntTier = 40;        // [3] HBM hits, host hits, misses
+constexpr int kNumCounters = 64;
+
+}  // namespace
+
+struct helios_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    hipStream_t aux = nullptr;                 // host-tier row copies run here, beside the HBM-tier ones
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool timing = false, timed = false;
+    hipEvent_t t_hbm[2] = {nullptr, nullptr}, t_host[2] = {nullptr, nullptr};
+    bool timed_hbm = false, timed_host = false;
+    char errmsg[256] = {0};
+
+    CsrView g{nullptr, nullptr, 0};
+    int64_t n_edges = 0;
+    bool has_graph = false;
+
+    int32_t* rank = nullptr;
+    int64_t rank_cap = 0;
+    int64_t n_hbm = 0, n_host = 0;
+    int32_t row_bytes = 0;
+    const void *hbm_table = nullptr, *host_table = nullptr, *standin_table = nullptr;
+    bool has_cache = false;
+
+    int32_t* err = nullptr;                    // pinned, GPU-mapped int32[2]
+    int64_t* cnt = nullptr;                    // device int64[kNumCounters]
+
+    int64_t cap_ids = 0;                       // IDs per call the scratch below has room for
+    DedupScratch dd{nullptr, 0, nullptr, nullptr};
+    int32_t* list_pos[2] = {nullptr, nullptr};
+    int32_t* list_slot[2] = {nullptr, nullptr};
+    int32_t* cat = nullptr;
+    unsigned long long* scan_status = nullptr;
+    uint32_t scan_stride = 0;
+    uint32_t* scan_ticket = nullptr;
+    uint32_t epoch = 0;
+};
+
+namespace {
+
+int fail(helios_ctx* c, int code, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->errmsg, sizeof(c->errmsg), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define HIP_TRY(c, expr)                                                                       \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail((c), HELIOS_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// keeps the caller's current device
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && (prev == dev || hipSetDevice(dev) == hipSuccess)) ok = true;
+        want = dev;
+    }
+    ~DeviceGuard() {
+        if (ok && prev != want) (void)hipSetDevice(prev);
+    }
+    int want;
+};
+
+uint32_t pow2_at_least(int64_t n) {
+    uint32_t p = 1024;
+    while (static_cast<int64_t>(p) < n && p < (1u << 31)) p <<= 1;
+    return p;
+}
+
+void free_scratch(helios_ctx* c) {
+    (void)hipFree(c->dd.table);
+    (void)hipFree(c->dd.slot_of);
+    (void)hipFree(c->dd.index_of_first);
+    for (int t = 0; t < 2; ++t) {
+        (void)hipFree(c->list_pos[t]);
+        (void)hipFree(c->list_slot[t]);
+        c->list_pos[t] = c->list_slot[t] = nullptr;
+    }
+    (void)hipFree(c->cat);
+    (void)hipFree(c->scan_status);
+    c->dd = DedupScratch{nullptr, 0, nullptr, nullptr};
+    c->cat = nullptr;
+    c->scan_status = nullptr;
+    c->cap_ids = 0;
+    c->scan_stride = 0;
+}
+
+// Scratch for calls with up to n IDs.  Growing waits for the stream first: the
+// old buffers may still be in use.
+int ensure_capacity(helios_ctx* c, int64_t n) {
+    if (n <= c->cap_ids) return HELIOS_OK;
+    if (n >= (1ll << 31) - 1024) return fail(c, HELIOS_EINVAL, "a call handles fewer than 2^31 IDs (got %lld)", (long long)n);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    free_scratch(c);
+    const int64_t cap = (n + 4095) / 4096 * 4096;
+    const uint32_t slots = pow2_at_least(2 * cap);
+    const uint32_t stride = static_cast<uint32_t>(cap / kBlock + 2);
+    HIP_TRY(c, hipMalloc(&c->dd.table, sizeof(unsigned long long) * slots));
+    HIP_TRY(c, hipMalloc(&c->dd.slot_of, sizeof(int32_t) * cap));
+    HIP_TRY(c, hipMalloc(&c->dd.index_of_first, sizeof(int32_t) * cap));
+    for (int t = 0; t < 2; ++t) {
+        HIP_TRY(c, hipMalloc(&c->list_pos[t], sizeof(int32_t) * cap));
+        HIP_TRY(c, hipMalloc(&c->list_slot[t], sizeof(int32_t) * cap));
+    }
+    HIP_TRY(c, hipMalloc(&c->cat, sizeof(int32_t) * cap));
+    HIP_TRY(c, hipMalloc(&c->scan_status, sizeof(unsigned long long) * 3 * stride));
+    HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * stride, c->stream));
+    c->dd.n_slots = slots;
+    c->scan_stride = stride;
+    c->epoch = 0;
+    c->cap_ids = cap;
+    return HELIOS_OK;
+}
+
+// scan state with a fresh epoch; stale status words of earlier launches read as unpublished
+int next_scan(helios_ctx* c, ScanState* out) {
+    if (c->epoch >= (1u << 30) - 2) {
+        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * c->scan_stride, c->stream));
+        c->epoch = 0;
+    }
+    c->epoch += 1;
+    *out = ScanState{c->scan_status, c->scan_ticket, c->scan_stride, c->epoch};
+    return HELIOS_OK;
+}
+
+int64_t sat_mul(int64_t a, int64_t b) {
+    if (a == 0 || b == 0) return 0;
+    if (a > (1ll << 40) / b) return 1ll << 40;
+    return a * b;
+}
+
+struct HopPlan {
+    int64_t frontier_max[HELIOS_MAX_HOPS];   // bound on |frontier h| that the buffers can hold
+    int64_t flat_max[HELIOS_MAX_HOPS];       // bound on |flat h| that the buffers can hold
+    int64_t cat_max;                         // n_seeds + sum flat_max
+    int64_t ids_max;                         // the largest list any kernel of the call sees
+};
+
+int plan_hops(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, const helios_hop_out* hops,
+              HopPlan* p) {
+    if (n_seeds < 0) return fail(c, HELIOS_EINVAL, "n_seeds < 0");
+    if (n_hops < 1 || n_hops > HELIOS_MAX_HOPS) return fail(c, HELIOS_EINVAL, "n_hops must be 1..%d", HELIOS_MAX_HOPS);
+    if (!fanouts || !hops) return fail(c, HELIOS_EINVAL, "fanouts / hops is NULL");
+    int64_t nf = n_seeds;
+    p->cat_max = n_seeds;
+    p->ids_max = n_seeds;
+    for (int h = 0; h < n_hops; ++h) {
+        const helios_hop_out& o = hops[h];
+        if (fanouts[h] < 0 || fanouts[h] > HELIOS_MAX_FANOUT)
+            return fail(c, HELIOS_EINVAL, "fanouts[%d] = %d outside 0..%d", h, fanouts[h], HELIOS_MAX_FANOUT);
+        if (o.frontier_cap < 0 || o.flat_cap < 0) return fail(c, HELIOS_EINVAL, "negative capacity at hop %d", h);
+        if (!o.indptr || (o.frontier_cap > 0 && !o.frontier) || (o.flat_cap > 0 && !o.flat))
+            return fail(c, HELIOS_EINVAL, "hop %d: NULL output buffer", h);
+        if (h == 0 && o.frontier_cap < n_seeds)
+            return fail(c, HELIOS_EINVAL, "hops[0].frontier_cap (%lld) < n_seeds (%lld)", (long long)o.frontier_cap, (long long)n_seeds);
+        if (nf > o.frontier_cap) nf = o.frontier_cap;
+        p->frontier_max[h] = nf;
+        int64_t fl = sat_mul(nf, fanouts[h]);
+        if (fl > o.flat_cap) fl = o.flat_cap;
+        p->flat_max[h] = fl;
+        p->cat_max += fl;
+        if (fl > p->ids_max) p->ids_max = fl;
+        nf = fl;
+    }
+    if (p->cat_max > p->ids_max) p->ids_max = p->cat_max;
+    return HELIOS_OK;
+}
+
+int dedup_impl(helios_ctx* c, const int32_t* ids, Count n, int32_t* unique, int64_t unique_cap, int32_t* inverse,
+               int64_t* n_unique_dev, int64_t* n_unique_out) {
+    ScanState scan;
+    int rc = next_scan(c, &scan);
+    if (rc) return rc;
+    DedupScratch s = c->dd;
+    s.n_slots = pow2_at_least(2 * n.host);          // a table no larger than this call needs
+    if (s.n_slots > c->dd.n_slots) s.n_slots = c->dd.n_slots;
+    HIP_TRY(c, launch_dedup(c->stream, ids, n, n.host, c->g.n_nodes, s, unique, unique_cap, inverse, n_unique_dev,
+                            n_unique_out, scan, c->err));
+    return HELIOS_OK;
+}
+
+int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p) {
+    if (n_seeds > 0)
+        HIP_TRY(c, hipMemcpyAsync(hops[0].frontier, seeds, sizeof(int32_t) * n_seeds, hipMemcpyDeviceToDevice, c->stream));
+    Count nf{nullptr, n_seeds};
+    for (int h = 0; h < n_hops; ++h) {
+        ScanState scan;
+        int rc = next_scan(c, &scan);
+        if (rc) return rc;
+        HIP_TRY(c, launch_sample_hop(c->stream, c->g, hops[h].frontier, nf, p.frontier_max[h], fanouts[h], h, rng_seed,
+                                     hops[h].indptr, hops[h].flat, hops[h].flat_cap, c->cnt + kCntFlat + h,
+                                     sizes ? sizes + 2 * h : nullptr, scan, c->err));
+        if (h + 1 < n_hops) {
+            rc = dedup_impl(c, hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}, hops[h + 1].frontier,
+                            hops[h + 1].frontier_cap, nullptr, c->cnt + kCntFrontier + h + 1, nullptr);
+            if (rc) return rc;
+            nf = Count{c->cnt + kCntFrontier + h + 1, p.frontier_max[h + 1]};
+        }
+    }
+    return HELIOS_OK;
+}
+
+int gather_impl(helios_ctx* c, const int32_t* ids, Count n, void* out, int32_t* miss_pos, int32_t* miss_id,
+                int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
+    ScanState scan;
+    int rc = next_scan(c, &scan);
+    if (rc) return rc;
+    TierLists lists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier};
+    HIP_TRY(c, launch_lookup_partition(c->stream, ids, n, n.host, c->rank, c->g.n_nodes, c->n_hbm, c->n_host, lists,
+                                       miss_pos, miss_id, miss_slot, miss_cap, reinterpret_cast<int64_t*>(stats), scan,
+                                       c->err));
+    c->timed_hbm = c->timed_host = false;
+    const bool do_hbm = c->n_hbm > 0 && n.host > 0, do_host = c->n_host > 0 && n.host > 0;
+    if (do_host) {                              // fork: the host-tier copy runs beside the HBM-tier copy
+        HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));
+        HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_fork, 0));
+    }
+    if (do_hbm) {
+        if (c->timing) HIP_TRY(c, hipEventRecord(c->t_hbm[0], c->stream));
+        HIP_TRY(c, launch_gather_rows(c->stream, c->hbm_table, lists.pos[0], lists.slot[0],
+                                      Count{c->cnt + kCntTier + 0, n.host}, n.host, c->row_bytes, out, false));
+        if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream)); c->timed_hbm = true; }
+    }
+    if (do_host) {
+        if (c->timing) HIP_TRY(c, hipEventRecord(c->t_host[0], c->aux));
+        HIP_TRY(c, launch_gather_rows(c->aux, c->host_table, lists.pos[1], lists.slot[1],
+                                      Count{c->cnt + kCntTier + 1, n.host}, n.host, c->row_bytes, out, true));
+        if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_host[1], c->aux)); c->timed_host = true; }
+        HIP_TRY(c, hipEventRecord(c->ev_join, c->aux));
+        HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+    }
+    return HELIOS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int helios_create(helios_ctx** out, int device, void* hip_stream) {
+    if (!out) return HELIOS_EINVAL;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) return HELIOS_EHIP;
+    DeviceGuard guard(device);
+    if (!guard.ok) return HELIOS_EHIP;
+    helios_ctx* c = new helios_ctx();
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    bool ok = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) == hipSuccess &&
+              hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreate(&c->t_hbm[0]) == hipSuccess && hipEventCreate(&c->t_hbm[1]) == hipSuccess &&
+              hipEventCreate(&c->t_host[0]) == hipSuccess && hipEventCreate(&c->t_host[1]) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&c->err), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
+              hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
+              hipMalloc(&c->scan_ticket, 64) == hipSuccess;
+    if (ok) {
+        c->err[0] = c->err[1] = 0;
+        ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
+             hipMemsetAsync(c->scan_ticket, 0, 64, c->stream) == hipSuccess &&
+             hipStreamSynchronize(c->stream) == hipSuccess;
+    }
+    if (!ok) {
+        helios_destroy(c);
+        return HELIOS_EHIP;
+    }
+    *out = c;
+    return HELIOS_OK;
+}
+
+int helios_destroy(helios_ctx* c) {
+    if (!c) return HELIOS_EINVAL;
+    DeviceGuard guard(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    if (c->aux) (void)hipStreamSynchronize(c->aux);
+    free_scratch(c);
+    (void)hipFree(c->rank);
+    (void)hipFree(c->cnt);
+    (void)hipFree(c->scan_ticket);
+    if (c->err) (void)hipHostFree(c->err);
+    for (hipEvent_t e : {c->ev_fork, c->ev_join, c->t_hbm[0], c->t_hbm[1], c->t_host[0], c->t_host[1]})
+        if (e) (void)hipEventDestroy(e);
+    if (c->aux) (void)hipStreamDestroy(c->aux);
+    delete c;
+    return HELIOS_OK;
+}
+
+const char* helios_last_error(const helios_ctx* c) { return c ? c->errmsg : "no context"; }
+
+int helios_reserve(helios_ctx* c, int64_t max_ids) {
+    if (!c || max_ids < 0) return fail(c, HELIOS_EINVAL, "helios_reserve: bad argument");
+    DeviceGuard guard(c->device);
+    return ensure_capacity(c, max_ids);
+}
+
+int helios_sync(helios_ctx* c) {
+    if (!c) return HELIOS_EINVAL;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const int code = *reinterpret_cast<volatile int32_t*>(c->err);
+    if (code != 0) {
+        c->err[0] = 0;
+        return fail(c, code, code == HELIOS_ECAPACITY ? "an output did not fit its capacity"
+                                                      : "a node ID outside [0, n_nodes), or an order that is not a permutation");
+    }
+    return HELIOS_OK;
+}
+
+int helios_csr_load(helios_ctx* c, int64_t n_nodes, int64_t n_edges, const int64_t* offsets, const int32_t* indices) {
+    if (!c) return HELIOS_EINVAL;
+    if (n_nodes < 0 || n_edges < 0 || n_nodes > 0x7fffffffLL) return fail(c, HELIOS_EINVAL, "bad graph size");
+    if (!offsets || (n_edges > 0 && !indices)) return fail(c, HELIOS_EINVAL, "offsets / indices is NULL");
+    c->g = CsrView{offsets, indices, n_nodes};
+    c->n_edges = n_edges;
+    c->has_graph = true;
+    c->has_cache = false;              // the cache map belongs to the graph it was built for
+    return HELIOS_OK;
+}
+
+int helios_cache_build(helios_ctx* c, const int32_t* order, int64_t hbm_rows, int64_t host_rows, int32_t row_bytes,
+                       const void* hbm_table, const void* host_table, const void* standin_table) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_graph) return fail(c, HELIOS_ESTATE, "helios_cache_build before helios_csr_load");
+    if (!order && c->g.n_nodes > 0) return fail(c, HELIOS_EINVAL, "hotness_order is NULL");
+    if (hbm_rows < 0 || host_rows < 0) return fail(c, HELIOS_EINVAL, "negative tier size");
+    if (row_bytes <= 0 || row_bytes % 16 != 0) return fail(c, HELIOS_EINVAL, "row_bytes must be a positive multiple of 16");
+    const int64_t n = c->g.n_nodes;
+    if (hbm_rows > n) hbm_rows = n;
+    if (host_rows > n - hbm_rows) host_rows = n - hbm_rows;
+    if ((hbm_rows > 0 && !hbm_table) || (host_rows > 0 && !host_table))
+        return fail(c, HELIOS_EINVAL, "a tier with rows has a NULL table");
+    DeviceGuard guard(c->device);
+    if (n > c->rank_cap) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        (void)hipFree(c->rank);
+        c->rank = nullptr;
+        c->rank_cap = 0;
+        HIP_TRY(c, hipMalloc(&c->rank, sizeof(int32_t) * (n > 0 ? n : 1)));
+        c->rank_cap = n;
+    }
+    if (n > 0) HIP_TRY(c, launch_rank_build(c->stream, order, n, c->rank, c->err));
+    c->n_hbm = hbm_rows;
+    c->n_host = host_rows;
+    c->row_bytes = row_bytes;
+    c->hbm_table = hbm_table;
+    c->host_table = host_table;
+    c->standin_table = standin_table;
+    c->has_cache = true;
+    return HELIOS_OK;
+}
+
+int helios_cache_fill(helios_ctx* c, const void* src_table, const int32_t* order, int64_t first_rank, int64_t n_rows,
+                      int32_t row_bytes, void* dst) {
+    if (!c) return HELIOS_EINVAL;
+    if (n_rows < 0 || first_rank < 0) return fail(c, HELIOS_EINVAL, "negative row range");
+    if (row_bytes <= 0 || row_bytes % 16 != 0) return fail(c, HELIOS_EINVAL, "row_bytes must be a positive multiple of 16");
+    if (n_rows == 0) return HELIOS_OK;
+    if (!src_table || !order || !dst) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, launch_gather_rows(c->stream, src_table, nullptr, order + first_rank, Count{nullptr, n_rows}, n_rows,
+                                  row_bytes, dst, false));
+    return HELIOS_OK;
+}
+
+int helios_sample(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                  uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_graph) return fail(c, HELIOS_ESTATE, "helios_sample before helios_csr_load");
+    HopPlan p;
+    int rc = plan_hops(c, n_seeds, fanouts, n_hops, hops, &p);
+    if (rc) return rc;
+    if (n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
+    DeviceGuard guard(c->device);
+    rc = ensure_capacity(c, p.ids_max);
+    if (rc) return rc;
+    return sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p);
+}
+
+int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* unique, int64_t unique_cap,
+                 int32_t* inverse, int64_t* n_unique) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_graph) return fail(c, HELIOS_ESTATE, "helios_dedup before helios_csr_load");
+    if (n_ids < 0 || unique_cap < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if ((n_ids > 0 && !ids) || (unique_cap > 0 && !unique)) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    DeviceGuard guard(c->device);
+    int rc = ensure_capacity(c, n_ids);
+    if (rc) return rc;
+    return dedup_impl(c, ids, Count{nullptr, n_ids}, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique);
+}
+
+int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, int32_t* miss_pos, int32_t* miss_id,
+                  int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_cache) return fail(c, HELIOS_ESTATE, "helios_gather before helios_cache_build");
+    if (n_ids < 0 || miss_cap < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (n_ids > 0 && (!ids || !out)) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    if (miss_cap > 0 && (!miss_pos || !miss_id || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL miss list");
+    DeviceGuard guard(c->device);
+    int rc = ensure_capacity(c, n_ids);
+    if (rc) return rc;
+    return gather_impl(c, ids, Count{nullptr, n_ids}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+}
+
+int helios_gather_miss(helios_ctx* c, const int32_t* miss_pos, const int32_t* miss_slot, int64_t n_miss_max,
+                       const int64_t* n_miss_dev, void* out) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_cache) return fail(c, HELIOS_ESTATE, "helios_gather_miss before helios_cache_build");
+    if (n_miss_max < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (n_miss_max == 0) return HELIOS_OK;
+    if (!miss_pos || !miss_slot || !out) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    if (!c->standin_table) return fail(c, HELIOS_ESTATE, "no stand-in table was given to helios_cache_build");
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, launch_gather_rows(c->stream, c->standin_table, miss_pos, miss_slot, Count{n_miss_dev, n_miss_max},
+                                  n_miss_max, c->row_bytes, out, true));
+    return HELIOS_OK;
+}
+
+int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                         uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, int32_t* unique,
+                         int64_t unique_cap, int32_t* inverse, int64_t* n_unique, void* out, int32_t* miss_pos,
+                         int32_t* miss_id, int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_graph || !c->has_cache) return fail(c, HELIOS_ESTATE, "helios_prepare_batch needs the graph and the cache");
+    HopPlan p;
+    int rc = plan_hops(c, n_seeds, fanouts, n_hops, hops, &p);
+    if (rc) return rc;
+    if (n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
+    if (unique_cap < 0 || miss_cap < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (unique_cap > 0 && (!unique || !out)) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    if (miss_cap > 0 && (!miss_pos || !miss_id || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL miss list");
+    DeviceGuard guard(c->device);
+    rc = ensure_capacity(c, p.ids_max);
+    if (rc) return rc;
+    rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p);
+    if (rc) return rc;
+    ConcatArgs cat{};
+    cat.n_seg = n_hops + 1;
+    cat.src[0] = seeds;
+    cat.len[0] = Count{nullptr, n_seeds};
+    for (int h = 0; h < n_hops; ++h) {
+        cat.src[h + 1] = hops[h].flat;
+        cat.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
+    }
+    HIP_TRY(c, launch_concat(c->stream, cat, p.cat_max, c->cat, c->cnt + kCntCat));
+    rc = dedup_impl(c, c->cat, Count{c->cnt + kCntCat, p.cat_max}, unique, unique_cap, inverse, c->cnt + kCntUnique,
+                    n_unique);
+    if (rc) return rc;
+    const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
+    return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+}
+
+int helios_set_timing(helios_ctx* c, int enabled) {
+    if (!c) return HELIOS_EINVAL;
+    c->timing = enabled != 0;
+    c->timed_hbm = c->timed_host = false;
+    return HELIOS_OK;
+}
+
+int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms) {
+    if (!c || !hbm_ms || !host_ms) return HELIOS_EINVAL;
+    DeviceGuard guard(c->device);
+    *hbm_ms = *host_ms = 0.f;
+    if (c->timed_hbm) {
+        HIP_TRY(c, hipEventSynchronize(c->t_hbm[1]));
+        HIP_TRY(c, hipEventElapsedTime(hbm_ms, c->t_hbm[0], c->t_hbm[1]));
+    }
+    if (c->timed_host) {
+        HIP_TRY(c, hipEventSynchronize(c->t_host[1]));
+        HIP_TRY(c, hipEventElapsedTime(host_ms, c->t_host[0], c->t_host[1]));
+    }
+    return HELIOS_OK;
+}
+
+}  // extern "C"

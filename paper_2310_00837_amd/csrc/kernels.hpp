@@ -1,0 +1,65 @@
+// Host-side launchers of the Helios kernels (one per step of the path).
+// Every launcher enqueues on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include "common.hpp"
+#include "scan.hpp"
+#define HELIOS_KERNELS_MAX_SEG 9
+
+namespace helios {
+
+struct CsrView {
+    const int64_t* offsets;
+    const int32_t* indices;
+    int64_t n_nodes;
+};
+
+// ---- sample.hip
+// One hop: for i < n_frontier, indptr[i] = start of frontier[i]'s samples in flat,
+// indptr[n_frontier] = total; writes n_frontier and total to size_out[0], size_out[1]
+// (device-accessible, nullable) and total to *n_flat_dev.
+hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, Count n_frontier,
+                             int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
+                             int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
+                             int64_t* size_out, const ScanState& scan, int32_t* err);
+
+// ---- dedup.hip
+struct DedupScratch {
+    unsigned long long* table;   // n_slots entries {id:32, first position:32}
+    uint32_t n_slots;            // power of two
+    int32_t* slot_of;            // [n] table slot of every input position
+    int32_t* index_of_first;     // [n] index in `unique` of a first occurrence
+};
+hipError_t launch_dedup(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
+                        const DedupScratch& s, int32_t* unique, int64_t unique_cap, int32_t* inverse,
+                        int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err);
+
+// Concatenate K+1 segments whose lengths are only known on the device:
+// dst = [seg0 | seg1 | ...], total length to *n_total_dev.
+struct ConcatArgs {
+    const int32_t* src[HELIOS_KERNELS_MAX_SEG];
+    Count len[HELIOS_KERNELS_MAX_SEG];
+    int n_seg;
+};
+hipError_t launch_concat(hipStream_t stream, const ConcatArgs& a, int64_t n_max, int32_t* dst, int64_t* n_total_dev);
+
+// ---- cache.hip
+hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n_nodes, int32_t* rank, int32_t* err);
+
+struct TierLists {
+    int32_t* pos[2];    // positions in the ID list, per cached tier (0 = HBM, 1 = host)
+    int32_t* slot[2];   // row in the tier table
+    int64_t* count;     // device int64[3]: tier 0, tier 1, misses
+};
+hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max,
+                                   const int32_t* rank, int64_t n_nodes, int64_t n_hbm, int64_t n_host,
+                                   const TierLists& lists, int32_t* miss_pos, int32_t* miss_id,
+                                   int32_t* miss_slot, int64_t miss_cap, int64_t* stats_out,
+                                   const ScanState& scan, int32_t* err);
+
+// ---- gather.hip
+// out[pos[k], :] = table[slot[k], :] for k < n; pos == nullptr means pos[k] = k.
+// `wide` selects the launch shape tuned for a far (host-link) source.
+hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
+                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source);
+
+}  // namespace helios

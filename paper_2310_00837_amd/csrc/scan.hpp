@@ -1,0 +1,101 @@
+// Single-pass chained prefix sum across workgroups (decoupled look-back).
+//
+// Each workgroup owns one tile, taken in launch order from a ticket counter so
+// that every tile a workgroup waits for is already running.  A tile publishes
+// its aggregate, then looks back over its predecessors, 64 at a time, until it
+// meets one that has published a full inclusive prefix.  One 64-bit status word
+// per tile and counter holds {epoch:30, flag:2, value:32}; the epoch changes on
+// every launch, so a stale word reads as "not published" and the buffer never
+// needs clearing between launches.
+#pragma once
+#include "common.hpp"
+
+namespace helios {
+
+struct ScanState {
+    unsigned long long* status;   // [n_counters][stride]
+    uint32_t* ticket;             // one counter, zero between launches
+    uint32_t stride;              // tiles the status rows have room for
+    uint32_t epoch;               // 1 .. 2^30-1, new for every launch
+};
+
+constexpr uint32_t kFlagAggregate = 1u;
+constexpr uint32_t kFlagPrefix = 2u;
+
+__device__ __forceinline__ unsigned long long scan_pack(uint32_t epoch, uint32_t flag, uint32_t v) {
+    return (static_cast<unsigned long long>(epoch) << 34) | (static_cast<unsigned long long>(flag) << 32) | v;
+}
+
+__device__ __forceinline__ void scan_store(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long scan_load(unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Tile index of this workgroup (launch order).  The workgroup that takes the
+// last ticket puts the counter back to zero for the next launch: by then every
+// other workgroup of this launch has taken its ticket.  Contains a barrier.
+__device__ __forceinline__ uint32_t scan_take_ticket(const ScanState& st, uint32_t* s_ticket) {
+    if (threadIdx.x == 0) {
+        uint32_t t = atomicAdd(st.ticket, 1u);
+        if (t == gridDim.x - 1) __hip_atomic_store(st.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_ticket = t;
+    }
+    __syncthreads();
+    uint32_t t = *s_ticket;
+    __syncthreads();
+    return t;
+}
+
+// Exclusive prefix of this tile's aggregates over all earlier tiles, for NC
+// counters at once.  s_agg[c] holds the tile aggregate (written by the caller
+// before the call, barrier included here); on return s_excl[c] holds the
+// exclusive prefix.  The first wave does the look-back.  Call from uniform
+// control flow; tile < st.stride is the caller's duty.
+template <int NC>
+__device__ __forceinline__ void scan_chained_prefix(const ScanState& st, uint32_t tile,
+                                                    const uint32_t* s_agg, uint32_t* s_excl) {
+    __syncthreads();
+    if (wave_id() == 0) {
+        const int lane = lane_id();
+        for (int c = 0; c < NC; ++c) {
+            unsigned long long* row = st.status + static_cast<size_t>(c) * st.stride;
+            const uint32_t agg = s_agg[c];
+            uint32_t excl = 0;
+            if (tile == 0) {
+                if (lane == 0) scan_store(row, scan_pack(st.epoch, kFlagPrefix, agg));
+            } else {
+                if (lane == 0) scan_store(row + tile, scan_pack(st.epoch, kFlagAggregate, agg));
+                int64_t first = static_cast<int64_t>(tile) - 1;      // nearest predecessor of the window
+                while (true) {
+                    const int64_t idx = first - lane;
+                    uint32_t flag = kFlagPrefix, val = 0;            // lanes before tile 0 act as an empty prefix
+                    if (idx >= 0) {
+                        unsigned long long w;
+                        do {
+                            w = scan_load(row + idx);
+                            flag = static_cast<uint32_t>(w >> 32) & 3u;
+                            if (static_cast<uint32_t>(w >> 34) != st.epoch) flag = 0;
+                            if (flag == 0) __builtin_amdgcn_s_sleep(1);
+                        } while (flag == 0);
+                        val = static_cast<uint32_t>(w);
+                    }
+                    const unsigned long long has_prefix = __ballot(flag == kFlagPrefix);
+                    if (has_prefix) {
+                        const int stop = __ffsll(static_cast<long long>(has_prefix)) - 1;
+                        excl += wave_sum(lane <= stop ? val : 0u);
+                        break;
+                    }
+                    excl += wave_sum(val);
+                    first -= kWave;
+                }
+                if (lane == 0) scan_store(row + tile, scan_pack(st.epoch, kFlagPrefix, excl + agg));
+            }
+            if (lane == 0) s_excl[c] = excl;
+        }
+    }
+    __syncthreads();
+}
+
+}  // namespace helios

@@ -1,0 +1,260 @@
+"""Thin Python binding of libhelios.so (argument marshalling only).
+
+Every step of the path runs in the library's HIP kernels; torch is used for
+device memory and streams.  There is no fallback: if the library is missing,
+importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libhelios.so")
+
+OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA = 0, -1, -2, -3, -4, -5
+MAX_HOPS, MAX_FANOUT = 8, 1024
+_NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
+          -5: "HELIOS_EDATA"}
+
+# every symbol include/helios.h declares
+EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
+           "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
+           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_set_timing",
+           "helios_gather_times"]
+
+
+class HopOut(C.Structure):
+    _fields_ = [("frontier", C.c_void_p), ("frontier_cap", C.c_int64), ("indptr", C.c_void_p),
+                ("flat", C.c_void_p), ("flat_cap", C.c_int64)]
+
+
+class HeliosError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+def load_library() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2310_00837_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    for name in EXPORTS:
+        getattr(lib, name)                      # raises AttributeError if a symbol is missing
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+    lib.helios_create.argtypes = [C.POINTER(vp), C.c_int, vp]
+    lib.helios_destroy.argtypes = [vp]
+    lib.helios_last_error.argtypes = [vp]
+    lib.helios_last_error.restype = C.c_char_p
+    lib.helios_reserve.argtypes = [vp, i64]
+    lib.helios_sync.argtypes = [vp]
+    lib.helios_csr_load.argtypes = [vp, i64, i64, vp, vp]
+    lib.helios_cache_build.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp]
+    lib.helios_cache_fill.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+    lib.helios_sample.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp]
+    lib.helios_dedup.argtypes = [vp, vp, i64, vp, i64, vp, vp]
+    lib.helios_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, i64, vp]
+    lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp]
+    lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
+                                         vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.helios_set_timing.argtypes = [vp, C.c_int]
+    lib.helios_gather_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    return lib
+
+
+_lib = load_library()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
+    if t.dtype != dtype or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{what}: expected a contiguous {dtype} tensor on the GPU")
+    return t
+
+
+def _dev_accessible(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
+    if t.dtype != dtype or not t.is_contiguous() or not (t.is_cuda or t.is_pinned()):
+        raise TypeError(f"{what}: expected a contiguous {dtype} tensor on the GPU or in pinned host memory")
+    return t
+
+
+@dataclass
+class HopBuffers:
+    """Caller-owned device outputs of one hop."""
+    frontier: torch.Tensor     # int32[frontier_cap]
+    indptr: torch.Tensor       # int64[frontier_cap + 1]
+    flat: torch.Tensor         # int32[flat_cap]
+
+
+def alloc_hops(n_seeds: int, fanouts: Sequence[int], device) -> List[HopBuffers]:
+    """Worst-case buffers: frontier_cap(0) = n_seeds, flat_cap(h) = frontier_cap(h) * fanouts[h]."""
+    hops, cap = [], n_seeds
+    for f in fanouts:
+        fr = torch.empty(max(cap, 1), dtype=torch.int32, device=device)
+        ip = torch.empty(cap + 1, dtype=torch.int64, device=device)
+        cap = cap * f
+        fl = torch.empty(max(cap, 1), dtype=torch.int32, device=device)
+        hops.append(HopBuffers(fr, ip, fl))
+    return hops
+
+
+class Helios:
+    """One library context on one device and stream."""
+
+    def __init__(self, device: int = 0, stream: Optional[torch.cuda.Stream] = None):
+        self._h = C.c_void_p()
+        self._keep = {}
+        s = stream.cuda_stream if stream is not None else torch.cuda.current_stream(device).cuda_stream
+        rc = _lib.helios_create(C.byref(self._h), device, C.c_void_p(s))
+        if rc != OK:
+            self._h = C.c_void_p()
+            raise HeliosError(rc, "helios_create failed")
+        self.device = torch.device("cuda", device)
+        self.row_bytes = 0
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.helios_destroy(self._h)
+            self._h = C.c_void_p()
+            self._keep.clear()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int) -> None:
+        if rc != OK:
+            raise HeliosError(rc, _lib.helios_last_error(self._h).decode())
+
+    # ---- plumbing
+    def reserve(self, max_ids: int) -> None:
+        self._check(_lib.helios_reserve(self._h, max_ids))
+
+    def sync(self) -> None:
+        self._check(_lib.helios_sync(self._h))
+
+    def set_timing(self, enabled: bool) -> None:
+        self._check(_lib.helios_set_timing(self._h, int(enabled)))
+
+    def gather_times(self):
+        a, b = C.c_float(), C.c_float()
+        self._check(_lib.helios_gather_times(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    # ---- S0
+    def csr_load(self, offsets: torch.Tensor, indices: torch.Tensor) -> None:
+        _dev_accessible(offsets, torch.int64, "offsets")
+        _dev_accessible(indices, torch.int32, "indices")
+        self._keep["csr"] = (offsets, indices)
+        self.n_nodes = offsets.numel() - 1
+        self._check(_lib.helios_csr_load(self._h, self.n_nodes, indices.numel(), _ptr(offsets), _ptr(indices)))
+
+    def cache_build(self, order: torch.Tensor, hbm_rows: int, host_rows: int, row_bytes: int,
+                    hbm_table: Optional[torch.Tensor], host_table: Optional[torch.Tensor],
+                    standin_table: Optional[torch.Tensor]) -> None:
+        _dev(order, torch.int32, "order")
+        if hbm_table is not None and not hbm_table.is_cuda:
+            raise TypeError("hbm_table must be on the GPU")
+        for t, w in ((host_table, "host_table"), (standin_table, "standin_table")):
+            if t is not None and not (t.is_pinned() or t.is_cuda):
+                raise TypeError(f"{w} must be pinned host memory")
+        self._keep["cache"] = (order, hbm_table, host_table, standin_table)
+        self.row_bytes = row_bytes
+        self._check(_lib.helios_cache_build(self._h, _ptr(order), hbm_rows, host_rows, row_bytes, _ptr(hbm_table),
+                                            _ptr(host_table), _ptr(standin_table)))
+
+    def cache_fill(self, src_table: torch.Tensor, order: torch.Tensor, first_rank: int, n_rows: int,
+                   dst: torch.Tensor) -> None:
+        row_bytes = src_table.shape[1] * src_table.element_size()
+        assert dst.shape[1] * dst.element_size() == row_bytes and dst.shape[0] >= n_rows
+        assert first_rank + n_rows <= order.numel()
+        _dev(order, torch.int32, "order")
+        self._check(_lib.helios_cache_fill(self._h, _ptr(src_table), _ptr(order), first_rank, n_rows, row_bytes,
+                                           _ptr(dst)))
+
+    # ---- S1
+    def _hop_array(self, hops: Sequence[HopBuffers]):
+        arr = (HopOut * len(hops))()
+        for i, h in enumerate(hops):
+            _dev(h.frontier, torch.int32, "frontier"), _dev(h.indptr, torch.int64, "indptr"), _dev(h.flat, torch.int32, "flat")
+            arr[i] = HopOut(h.frontier.data_ptr(), min(h.frontier.numel(), h.indptr.numel() - 1), h.indptr.data_ptr(),
+                            h.flat.data_ptr(), h.flat.numel())
+        return arr
+
+    def sample(self, seeds: torch.Tensor, fanouts: Sequence[int], rng_seed: int, hops: Sequence[HopBuffers],
+               sizes: torch.Tensor) -> None:
+        _dev(seeds, torch.int32, "seeds")
+        _dev_accessible(sizes, torch.int64, "sizes")
+        assert sizes.numel() >= 2 * len(fanouts) and len(hops) == len(fanouts)
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        self._check(_lib.helios_sample(self._h, _ptr(seeds), seeds.numel(), fan, len(fanouts),
+                                       C.c_uint64(rng_seed), self._hop_array(hops), _ptr(sizes)))
+
+    # ---- S2
+    def dedup(self, ids: torch.Tensor, unique: torch.Tensor, inverse: Optional[torch.Tensor],
+              n_unique: torch.Tensor, n_ids: Optional[int] = None) -> None:
+        _dev(ids, torch.int32, "ids"), _dev(unique, torch.int32, "unique")
+        _dev_accessible(n_unique, torch.int64, "n_unique")
+        n = ids.numel() if n_ids is None else n_ids
+        if inverse is not None:
+            _dev(inverse, torch.int32, "inverse")
+            assert inverse.numel() >= n
+        self._check(_lib.helios_dedup(self._h, _ptr(ids), n, _ptr(unique), unique.numel(), _ptr(inverse),
+                                      _ptr(n_unique)))
+
+    # ---- S3 + S4 + S5
+    def gather(self, ids: torch.Tensor, out: torch.Tensor, miss_pos: torch.Tensor, miss_id: torch.Tensor,
+               miss_slot: torch.Tensor, stats: torch.Tensor, n_ids: Optional[int] = None) -> None:
+        _dev(ids, torch.int32, "ids")
+        n = ids.numel() if n_ids is None else n_ids
+        if not out.is_cuda or not out.is_contiguous() or out.numel() * out.element_size() < n * self.row_bytes:
+            raise TypeError("out must be a contiguous GPU tensor of n_ids x row_bytes")
+        for t in (miss_pos, miss_id, miss_slot):
+            _dev(t, torch.int32, "miss list")
+        _dev_accessible(stats, torch.int64, "stats")
+        assert stats.numel() >= 4
+        cap = min(miss_pos.numel(), miss_id.numel(), miss_slot.numel())
+        self._check(_lib.helios_gather(self._h, _ptr(ids), n, _ptr(out), _ptr(miss_pos), _ptr(miss_id),
+                                       _ptr(miss_slot), cap, _ptr(stats)))
+
+    # ---- S6
+    def gather_miss(self, miss_pos: torch.Tensor, miss_slot: torch.Tensor, n_miss_max: int,
+                    n_miss_dev: Optional[torch.Tensor], out: torch.Tensor) -> None:
+        _dev(miss_pos, torch.int32, "miss_pos"), _dev(miss_slot, torch.int32, "miss_slot")
+        assert n_miss_max <= min(miss_pos.numel(), miss_slot.numel())
+        if n_miss_dev is not None:
+            _dev_accessible(n_miss_dev, torch.int64, "n_miss_dev")
+        self._check(_lib.helios_gather_miss(self._h, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev),
+                                            _ptr(out)))
+
+    # ---- whole path
+    def prepare_batch(self, seeds: torch.Tensor, fanouts: Sequence[int], rng_seed: int, hops: Sequence[HopBuffers],
+                      sizes: torch.Tensor, unique: torch.Tensor, inverse: Optional[torch.Tensor],
+                      n_unique: torch.Tensor, out: torch.Tensor, miss_pos: torch.Tensor, miss_id: torch.Tensor,
+                      miss_slot: torch.Tensor, stats: torch.Tensor) -> None:
+        _dev(seeds, torch.int32, "seeds"), _dev(unique, torch.int32, "unique")
+        _dev_accessible(sizes, torch.int64, "sizes"), _dev_accessible(n_unique, torch.int64, "n_unique")
+        _dev_accessible(stats, torch.int64, "stats")
+        if inverse is not None:
+            _dev(inverse, torch.int32, "inverse")
+            assert inverse.numel() >= seeds.numel() + sum(h.flat.numel() for h in hops)
+        if not out.is_cuda or out.numel() * out.element_size() < unique.numel() * self.row_bytes:
+            raise TypeError("out must be a GPU tensor with room for unique_cap rows")
+        cap = min(miss_pos.numel(), miss_id.numel(), miss_slot.numel())
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        self._check(_lib.helios_prepare_batch(
+            self._h, _ptr(seeds), seeds.numel(), fan, len(fanouts), C.c_uint64(rng_seed), self._hop_array(hops),
+            _ptr(sizes), _ptr(unique), unique.numel(), _ptr(inverse), _ptr(n_unique), _ptr(out), _ptr(miss_pos),
+            _ptr(miss_id), _ptr(miss_slot), cap, _ptr(stats)))

@@ -1,0 +1,107 @@
+"""Shared helpers of the GPU parity tests: run the path through the C ABI (via the thin
+binding) and through the CPU oracle on the same inputs, and compare every output array."""
+import numpy as np
+import torch
+
+SENTINEL = 0xA5
+
+
+def to_bytes(t: torch.Tensor) -> np.ndarray:
+    """[rows, dim] tensor of any dtype -> numpy uint8 [rows, row_bytes] (host copy)."""
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.uint8).reshape(t.shape[0], -1).numpy() if t.numel() else \
+        np.zeros((0, t.shape[1] * t.element_size()), np.uint8)
+
+
+class GpuCache:
+    """Tier tables of a small workload, built from a full feature table through helios_cache_fill."""
+
+    def __init__(self, h, feats: torch.Tensor, order: torch.Tensor, n_hbm: int, n_host: int):
+        n, dim = feats.shape
+        self.row_bytes = dim * feats.element_size()
+        dev = h.device
+        self.order = order.to(dev)
+        src = feats.to(dev)
+        n_rest = n - n_hbm - n_host
+        self.hbm = torch.empty((max(n_hbm, 1), dim), dtype=feats.dtype, device=dev)
+        self.host = torch.empty((max(n_host, 1), dim), dtype=feats.dtype).pin_memory()
+        self.standin = torch.empty((max(n_rest, 1), dim), dtype=feats.dtype).pin_memory()
+        h.cache_fill(src, self.order, 0, n_hbm, self.hbm)
+        h.cache_fill(src, self.order, n_hbm, n_host, self.host)
+        h.cache_fill(src, self.order, n_hbm + n_host, n_rest, self.standin)
+        h.sync()
+        self.n_hbm, self.n_host, self.n_rest = n_hbm, n_host, n_rest
+        h.cache_build(self.order, n_hbm, n_host, self.row_bytes, self.hbm, self.host, self.standin)
+        h.sync()
+
+
+def gpu_path(h, helios, seeds: torch.Tensor, fanouts, rng_seed: int, fused: bool, serve_misses: bool = True):
+    """Returns a dict of numpy arrays with every output of the path."""
+    dev = h.device
+    seeds = seeds.to(dev)
+    B = seeds.numel()
+    hops = helios.alloc_hops(B, fanouts, dev)
+    K = len(fanouts)
+    cat_cap = B + sum(hb.flat.numel() for hb in hops)
+    sizes = torch.zeros(2 * K, dtype=torch.int64).pin_memory()
+    n_unique = torch.zeros(1, dtype=torch.int64).pin_memory()
+    stats = torch.zeros(4, dtype=torch.int64).pin_memory()
+    unique = torch.empty(max(cat_cap, 1), dtype=torch.int32, device=dev)
+    inverse = torch.empty(max(cat_cap, 1), dtype=torch.int32, device=dev)
+    out = torch.full((max(cat_cap, 1), h.row_bytes), SENTINEL, dtype=torch.uint8, device=dev)
+    mp = torch.empty(max(cat_cap, 1), dtype=torch.int32, device=dev)
+    mi = torch.empty_like(mp)
+    ms = torch.empty_like(mp)
+    if fused:
+        h.prepare_batch(seeds, fanouts, rng_seed, hops, sizes, unique, inverse, n_unique, out, mp, mi, ms, stats)
+        h.sync()
+    else:
+        h.sample(seeds, fanouts, rng_seed, hops, sizes)
+        h.sync()
+        parts = [seeds] + [hops[k].flat[:int(sizes[2 * k + 1])] for k in range(K)]
+        cat = torch.cat(parts)
+        h.dedup(cat, unique, inverse, n_unique)
+        h.sync()
+        h.gather(unique, out, mp, mi, ms, stats, n_ids=int(n_unique[0]))
+        h.sync()
+    res = {"hops": []}
+    for k in range(K):
+        nf, nfl = int(sizes[2 * k]), int(sizes[2 * k + 1])
+        res["hops"].append((hops[k].frontier[:nf].cpu().numpy(), hops[k].indptr[:nf + 1].cpu().numpy(),
+                            hops[k].flat[:nfl].cpu().numpy()))
+    U = int(n_unique[0])
+    n_cat = B + sum(int(sizes[2 * k + 1]) for k in range(K))
+    nm = int(stats[3])
+    res.update(unique=unique[:U].cpu().numpy(), inverse=inverse[:n_cat].cpu().numpy(), stats=stats.numpy().copy(),
+               miss_pos=mp[:nm].cpu().numpy(), miss_id=mi[:nm].cpu().numpy(), miss_slot=ms[:nm].cpu().numpy(),
+               out_before_miss=out[:U].cpu().numpy())
+    if serve_misses:
+        h.gather_miss(mp, ms, mp.numel(), stats[3:4], out)
+        h.sync()
+        res["out"] = out[:U].cpu().numpy()
+    return res
+
+
+def oracle_path(oracle, off, idx, seeds, fanouts, rng_seed, rank, n_hbm, n_host, hbm_tab, host_tab, standin_tab,
+                row_bytes):
+    hops = oracle.sample(off, idx, seeds, fanouts, rng_seed)
+    cat = np.concatenate([np.asarray(seeds, np.int32)] + [fl for _, _, fl in hops])
+    uniq, inv = oracle.dedup(off.size - 1, cat)
+    out = np.full((uniq.size, row_bytes), SENTINEL, np.uint8)
+    mp, mi, ms, stats = oracle.gather(uniq, rank, n_hbm, n_host, hbm_tab, host_tab, out)
+    before = out.copy()
+    oracle.gather_miss(mp, ms, standin_tab, out)
+    return dict(hops=hops, unique=uniq, inverse=inv, stats=stats, miss_pos=mp, miss_id=mi, miss_slot=ms,
+                out_before_miss=before, out=out)
+
+
+def assert_same(got, want):
+    assert len(got["hops"]) == len(want["hops"])
+    for k, (g, w) in enumerate(zip(got["hops"], want["hops"])):
+        for name, a, b in zip(("frontier", "indptr", "flat"), g, w):
+            assert a.shape == b.shape, f"hop {k} {name}: {a.shape} vs {b.shape}"
+            assert np.array_equal(a, b), f"hop {k} {name} differs"
+    for key in ("unique", "inverse", "stats", "miss_pos", "miss_id", "miss_slot", "out_before_miss", "out"):
+        if key in got and key in want:
+            assert got[key].shape == want[key].shape, f"{key}: {got[key].shape} vs {want[key].shape}"
+            assert np.array_equal(got[key], want[key]), f"{key} differs"

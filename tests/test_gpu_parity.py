@@ -1,0 +1,254 @@
+"""GPU parity: every output of the HIP path, called through the C ABI, equals the CPU oracle's
+bit for bit (the path is integer indexing and byte copies; the tolerance is zero)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2310_00837_amd import workload as W
+from pathlib_helios import GpuCache, assert_same, gpu_path, oracle_path, to_bytes, SENTINEL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def helios():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2310_00837_amd import helios as hl
+    return hl
+
+
+@pytest.fixture()
+def h(helios):
+    ctx = helios.Helios(0)
+    yield ctx
+    ctx.close()
+
+
+def _random_graph(rng, n, max_deg, hub_deg=0):
+    deg = rng.integers(0, max_deg + 1, n)
+    deg[rng.integers(0, n, max(1, n // 8))] = 0
+    if hub_deg:
+        deg[rng.integers(0, n, 3)] = hub_deg
+    offsets = np.zeros(n + 1, np.int64)
+    offsets[1:] = np.cumsum(deg)
+    rows = [np.sort(rng.choice(n, int(d), replace=False)).astype(np.int32) for d in deg]
+    return offsets, np.concatenate(rows).astype(np.int32)
+
+
+# ------------------------------------------------------------------ sampling
+@pytest.mark.parametrize("fanouts", [[3], [5, 5], [8, 9], [16, 17, 2], [25, 10], [33], [64, 2], [65], [200, 3], [0, 4], [4, 0]])
+def test_sample_parity_random_graph(h, helios, oracle, fanouts):
+    print("fanouts", fanouts, flush=True)
+    rng = np.random.default_rng(sum(fanouts) + len(fanouts))
+    n = 3000
+    off, idx = _random_graph(rng, n, 40, hub_deg=700)
+    h.csr_load(torch.from_numpy(off).cuda(), torch.from_numpy(idx).cuda())
+    seeds = rng.integers(0, n, 700).astype(np.int32)            # duplicates, several tiles, ragged tail
+    for rs in (1, 0xFFFFFFFFFFFFFFFF, 0x123456789ABCDEF0):
+        hops = helios.alloc_hops(seeds.size, fanouts, h.device)
+        sizes = torch.zeros(2 * len(fanouts), dtype=torch.int64).pin_memory()
+        h.sample(torch.from_numpy(seeds).cuda(), fanouts, rs, hops, sizes)
+        h.sync()
+        want = oracle.sample(off, idx, seeds, fanouts, rs)
+        for k, (fr, ip, fl) in enumerate(want):
+            assert int(sizes[2 * k]) == fr.size and int(sizes[2 * k + 1]) == fl.size
+            assert np.array_equal(hops[k].frontier[:fr.size].cpu().numpy(), fr)
+            assert np.array_equal(hops[k].indptr[:fr.size + 1].cpu().numpy(), ip)
+            assert np.array_equal(hops[k].flat[:fl.size].cpu().numpy(), fl)
+
+
+def test_sample_edge_cases(h, helios, oracle):
+    # star + isolated nodes; degree == fanout, degree == fanout + 1, empty seed list
+    off = np.array([0, 5, 6, 7, 8, 9, 10, 10, 16], np.int64)
+    idx = np.array([1, 2, 3, 4, 5, 0, 0, 0, 0, 0, 0, 1, 2, 3, 4, 5], np.int32)
+    h.csr_load(torch.from_numpy(off).cuda(), torch.from_numpy(idx).cuda())
+    for seeds, fanouts in [([0], [5]), ([0], [4]), ([7, 7, 0, 6], [5, 5]), ([6], [3, 3]), ([], [3, 2]), ([7], [6]), ([7], [1, 1, 1])]:
+        print("edge", seeds, fanouts, flush=True)
+        s = np.array(seeds, np.int32)
+        hops = helios.alloc_hops(s.size, fanouts, h.device)
+        sizes = torch.full((2 * len(fanouts),), -7, dtype=torch.int64).pin_memory()
+        h.sample(torch.from_numpy(s).cuda(), fanouts, 42, hops, sizes)
+        h.sync()
+        want = oracle.sample(off, idx, s, fanouts, 42)
+        for k, (fr, ip, fl) in enumerate(want):
+            assert [int(sizes[2 * k]), int(sizes[2 * k + 1])] == [fr.size, fl.size]
+            assert np.array_equal(hops[k].frontier[:fr.size].cpu().numpy(), fr)
+            assert np.array_equal(hops[k].indptr[:fr.size + 1].cpu().numpy(), ip)
+            assert np.array_equal(hops[k].flat[:fl.size].cpu().numpy(), fl)
+
+
+# ------------------------------------------------------------------ dedup
+@pytest.mark.parametrize("n_ids,hi", [(0, 10), (1, 10), (255, 40), (256, 1000), (257, 50), (5000, 300), (100_000, 20_000),
+                                      (300_000, 2_000_000), (70_000, 3)])
+def test_dedup_parity(h, oracle, n_ids, hi):
+    print("dedup", n_ids, hi, flush=True)
+    rng = np.random.default_rng(n_ids + hi)
+    n_nodes = max(hi, 1)
+    off = torch.zeros(n_nodes + 1, dtype=torch.int64, device="cuda")
+    h.csr_load(off, torch.zeros(1, dtype=torch.int32, device="cuda"))
+    ids = rng.integers(0, hi, n_ids).astype(np.int32)
+    # a power-law mix: many repeats of a few hot IDs, as sampled hubs are
+    if n_ids > 1000:
+        hot = rng.integers(0, hi, 5).astype(np.int32)
+        where = rng.random(n_ids) < 0.3
+        ids[where] = hot[rng.integers(0, 5, int(where.sum()))]
+    t = torch.from_numpy(ids).cuda()
+    uniq = torch.full((max(n_ids, 1),), -9, dtype=torch.int32, device="cuda")
+    inv = torch.full((max(n_ids, 1),), -9, dtype=torch.int32, device="cuda")
+    nu = torch.full((1,), -9, dtype=torch.int64).pin_memory()
+    for _ in range(2):                                        # the table is reused by the second call
+        h.dedup(t, uniq, inv, nu, n_ids=n_ids)
+        h.sync()
+        wu, wi = oracle.dedup(n_nodes, ids)
+        assert int(nu[0]) == wu.size
+        assert np.array_equal(uniq[:wu.size].cpu().numpy(), wu)
+        assert np.array_equal(inv[:n_ids].cpu().numpy(), wi)
+    h.dedup(t, uniq, None, nu, n_ids=n_ids)                    # inverse is optional
+    h.sync()
+    assert int(nu[0]) == wu.size
+
+
+# ------------------------------------------------------------------ lookup + gather + miss list
+@pytest.mark.parametrize("row_bytes", [16, 48, 256, 512, 1024, 2048, 4096, 4112])
+@pytest.mark.parametrize("tiers", [(0.1, 0.2), (0.0, 0.5), (1.0, 0.0), (0.0, 0.0), (0.0, 1.0)])
+def test_gather_parity(h, oracle, row_bytes, tiers):
+    print("gather", row_bytes, tiers, flush=True)
+    rng = np.random.default_rng(row_bytes)
+    n = 5000
+    n_hbm, n_host = int(tiers[0] * n), int(tiers[1] * n)
+    feats = torch.from_numpy(rng.integers(0, 256, (n, row_bytes), dtype=np.uint8))
+    order = torch.from_numpy(rng.permutation(n).astype(np.int32))
+    h.csr_load(torch.zeros(n + 1, dtype=torch.int64, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"))
+    cache = GpuCache(h, feats, order, n_hbm, n_host)
+    by_rank = feats.numpy()[order.numpy()]
+    assert np.array_equal(cache.hbm[:n_hbm].cpu().numpy(), by_rank[:n_hbm])
+    assert np.array_equal(cache.host[:n_host].numpy(), by_rank[n_hbm:n_hbm + n_host])
+    assert np.array_equal(cache.standin[:cache.n_rest].numpy(), by_rank[n_hbm + n_host:])
+    rank = oracle.rank_build(order.numpy())
+    for n_ids in (0, 1, 777, 4100):
+        ids = rng.integers(0, n, n_ids).astype(np.int32)         # duplicates allowed
+        out = torch.full((max(n_ids, 1), row_bytes), SENTINEL, dtype=torch.uint8, device="cuda")
+        mp = torch.full((max(n_ids, 1),), -9, dtype=torch.int32, device="cuda")
+        mi, ms = mp.clone(), mp.clone()
+        stats = torch.full((4,), -9, dtype=torch.int64).pin_memory()
+        h.gather(torch.from_numpy(ids).cuda(), out, mp, mi, ms, stats, n_ids=n_ids)
+        h.sync()
+        wout = np.full((n_ids, row_bytes), SENTINEL, np.uint8)
+        wmp, wmi, wms, wstats = oracle.gather(ids, rank, n_hbm, n_host, np.ascontiguousarray(by_rank[:n_hbm]),
+                                              np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]), wout)
+        assert stats.tolist() == wstats.tolist()
+        nm = int(wstats[3])
+        assert np.array_equal(mp[:nm].cpu().numpy(), wmp) and np.array_equal(mi[:nm].cpu().numpy(), wmi)
+        assert np.array_equal(ms[:nm].cpu().numpy(), wms)
+        assert np.array_equal(out[:n_ids].cpu().numpy(), wout)         # hit rows copied, miss rows untouched
+        h.gather_miss(mp, ms, nm, None, out)
+        h.sync()
+        assert np.array_equal(out[:n_ids].cpu().numpy(), feats.numpy()[ids])
+
+
+# ------------------------------------------------------------------ whole path on the small workloads
+@pytest.fixture(scope="module")
+def workloads():
+    made = {}
+
+    def get(cfg):
+        if cfg not in made:
+            sp = W.spec(cfg)
+            g = W.make_graph(sp, 1234, "cpu")
+            feats = W.feature_rows(1234, torch.arange(g.n_nodes), sp.dim, sp.dtype)
+            made[cfg] = (sp, g, feats)
+        return made[cfg]
+    return get
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_whole_path_parity(h, helios, oracle, workloads, cfg):
+    sp, g, feats = workloads(cfg)
+    print("workload", sp.name, "N", g.n_nodes, "E", g.n_edges, flush=True)
+    n_hbm, n_host, n_rest = sp.tier_rows(g.n_nodes)
+    h.csr_load(g.offsets.cuda(), g.indices.cuda())
+    cache = GpuCache(h, feats, g.order, n_hbm, n_host)
+    off, idx, order = g.offsets.numpy(), g.indices.numpy(), g.order.numpy()
+    rank = oracle.rank_build(order)
+    by_rank = to_bytes(feats)[order]
+    tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
+            np.ascontiguousarray(by_rank[n_hbm + n_host:])]
+    for b in range(3):
+        seeds = W.seed_batch(sp, g, b)
+        rs = W.batch_rng_seed(1234, b)
+        want = oracle_path(oracle, off, idx, seeds.numpy(), sp.fanouts, rs, rank, n_hbm, n_host, *tabs, sp.row_bytes)
+        fused = gpu_path(h, helios, seeds, sp.fanouts, rs, fused=True)
+        assert_same(fused, want)
+        steps = gpu_path(h, helios, seeds, sp.fanouts, rs, fused=False)
+        assert_same(steps, want)
+        again = gpu_path(h, helios, seeds, sp.fanouts, rs, fused=True)     # run-twice determinism
+        assert_same(again, fused)
+        print(" batch", b, "unique", want["unique"].size, "stats", want["stats"].tolist(), flush=True)
+    # Zipf seeds (duplicates in the seed list) on the same graph
+    z = W.spec(4)
+    z.batch = sp.batch
+    seeds = W.seed_batch(z, g, 0)
+    want = oracle_path(oracle, off, idx, seeds.numpy(), sp.fanouts, 99, rank, n_hbm, n_host, *tabs, sp.row_bytes)
+    assert_same(gpu_path(h, helios, seeds, sp.fanouts, 99, fused=True), want)
+
+
+# ------------------------------------------------------------------ error behaviour
+def test_errors(h, helios):
+    HE = helios.HeliosError
+    seeds = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    hops = helios.alloc_hops(2, [2], h.device)
+    sizes = torch.zeros(2, dtype=torch.int64).pin_memory()
+    with pytest.raises(HE) as e:
+        h.sample(seeds, [2], 1, hops, sizes)                         # no graph yet
+    assert e.value.code == helios.ESTATE
+    off = torch.tensor([0, 3, 3, 6], dtype=torch.int64, device="cuda")
+    idx = torch.tensor([1, 2, 0, 0, 1, 2], dtype=torch.int32, device="cuda")
+    h.csr_load(off, idx)
+    with pytest.raises(HE) as e:
+        h.gather(seeds, torch.zeros(2, 16, dtype=torch.uint8, device="cuda"), seeds, seeds, seeds,
+                 torch.zeros(4, dtype=torch.int64).pin_memory())
+    assert e.value.code == helios.ESTATE
+    with pytest.raises(HE) as e:
+        h.sample(seeds, [helios.MAX_FANOUT + 1], 1, hops, sizes)
+    assert e.value.code == helios.EINVAL
+    with pytest.raises(HE) as e:
+        h.cache_build(torch.arange(3, dtype=torch.int32, device="cuda"), 1, 1, 24, off, None, None)   # row_bytes % 16
+    assert e.value.code == helios.EINVAL
+    # a seed that is not a node: reported by the next sync, and the context keeps working
+    bad = torch.tensor([0, 3], dtype=torch.int32, device="cuda")
+    h.sample(bad, [2], 1, hops, sizes)
+    with pytest.raises(HE) as e:
+        h.sync()
+    assert e.value.code == helios.EDATA
+    h.sample(seeds, [2], 1, hops, sizes)
+    h.sync()
+    assert sizes.tolist() == [2, 2]
+    # sample list larger than its buffer: nothing written past it, required size reported
+    small = [helios.HopBuffers(hops[0].frontier, hops[0].indptr, torch.full((3,), -5, dtype=torch.int32, device="cuda"))]
+    both = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
+    guard = small[0].flat
+    h.sample(both, [3], 1, small, sizes)
+    with pytest.raises(HE) as e:
+        h.sync()
+    assert e.value.code == helios.ECAPACITY and sizes.tolist() == [2, 6]
+    assert guard.cpu().tolist() == [1, 2, 0]
+    # an order that repeats a node is not a permutation
+    h.cache_build(torch.tensor([0, 1, 1], dtype=torch.int32, device="cuda"), 1, 1, 16,
+                  torch.zeros(16, dtype=torch.uint8, device="cuda"), torch.zeros(16, dtype=torch.uint8).pin_memory(), None)
+    with pytest.raises(HE) as e:
+        h.sync()
+    assert e.value.code == helios.EDATA
+    # miss list too small
+    h.cache_build(torch.tensor([2, 0, 1], dtype=torch.int32, device="cuda"), 1, 0, 16,
+                  torch.zeros(16, dtype=torch.uint8, device="cuda"), None, None)
+    h.sync()
+    ids = torch.tensor([0, 1, 2, 0, 1], dtype=torch.int32, device="cuda")
+    out = torch.zeros(5, 16, dtype=torch.uint8, device="cuda")
+    m = torch.full((2,), -5, dtype=torch.int32, device="cuda")
+    stats = torch.zeros(4, dtype=torch.int64).pin_memory()
+    h.gather(ids, out, m, m.clone(), m.clone(), stats)
+    with pytest.raises(HE) as e:
+        h.sync()
+    assert e.value.code == helios.ECAPACITY and stats.tolist() == [5, 1, 0, 4]
+    assert m.cpu().tolist() == [0, 1]
