@@ -1,0 +1,222 @@
+"""Benchmark of the Helios mini-batch preparation path on one MI355X.
+
+A step is one pass of the whole path (k-hop sampling, de-duplication, cache lookup, gather of
+both cached tiers, miss list: helios_prepare_batch + helios_sync) over one batch of seeds of a
+synthetic workload whose graph, feature tables and seeds are resident before the timed region
+(graph, cache map and HBM tier in HBM; host tier and storage stand-in in pinned host memory,
+where the method keeps them).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--hbm-frac P]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def log(msg: str) -> None:
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def measure_host_link(torch, gib: float = 1.0) -> float:
+    """Pinned host -> device copy rate in GB/s (best of 5), the denominator of the host-tier gather."""
+    n = int(gib * (1 << 30))
+    src = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    src.fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    best = 0.0
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dst.copy_(src, non_blocking=True)
+        e1.record()
+        e1.synchronize()
+        best = max(best, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    return best
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload index in BASELINE.json configs (0-based)")
+    ap.add_argument("--hbm-frac", type=float, default=None, help="config 4 only: HBM-tier fraction of the sweep")
+    ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; the path shards by giving each GPU its own "
+              "mini-batches, which needs no code here. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2310_00837_amd import helios, workload as W
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    sp = W.spec(args.config, args.hbm_frac)
+    K, Wm = args.steps, args.warmup
+
+    # ---------------- inputs (untimed)
+    t0 = time.time()
+    gen_dev = dev if sp.n_nodes > 5_000_000 else "cpu"
+    g = W.make_graph(sp, args.seed, gen_dev, progress=log if sp.n_nodes > 5_000_000 else None)
+    log(f"{sp.name}: N={g.n_nodes} E={g.n_edges} generated on {gen_dev} in {time.time() - t0:.1f}s")
+    offsets, indices, order = g.offsets.to(dev), g.indices.to(dev), g.order.to(dev)
+    g.offsets, g.indices, g.order, g.perm_seed = offsets, indices, order, g.perm_seed.to(dev)
+    t1 = time.time()
+    tiers = W.make_tiers(sp, g, dev, progress=log if sp.n_nodes > 5_000_000 else None)
+    log(f"tiers: hbm {tiers.n_hbm} host {tiers.n_host} stand-in {tiers.n_rest} rows x {sp.row_bytes} B "
+        f"filled in {time.time() - t1:.1f}s")
+    link_gbs = measure_host_link(torch)
+    log(f"host link (pinned H2D copy): {link_gbs:.1f} GB/s")
+
+    h = helios.Helios(0)
+    h.csr_load(offsets, indices)
+    h.cache_build(order, tiers.n_hbm, tiers.n_host, sp.row_bytes, tiers.hbm, tiers.host, tiers.standin)
+    h.sync()
+
+    B = min(sp.batch, g.n_nodes)
+    hops = helios.alloc_hops(B, sp.fanouts, dev)
+    cat_cap = B + sum(hb.flat.numel() for hb in hops)
+    h.reserve(cat_cap)
+    unique = torch.empty(cat_cap, dtype=torch.int32, device=dev)
+    inverse = torch.empty(cat_cap, dtype=torch.int32, device=dev)
+    out = torch.empty((cat_cap, sp.row_bytes), dtype=torch.uint8, device=dev)
+    mp = torch.empty(cat_cap, dtype=torch.int32, device=dev)
+    mi, ms = torch.empty_like(mp), torch.empty_like(mp)
+    sizes = torch.zeros(2 * len(sp.fanouts), dtype=torch.int64).pin_memory()
+    n_unique = torch.zeros(1, dtype=torch.int64).pin_memory()
+    stats = torch.zeros(4, dtype=torch.int64).pin_memory()
+    n_batches = K + Wm
+    seeds = [W.seed_batch(sp, g, b).to(dev) for b in range(n_batches)]
+    rng_seeds = [W.batch_rng_seed(args.seed, b) for b in range(n_batches)]
+
+    def step(b: int, serve_misses: bool) -> None:
+        h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], hops, sizes, unique, inverse, n_unique, out, mp, mi, ms,
+                        stats)
+        if serve_misses:
+            h.gather_miss(mp, ms, mp.numel(), stats[3:4], out)
+        h.sync()
+
+    # ---------------- timed region: K steps, S1-S5, gather kernels bracketed by HIP events
+    h.set_timing(True)
+    for b in range(Wm):
+        step(b, False)
+    acc = dict(hbm_ms=0.0, host_ms=0.0, hbm_ev_ms=0.0, host_ev_ms=0.0, hbm_rows=0, host_rows=0, miss=0, unique=0, raw=0)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for b in range(Wm, Wm + K):
+        step(b, False)
+        a_ms, b_ms, a_ev, b_ev = h.gather_times()
+        acc["hbm_ms"] += a_ms
+        acc["host_ms"] += b_ms
+        acc["hbm_ev_ms"] += a_ev
+        acc["host_ev_ms"] += b_ev
+        acc["hbm_rows"] += int(stats[1])
+        acc["host_rows"] += int(stats[2])
+        acc["miss"] += int(stats[3])
+        acc["unique"] += int(stats[0])
+        acc["raw"] += int(sizes[1::2].sum())
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    h.set_timing(False)
+
+    # same K steps once more with the miss list served from the stand-in (reported, not `value`)
+    torch.cuda.synchronize()
+    t_s6 = time.perf_counter()
+    for b in range(Wm, Wm + K):
+        step(b, True)
+    torch.cuda.synchronize()
+    elapsed_s6 = time.perf_counter() - t_s6
+
+    rb = sp.row_bytes
+    hbm_bytes = 2.0 * acc["hbm_rows"] * rb                 # every row is read from HBM and written to HBM
+    host_bytes = 1.0 * acc["host_rows"] * rb               # bytes that cross the host link
+    hbm_gbs = hbm_bytes / (acc["hbm_ms"] * 1e-3) / 1e9 if acc["hbm_ms"] > 0 else 0.0
+    host_gbs = host_bytes / (acc["host_ms"] * 1e-3) / 1e9 if acc["host_ms"] > 0 else 0.0
+    dominant_host = acc["host_ms"] > acc["hbm_ms"]
+
+    result = {
+        "metric": "sampled mini-batches/sec; feature gather GB/s vs HBM and host-link peak",
+        "value": K / elapsed,
+        "unit": "mini-batches/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": elapsed / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 ids / byte rows (" + ("fp32" if sp.dtype == torch.float32 else "fp16") + " features)",
+        "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{args.config}] {sp.name}", "n_nodes": g.n_nodes,
+                   "n_edges": g.n_edges, "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
+                   "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed,
+                   "step": "helios_prepare_batch (sample, dedup, lookup, HBM+host gather, miss list) + helios_sync"},
+        "roofline": {"kernel": "gather_rows_kernel (HBM tier)", "bound": "hbm", "achieved": hbm_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "avg_kernel_us": acc["hbm_ms"] / K * 1e3, "avg_event_us": acc["hbm_ev_ms"] / K * 1e3,
+                     "timer": "device clock, earliest workgroup start to latest end", "rows_per_launch": acc["hbm_rows"] / K,
+                     "bytes_per_row": 2 * rb},
+        "roofline_host_link": {"kernel": "gather_rows_kernel (host tier)", "bound": "host_link",
+                               "achieved": host_gbs, "peak": link_gbs, "unit": "GB/s",
+                               "frac": host_gbs / link_gbs if link_gbs > 0 else None,
+                               "peak_source": "pinned H2D copy measured in this run",
+                               "avg_kernel_us": acc["host_ms"] / K * 1e3, "avg_event_us": acc["host_ev_ms"] / K * 1e3,
+                               "rows_per_launch": acc["host_rows"] / K,
+                               "bytes_per_row": rb},
+        "dominant_kernel": "host-tier gather" if dominant_host else "HBM-tier gather",
+        "with_miss_service": {"value": K / elapsed_s6, "ms_per_step": elapsed_s6 / K * 1e3},
+        "per_batch": {"raw_sampled_ids": acc["raw"] / K, "unique_ids": acc["unique"] / K,
+                      "hit_ratio_hbm": acc["hbm_rows"] / max(acc["unique"], 1),
+                      "hit_ratio_host": acc["host_rows"] / max(acc["unique"], 1),
+                      "miss_ratio": acc["miss"] / max(acc["unique"], 1)},
+    }
+
+    # ---------------- CPU oracle on the same batches (reported baseline) + parity of one batch
+    if not args.no_cpu:
+        from oracle import helios_oracle as oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from pathlib_helios import assert_same, gpu_path, oracle_path, to_bytes
+        off_h, idx_h, ord_h = offsets.cpu().numpy(), indices.cpu().numpy(), order.cpu().numpy()
+        rank_h = oracle.rank_build(ord_h)
+        tabs = [to_bytes(tiers.hbm[:tiers.n_hbm]), to_bytes(tiers.host[:tiers.n_host]),
+                to_bytes(tiers.standin[:tiers.n_rest])]
+        log("CPU oracle leg: host copies ready")
+        b0 = Wm
+        want = oracle_path(oracle, off_h, idx_h, seeds[b0].cpu().numpy(), sp.fanouts, rng_seeds[b0], rank_h,
+                           tiers.n_hbm, tiers.n_host, *tabs, rb)
+        got = gpu_path(h, helios, seeds[b0], sp.fanouts, rng_seeds[b0], fused=True)
+        assert_same(got, want)
+        result["parity"] = "bit-exact vs CPU oracle on batch %d (all outputs)" % b0
+        done, t_cpu = 0, time.perf_counter()
+        while done < K and (time.perf_counter() - t_cpu) < args.cpu_seconds:
+            b = Wm + done
+            hops_o = oracle.sample(off_h, idx_h, seeds[b].cpu().numpy(), sp.fanouts, rng_seeds[b])
+            cat = np.concatenate([seeds[b].cpu().numpy()] + [fl for _, _, fl in hops_o])
+            uq, _ = oracle.dedup(g.n_nodes, cat)
+            o = np.empty((uq.size, rb), np.uint8)
+            oracle.gather(uq, rank_h, tiers.n_hbm, tiers.n_host, tabs[0], tabs[1], o)
+            done += 1
+        cpu_elapsed = time.perf_counter() - t_cpu
+        result["cpu_baseline"] = {"value": done / cpu_elapsed, "unit": "mini-batches/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"{done} of the {K} timed batches (sample, dedup, lookup, gather, miss list), "
+                                            f"{cpu_elapsed:.1f} s"}
+    h.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -180,13 +180,33 @@ int helios_prepare_batch(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
                          void *out, int32_t *miss_pos, int32_t *miss_id, int32_t *miss_slot,
                          int64_t miss_cap, helios_gather_stats *stats);
 
-/* Timing of the two gather kernels of the last helios_gather /
- * helios_prepare_batch on this context, from HIP events recorded on the
- * streams the kernels ran on.  Enable first; when enabled, each such call
- * records events around the HBM-tier and the host-tier row-copy kernels.
- * helios_gather_times waits for them and returns milliseconds. */
+/* Launch-shape parameters of the row-copy kernels (tuning; results do not
+ * depend on them).  *_GATHER_BLOCKS: workgroups of the persistent grid that
+ * copies the HBM tier / the host tier and stand-in (0 = built-in default; the
+ * host-link kernels need few workgroups to fill the link, and fewer of them
+ * leave more of the memory system to the HBM-tier copy that runs beside them,
+ * cf. Sec. 3.3 "Operator Resources Allocation").  SERIAL_TIERS != 0 runs the
+ * two tier copies one after the other on the context's stream instead of side
+ * by side. */
+typedef enum {
+    HELIOS_PARAM_HBM_GATHER_BLOCKS = 1,
+    HELIOS_PARAM_HOST_GATHER_BLOCKS = 2,
+    HELIOS_PARAM_SERIAL_TIERS = 3
+} helios_param;
+int helios_set_param(helios_ctx *ctx, int param, int64_t value);
+
+/* Timing of the two row-copy kernels (HBM tier, host tier) of the last
+ * helios_gather / helios_prepare_batch on this context.  When enabled, every
+ * workgroup of those kernels stores its first and last tick of the GPU's
+ * constant-rate clock; helios_gather_times waits for the kernels and returns,
+ * per kernel, latest end minus earliest start in milliseconds (hbm_ms,
+ * host_ms: the kernel's own duration, as a kernel trace reports it), and the
+ * time between HIP events recorded around the launch on the kernel's stream
+ * (hbm_event_ms, host_event_ms, nullable: these also contain launch gaps).
+ * A tier that launched nothing reports 0. */
 int helios_set_timing(helios_ctx *ctx, int enabled);
-int helios_gather_times(helios_ctx *ctx, float *hbm_ms, float *host_ms);
+int helios_gather_times(helios_ctx *ctx, float *hbm_ms, float *host_ms,
+                        float *hbm_event_ms, float *host_event_ms);
 
 #ifdef __cplusplus
 }

@@ -26,7 +26,14 @@ struct GatherArgs {
     Count n;
     int32_t chunks;         // 16-byte pieces per row
     chunk16* out;
+    uint64_t* clock;        // nullable: [2 * gridDim.x] first and last tick of every workgroup
 };
+
+// Optional per-workgroup time stamps of the constant-rate device clock: the
+// host takes the earliest start and the latest end as the kernel's duration.
+__device__ __forceinline__ void stamp(uint64_t* clock, unsigned slot) {
+    if (clock && threadIdx.x == 0) clock[slot] = wall_clock64();
+}
 
 __device__ __forceinline__ chunk16 load16(const chunk16* p) {
     return __builtin_nontemporal_load(p);
@@ -39,6 +46,7 @@ __device__ __forceinline__ void store16(chunk16* p, const chunk16& v) {
 template <int L, int CPL, int R>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
     constexpr int kGroups = kBlock / L;
+    stamp(a.clock, blockIdx.x);
     const int64_t n = a.n.get();
     const int l = threadIdx.x % L;
     const int g = threadIdx.x / L;
@@ -73,10 +81,15 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
             }
         }
     }
+    if (a.clock) {
+        __syncthreads();
+        stamp(a.clock, gridDim.x + blockIdx.x);
+    }
 }
 
 // any row length: a wave per row, looping over the pieces
 __global__ __launch_bounds__(kBlock) void gather_rows_long_kernel(GatherArgs a) {
+    stamp(a.clock, blockIdx.x);
     const int64_t n = a.n.get();
     const int l = lane_id();
     const int64_t step = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
@@ -87,39 +100,49 @@ __global__ __launch_bounds__(kBlock) void gather_rows_long_kernel(GatherArgs a) 
         chunk16* o = a.out + d * a.chunks;
         for (int idx = l; idx < a.chunks; idx += kWave) store16(o + idx, load16(src + idx));
     }
+    if (a.clock) {
+        __syncthreads();
+        stamp(a.clock, gridDim.x + blockIdx.x);
+    }
 }
 
 template <int L, int CPL, int R>
-void launch_shape(hipStream_t stream, const GatherArgs& a, int64_t n_max, unsigned max_blocks) {
+unsigned launch_shape(hipStream_t stream, const GatherArgs& a, int64_t n_max, unsigned max_blocks) {
     constexpr int kRowsPerBlockStep = (kBlock / L) * R;
     int64_t blocks = (n_max + kRowsPerBlockStep - 1) / kRowsPerBlockStep;
     if (blocks < 1) blocks = 1;
     if (blocks > max_blocks) blocks = max_blocks;
     hipLaunchKernelGGL((gather_rows_kernel<L, CPL, R>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream, a);
+    return static_cast<unsigned>(blocks);
 }
 
 }  // namespace
 
 hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
-                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source) {
-    GatherArgs a{static_cast<const chunk16*>(table), pos, slot, n, row_bytes / 16, static_cast<chunk16*>(out)};
+                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,
+                              uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit) {
+    GatherArgs a{static_cast<const chunk16*>(table), pos, slot, n, row_bytes / 16, static_cast<chunk16*>(out), clock};
+    unsigned nb = 0;
     // persistent grid: 8 workgroups per CU for HBM sources; a far (host-link) source
     // saturates with far fewer requests in flight and leaves the CUs to other kernels
-    const unsigned max_blocks = far_source ? 256u : 2048u;
+    unsigned max_blocks = far_source ? 256u : kGatherMaxBlocks;
+    if (blocks_limit > 0) max_blocks = blocks_limit < kGatherMaxBlocks ? blocks_limit : kGatherMaxBlocks;
     const int c = a.chunks;
-    if (c <= 4) launch_shape<4, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 8) launch_shape<8, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 16) launch_shape<16, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 32) launch_shape<32, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 64) launch_shape<64, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 128) launch_shape<64, 2, 2>(stream, a, n_max, max_blocks);
-    else if (c <= 256) launch_shape<64, 4, 1>(stream, a, n_max, max_blocks);
+    if (c <= 4) nb = launch_shape<4, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 8) nb = launch_shape<8, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 16) nb = launch_shape<16, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 32) nb = launch_shape<32, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 64) nb = launch_shape<64, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 128) nb = launch_shape<64, 2, 2>(stream, a, n_max, max_blocks);
+    else if (c <= 256) nb = launch_shape<64, 4, 1>(stream, a, n_max, max_blocks);
     else {
         int64_t blocks = (n_max + kWavesPerBlock - 1) / kWavesPerBlock;
         if (blocks < 1) blocks = 1;
         if (blocks > max_blocks) blocks = max_blocks;
         hipLaunchKernelGGL(gather_rows_long_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream, a);
+        nb = static_cast<unsigned>(blocks);
     }
+    if (blocks_out) *blocks_out = nb;
     return hipGetLastError();
 }
 

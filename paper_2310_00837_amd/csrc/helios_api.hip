@@ -30,6 +30,12 @@ struct helios_ctx {
     bool timing = false, timed = false;
     hipEvent_t t_hbm[2] = {nullptr, nullptr}, t_host[2] = {nullptr, nullptr};
     bool timed_hbm = false, timed_host = false;
+    uint64_t* clock = nullptr;                 // device [2][2 * kGatherMaxBlocks] workgroup time stamps
+    uint64_t* clock_host = nullptr;            // pinned copy
+    unsigned clock_blocks[2] = {0, 0};
+    double clock_khz = 100000.0;
+    unsigned hbm_blocks = 0, host_blocks = 0;  // 0 = the launcher's default
+    bool serial_tiers = true;                  // the host-tier copy follows the HBM-tier copy (see helios_set_param)
     char errmsg[256] = {0};
 
     CsrView g{nullptr, nullptr, 0};
@@ -122,7 +128,7 @@ int ensure_capacity(helios_ctx* c, int64_t n) {
     free_scratch(c);
     const int64_t cap = (n + 4095) / 4096 * 4096;
     const uint32_t slots = pow2_at_least(2 * cap);
-    const uint32_t stride = static_cast<uint32_t>(cap / kBlock + 2);
+    const uint32_t stride = static_cast<uint32_t>(cap / (kBlock / kWave) + 2);   // most tiles: a hop with one wave per node
     HIP_TRY(c, hipMalloc(&c->dd.table, sizeof(unsigned long long) * slots));
     HIP_TRY(c, hipMalloc(&c->dd.slot_of, sizeof(int32_t) * cap));
     HIP_TRY(c, hipMalloc(&c->dd.index_of_first, sizeof(int32_t) * cap));
@@ -240,23 +246,29 @@ int gather_impl(helios_ctx* c, const int32_t* ids, Count n, void* out, int32_t* 
                                        c->err));
     c->timed_hbm = c->timed_host = false;
     const bool do_hbm = c->n_hbm > 0 && n.host > 0, do_host = c->n_host > 0 && n.host > 0;
-    if (do_host) {                              // fork: the host-tier copy runs beside the HBM-tier copy
+    const bool fork = do_host && !c->serial_tiers;
+    hipStream_t host_stream = fork ? c->aux : c->stream;
+    if (fork) {                                 // the host-tier copy runs beside the HBM-tier copy
         HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));
         HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_fork, 0));
     }
     if (do_hbm) {
         if (c->timing) HIP_TRY(c, hipEventRecord(c->t_hbm[0], c->stream));
         HIP_TRY(c, launch_gather_rows(c->stream, c->hbm_table, lists.pos[0], lists.slot[0],
-                                      Count{c->cnt + kCntTier + 0, n.host}, n.host, c->row_bytes, out, false));
+                                      Count{c->cnt + kCntTier + 0, n.host}, n.host, c->row_bytes, out, false,
+                                      c->timing ? c->clock : nullptr, &c->clock_blocks[0], c->hbm_blocks));
         if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream)); c->timed_hbm = true; }
     }
     if (do_host) {
-        if (c->timing) HIP_TRY(c, hipEventRecord(c->t_host[0], c->aux));
-        HIP_TRY(c, launch_gather_rows(c->aux, c->host_table, lists.pos[1], lists.slot[1],
-                                      Count{c->cnt + kCntTier + 1, n.host}, n.host, c->row_bytes, out, true));
-        if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_host[1], c->aux)); c->timed_host = true; }
-        HIP_TRY(c, hipEventRecord(c->ev_join, c->aux));
-        HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+        if (c->timing) HIP_TRY(c, hipEventRecord(c->t_host[0], host_stream));
+        HIP_TRY(c, launch_gather_rows(host_stream, c->host_table, lists.pos[1], lists.slot[1],
+                                      Count{c->cnt + kCntTier + 1, n.host}, n.host, c->row_bytes, out, true,
+                                      c->timing ? c->clock + 2 * kGatherMaxBlocks : nullptr, &c->clock_blocks[1], c->host_blocks));
+        if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_host[1], host_stream)); c->timed_host = true; }
+        if (fork) {
+            HIP_TRY(c, hipEventRecord(c->ev_join, c->aux));
+            HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+        }
     }
     return HELIOS_OK;
 }
@@ -282,8 +294,12 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipEventCreate(&c->t_host[0]) == hipSuccess && hipEventCreate(&c->t_host[1]) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->err), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
-              hipMalloc(&c->scan_ticket, 64) == hipSuccess;
+              hipMalloc(&c->scan_ticket, 64) == hipSuccess &&
+              hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4 * kGatherMaxBlocks, hipHostMallocDefault) == hipSuccess;
     if (ok) {
+        int khz = 0;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;
         c->err[0] = c->err[1] = 0;
         ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
              hipMemsetAsync(c->scan_ticket, 0, 64, c->stream) == hipSuccess &&
@@ -306,6 +322,8 @@ int helios_destroy(helios_ctx* c) {
     (void)hipFree(c->rank);
     (void)hipFree(c->cnt);
     (void)hipFree(c->scan_ticket);
+    (void)hipFree(c->clock);
+    if (c->clock_host) (void)hipHostFree(c->clock_host);
     if (c->err) (void)hipHostFree(c->err);
     for (hipEvent_t e : {c->ev_fork, c->ev_join, c->t_hbm[0], c->t_hbm[1], c->t_host[0], c->t_host[1]})
         if (e) (void)hipEventDestroy(e);
@@ -387,7 +405,7 @@ int helios_cache_fill(helios_ctx* c, const void* src_table, const int32_t* order
     if (!src_table || !order || !dst) return fail(c, HELIOS_EINVAL, "NULL pointer");
     DeviceGuard guard(c->device);
     HIP_TRY(c, launch_gather_rows(c->stream, src_table, nullptr, order + first_rank, Count{nullptr, n_rows}, n_rows,
-                                  row_bytes, dst, false));
+                                  row_bytes, dst, false, nullptr, nullptr, 0));
     return HELIOS_OK;
 }
 
@@ -440,7 +458,7 @@ int helios_gather_miss(helios_ctx* c, const int32_t* miss_pos, const int32_t* mi
     if (!c->standin_table) return fail(c, HELIOS_ESTATE, "no stand-in table was given to helios_cache_build");
     DeviceGuard guard(c->device);
     HIP_TRY(c, launch_gather_rows(c->stream, c->standin_table, miss_pos, miss_slot, Count{n_miss_dev, n_miss_max},
-                                  n_miss_max, c->row_bytes, out, true));
+                                  n_miss_max, c->row_bytes, out, true, nullptr, nullptr, c->host_blocks));
     return HELIOS_OK;
 }
 
@@ -478,6 +496,24 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
 }
 
+int helios_set_param(helios_ctx* c, int param, int64_t value) {
+    if (!c) return HELIOS_EINVAL;
+    if (value < 0) return fail(c, HELIOS_EINVAL, "helios_set_param: negative value");
+    switch (param) {
+        case HELIOS_PARAM_HBM_GATHER_BLOCKS:
+            c->hbm_blocks = static_cast<unsigned>(value > kGatherMaxBlocks ? kGatherMaxBlocks : value);
+            return HELIOS_OK;
+        case HELIOS_PARAM_HOST_GATHER_BLOCKS:
+            c->host_blocks = static_cast<unsigned>(value > kGatherMaxBlocks ? kGatherMaxBlocks : value);
+            return HELIOS_OK;
+        case HELIOS_PARAM_SERIAL_TIERS:
+            c->serial_tiers = value != 0;
+            return HELIOS_OK;
+        default:
+            return fail(c, HELIOS_EINVAL, "helios_set_param: unknown parameter %d", param);
+    }
+}
+
 int helios_set_timing(helios_ctx* c, int enabled) {
     if (!c) return HELIOS_EINVAL;
     c->timing = enabled != 0;
@@ -485,17 +521,30 @@ int helios_set_timing(helios_ctx* c, int enabled) {
     return HELIOS_OK;
 }
 
-int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms) {
+int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms, float* hbm_event_ms, float* host_event_ms) {
     if (!c || !hbm_ms || !host_ms) return HELIOS_EINVAL;
     DeviceGuard guard(c->device);
     *hbm_ms = *host_ms = 0.f;
-    if (c->timed_hbm) {
-        HIP_TRY(c, hipEventSynchronize(c->t_hbm[1]));
-        HIP_TRY(c, hipEventElapsedTime(hbm_ms, c->t_hbm[0], c->t_hbm[1]));
-    }
-    if (c->timed_host) {
-        HIP_TRY(c, hipEventSynchronize(c->t_host[1]));
-        HIP_TRY(c, hipEventElapsedTime(host_ms, c->t_host[0], c->t_host[1]));
+    if (hbm_event_ms) *hbm_event_ms = 0.f;
+    if (host_event_ms) *host_event_ms = 0.f;
+    if (!c->timed_hbm && !c->timed_host) return HELIOS_OK;
+    if (c->timed_hbm) HIP_TRY(c, hipEventSynchronize(c->t_hbm[1]));
+    if (c->timed_host) HIP_TRY(c, hipEventSynchronize(c->t_host[1]));
+    HIP_TRY(c, hipMemcpy(c->clock_host, c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks, hipMemcpyDeviceToHost));
+    for (int t = 0; t < 2; ++t) {
+        if (!(t == 0 ? c->timed_hbm : c->timed_host)) continue;
+        const uint64_t* k = c->clock_host + static_cast<size_t>(t) * 2 * kGatherMaxBlocks;
+        const unsigned nb = c->clock_blocks[t];
+        uint64_t lo = ~0ull, hi = 0;
+        for (unsigned b = 0; b < nb; ++b) {
+            if (k[b] < lo) lo = k[b];
+            if (k[nb + b] > hi) hi = k[nb + b];
+        }
+        const float ms = nb && hi >= lo ? static_cast<float>(static_cast<double>(hi - lo) / c->clock_khz) : 0.f;
+        float ev = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ev, t == 0 ? c->t_hbm[0] : c->t_host[0], t == 0 ? c->t_hbm[1] : c->t_host[1]));
+        if (t == 0) { *hbm_ms = ms; if (hbm_event_ms) *hbm_event_ms = ev; }
+        else { *host_ms = ms; if (host_event_ms) *host_event_ms = ev; }
     }
     return HELIOS_OK;
 }

@@ -17,6 +17,9 @@ struct CsrView {
 // One hop: for i < n_frontier, indptr[i] = start of frontier[i]'s samples in flat,
 // indptr[n_frontier] = total; writes n_frontier and total to size_out[0], size_out[1]
 // (device-accessible, nullable) and total to *n_flat_dev.
+// lanes that share one node, and workgroups (= scan tiles) a hop needs
+int sample_group_lanes(int32_t fanout);
+int64_t sample_hop_tiles(int64_t n_frontier_max, int32_t fanout);
 hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, Count n_frontier,
                              int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
                              int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
@@ -59,7 +62,11 @@ hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count
 // ---- gather.hip
 // out[pos[k], :] = table[slot[k], :] for k < n; pos == nullptr means pos[k] = k.
 // `wide` selects the launch shape tuned for a far (host-link) source.
+// clock (nullable): device uint64[2 * kGatherMaxBlocks]; every workgroup stores its first and last
+// tick of the constant-rate device clock at [b] and [blocks + b]; *blocks_out = workgroups launched.
+constexpr unsigned kGatherMaxBlocks = 2048;
 hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
-                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source);
+                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,
+                              uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit /* 0 = default */);
 
 }  // namespace helios

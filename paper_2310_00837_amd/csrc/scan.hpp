@@ -2,7 +2,7 @@
 //
 // Each workgroup owns one tile, taken in launch order from a ticket counter so
 // that every tile a workgroup waits for is already running.  A tile publishes
-// its aggregate, then looks back over its predecessors, 64 at a time, until it
+// its aggregate, then looks back over its predecessors, 256 at a time, until it
 // meets one that has published a full inclusive prefix.  One 64-bit status word
 // per tile and counter holds {epoch:30, flag:2, value:32}; the epoch changes on
 // every launch, so a stale word reads as "not published" and the buffer never
@@ -48,52 +48,98 @@ __device__ __forceinline__ uint32_t scan_take_ticket(const ScanState& st, uint32
     return t;
 }
 
+// LDS the look-back needs: per counter and wave, {prefix seen, partial sum}.
+template <int NC>
+struct ScanLookbackLds {
+    uint32_t seen[NC][kWavesPerBlock];
+    uint32_t part[NC][kWavesPerBlock];
+};
+
 // Exclusive prefix of this tile's aggregates over all earlier tiles, for NC
 // counters at once.  s_agg[c] holds the tile aggregate (written by the caller
-// before the call, barrier included here); on return s_excl[c] holds the
-// exclusive prefix.  The first wave does the look-back.  Call from uniform
-// control flow; tile < st.stride is the caller's duty.
+// before the call; a barrier comes first here); on return s_excl[c] holds the
+// exclusive prefix.  The whole workgroup looks back, 256 predecessors per round
+// and all counters in the same round: thread k reads the status words of tile
+// (first - k); within a round each wave reduces its 64 words and the waves are
+// combined in order, stopping at the nearest predecessor that has published a
+// full prefix.  A round costs one device-scope read latency, so the look-back
+// of a launch with T tiles takes about T/256 rounds at worst.  Call from
+// uniform control flow; tile < st.stride is the caller's duty.
 template <int NC>
-__device__ __forceinline__ void scan_chained_prefix(const ScanState& st, uint32_t tile,
-                                                    const uint32_t* s_agg, uint32_t* s_excl) {
+__device__ __forceinline__ void scan_chained_prefix(const ScanState& st, uint32_t tile, const uint32_t* s_agg,
+                                                    uint32_t* s_excl, ScanLookbackLds<NC>* lds) {
     __syncthreads();
-    if (wave_id() == 0) {
-        const int lane = lane_id();
+    if (threadIdx.x < NC) {
+        const uint32_t c = threadIdx.x;
+        scan_store(st.status + static_cast<size_t>(c) * st.stride + tile,
+                   scan_pack(st.epoch, tile == 0 ? kFlagPrefix : kFlagAggregate, s_agg[c]));
+        if (tile == 0) s_excl[c] = 0;
+    }
+    if (tile == 0) {
+        __syncthreads();
+        return;
+    }
+    const int lane = lane_id(), wave = wave_id();
+    uint32_t excl[NC];
+    bool done[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) { excl[c] = 0; done[c] = false; }
+    int64_t first = static_cast<int64_t>(tile) - 1;          // nearest predecessor of the round
+    while (true) {
+        const int64_t idx = first - static_cast<int64_t>(threadIdx.x);
+#pragma unroll
         for (int c = 0; c < NC; ++c) {
-            unsigned long long* row = st.status + static_cast<size_t>(c) * st.stride;
-            const uint32_t agg = s_agg[c];
-            uint32_t excl = 0;
-            if (tile == 0) {
-                if (lane == 0) scan_store(row, scan_pack(st.epoch, kFlagPrefix, agg));
-            } else {
-                if (lane == 0) scan_store(row + tile, scan_pack(st.epoch, kFlagAggregate, agg));
-                int64_t first = static_cast<int64_t>(tile) - 1;      // nearest predecessor of the window
-                while (true) {
-                    const int64_t idx = first - lane;
-                    uint32_t flag = kFlagPrefix, val = 0;            // lanes before tile 0 act as an empty prefix
-                    if (idx >= 0) {
-                        unsigned long long w;
-                        do {
-                            w = scan_load(row + idx);
-                            flag = static_cast<uint32_t>(w >> 32) & 3u;
-                            if (static_cast<uint32_t>(w >> 34) != st.epoch) flag = 0;
-                            if (flag == 0) __builtin_amdgcn_s_sleep(1);
-                        } while (flag == 0);
-                        val = static_cast<uint32_t>(w);
-                    }
-                    const unsigned long long has_prefix = __ballot(flag == kFlagPrefix);
-                    if (has_prefix) {
-                        const int stop = __ffsll(static_cast<long long>(has_prefix)) - 1;
-                        excl += wave_sum(lane <= stop ? val : 0u);
-                        break;
-                    }
-                    excl += wave_sum(val);
-                    first -= kWave;
-                }
-                if (lane == 0) scan_store(row + tile, scan_pack(st.epoch, kFlagPrefix, excl + agg));
+            if (done[c]) continue;                           // uniform over the workgroup
+            uint32_t flag = kFlagPrefix, val = 0;            // positions before tile 0 act as an empty prefix
+            if (idx >= 0) {
+                unsigned long long* p = st.status + static_cast<size_t>(c) * st.stride + idx;
+                unsigned long long w;
+                do {
+                    w = scan_load(p);
+                    flag = static_cast<uint32_t>(w >> 32) & 3u;
+                    if (static_cast<uint32_t>(w >> 34) != st.epoch) flag = 0;
+                    if (flag == 0) __builtin_amdgcn_s_sleep(1);
+                } while (flag == 0);
+                val = static_cast<uint32_t>(w);
             }
-            if (lane == 0) s_excl[c] = excl;
+            const unsigned long long has_prefix = __ballot(flag == kFlagPrefix);
+            uint32_t part;
+            if (has_prefix) {
+                const int stop = __ffsll(static_cast<long long>(has_prefix)) - 1;
+                part = wave_sum(lane <= stop ? val : 0u);
+            } else {
+                part = wave_sum(val);
+            }
+            if (lane == 0) {
+                lds->seen[c][wave] = has_prefix ? 1u : 0u;
+                lds->part[c][wave] = part;
+            }
         }
+        __syncthreads();
+        bool all_done = true;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (done[c]) continue;
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock; ++w) {
+                if (!done[c]) {
+                    excl[c] += lds->part[c][w];
+                    if (lds->seen[c][w]) done[c] = true;
+                }
+            }
+            all_done = all_done && done[c];
+        }
+        __syncthreads();                                     // lds is rewritten in the next round
+        if (all_done) break;
+        first -= kBlock;
+    }
+    if (threadIdx.x < NC) {
+        const uint32_t c = threadIdx.x;
+        uint32_t e = 0;
+#pragma unroll
+        for (int q = 0; q < NC; ++q) if (q == static_cast<int>(c)) e = excl[q];
+        scan_store(st.status + static_cast<size_t>(c) * st.stride + tile, scan_pack(st.epoch, kFlagPrefix, e + s_agg[c]));
+        s_excl[c] = e;
     }
     __syncthreads();
 }

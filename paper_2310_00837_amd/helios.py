@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libhelios.so")
 
 OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA = 0, -1, -2, -3, -4, -5
 MAX_HOPS, MAX_FANOUT = 8, 1024
+PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SERIAL_TIERS = 1, 2, 3
 _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
           -5: "HELIOS_EDATA"}
 
 # every symbol include/helios.h declares
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
-           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_set_timing",
+           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_set_param", "helios_set_timing",
            "helios_gather_times"]
 
 
@@ -61,8 +62,9 @@ def load_library() -> C.CDLL:
     lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
                                          vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.helios_set_param.argtypes = [vp, C.c_int, i64]
     lib.helios_set_timing.argtypes = [vp, C.c_int]
-    lib.helios_gather_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.helios_gather_times.argtypes = [vp] + [C.POINTER(C.c_float)] * 4
     return lib
 
 
@@ -145,13 +147,17 @@ class Helios:
     def sync(self) -> None:
         self._check(_lib.helios_sync(self._h))
 
+    def set_param(self, param: int, value: int) -> None:
+        self._check(_lib.helios_set_param(self._h, param, value))
+
     def set_timing(self, enabled: bool) -> None:
         self._check(_lib.helios_set_timing(self._h, int(enabled)))
 
     def gather_times(self):
-        a, b = C.c_float(), C.c_float()
-        self._check(_lib.helios_gather_times(self._h, C.byref(a), C.byref(b)))
-        return a.value, b.value
+        """(hbm_ms, host_ms, hbm_event_ms, host_event_ms) of the last gather."""
+        v = [C.c_float() for _ in range(4)]
+        self._check(_lib.helios_gather_times(self._h, *[C.byref(x) for x in v]))
+        return tuple(x.value for x in v)
 
     # ---- S0
     def csr_load(self, offsets: torch.Tensor, indices: torch.Tensor) -> None:

@@ -323,3 +323,31 @@ def seed_batch(sp: WorkloadSpec, g: Graph, batch_index: int, epoch: int = 0) -> 
         k = torch.clamp(torch.floor(torch.exp(u * math.log(n + 1.0))).to(torch.int64), 1, n)
         return g.perm_seed[k - 1].to(torch.int32)
     raise ValueError(sp.seeds)
+
+
+@dataclass
+class Tiers:
+    """Feature tables in rank order (row r of the concatenation = feat(order[r]))."""
+    n_hbm: int
+    n_host: int
+    n_rest: int
+    row_bytes: int
+    hbm: torch.Tensor          # [max(n_hbm,1), dim] on the GPU
+    host: torch.Tensor         # [max(n_host,1), dim] pinned host memory
+    standin: torch.Tensor      # [max(n_rest,1), dim] pinned host memory (storage stand-in)
+
+
+def make_tiers(sp: WorkloadSpec, g: Graph, device, progress: Optional[Callable[[str], None]] = None) -> Tiers:
+    """Fill the three tier tables directly in rank order; the full feature table is never
+    materialised.  `device` is where the HBM tier lives and where rows are generated."""
+    n_hbm, n_host, n_rest = sp.tier_rows(g.n_nodes)
+    dev = torch.device(device)
+    order = g.order.to(dev)
+    pin = dev.type == "cuda"
+    hbm = torch.empty((max(n_hbm, 1), sp.dim), dtype=sp.dtype, device=dev)
+    host = torch.empty((max(n_host, 1), sp.dim), dtype=sp.dtype, pin_memory=pin)
+    standin = torch.empty((max(n_rest, 1), sp.dim), dtype=sp.dtype, pin_memory=pin)
+    fill_rows(hbm[:n_hbm], g.seed, order[:n_hbm], progress=progress)
+    fill_rows(host[:n_host], g.seed, order[n_hbm:n_hbm + n_host], progress=progress)
+    fill_rows(standin[:n_rest], g.seed, order[n_hbm + n_host:], progress=progress)
+    return Tiers(n_hbm, n_host, n_rest, sp.row_bytes, hbm, host, standin)
