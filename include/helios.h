@@ -180,14 +180,22 @@ int helios_prepare_batch(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
                          void *out, int32_t *miss_pos, int32_t *miss_id, int32_t *miss_slot,
                          int64_t miss_cap, helios_gather_stats *stats);
 
+/* Pinned, GPU-mapped host memory of exactly `bytes` bytes for the host tier
+ * and the storage stand-in (Sec. 3.2.1 "CPU Cache": CPU memory that GPU
+ * threads read directly).  The pointer is valid on the host and on every GPU.
+ * Returns NULL on failure.  Free with helios_host_free, after every context
+ * that uses the memory is destroyed or has been given other tables. */
+void *helios_host_alloc(int64_t bytes);
+int helios_host_free(void *ptr);
+
 /* Launch-shape parameters of the row-copy kernels (tuning; results do not
  * depend on them).  *_GATHER_BLOCKS: workgroups of the persistent grid that
  * copies the HBM tier / the host tier and stand-in (0 = built-in default; the
  * host-link kernels need few workgroups to fill the link, and fewer of them
  * leave more of the memory system to the HBM-tier copy that runs beside them,
- * cf. Sec. 3.3 "Operator Resources Allocation").  SERIAL_TIERS != 0 runs the
- * two tier copies one after the other on the context's stream instead of side
- * by side. */
+ * cf. Sec. 3.3 "Operator Resources Allocation").  SERIAL_TIERS: non-zero (the
+ * default) runs the host-tier copy after the HBM-tier copy on the context's
+ * stream; zero runs the two side by side on two streams. */
 typedef enum {
     HELIOS_PARAM_HBM_GATHER_BLOCKS = 1,
     HELIOS_PARAM_HOST_GATHER_BLOCKS = 2,

@@ -455,6 +455,7 @@ int helios_gather_miss(helios_ctx* c, const int32_t* miss_pos, const int32_t* mi
     if (n_miss_max < 0) return fail(c, HELIOS_EINVAL, "negative size");
     if (n_miss_max == 0) return HELIOS_OK;
     if (!miss_pos || !miss_slot || !out) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    if (c->n_hbm + c->n_host >= c->g.n_nodes) return HELIOS_OK;      // every node is cached: nothing can miss
     if (!c->standin_table) return fail(c, HELIOS_ESTATE, "no stand-in table was given to helios_cache_build");
     DeviceGuard guard(c->device);
     HIP_TRY(c, launch_gather_rows(c->stream, c->standin_table, miss_pos, miss_slot, Count{n_miss_dev, n_miss_max},
@@ -494,6 +495,21 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     if (rc) return rc;
     const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
     return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+}
+
+void* helios_host_alloc(int64_t bytes) {
+    if (bytes <= 0) return nullptr;
+    void* p = nullptr;
+    if (hipHostMalloc(&p, static_cast<size_t>(bytes), hipHostMallocMapped | hipHostMallocPortable) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return p;
+}
+
+int helios_host_free(void* p) {
+    if (!p) return HELIOS_OK;
+    return hipHostFree(p) == hipSuccess ? HELIOS_OK : HELIOS_EHIP;
 }
 
 int helios_set_param(helios_ctx* c, int param, int64_t value) {

@@ -25,7 +25,7 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 # every symbol include/helios.h declares
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
-           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_set_param", "helios_set_timing",
+           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_set_param", "helios_set_timing",
            "helios_gather_times"]
 
 
@@ -62,6 +62,9 @@ def load_library() -> C.CDLL:
     lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
                                          vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.helios_host_alloc.argtypes = [i64]
+    lib.helios_host_alloc.restype = vp
+    lib.helios_host_free.argtypes = [vp]
     lib.helios_set_param.argtypes = [vp, C.c_int, i64]
     lib.helios_set_timing.argtypes = [vp, C.c_int]
     lib.helios_gather_times.argtypes = [vp] + [C.POINTER(C.c_float)] * 4
@@ -78,6 +81,13 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return t.data_ptr()
 
 
+def _is_pinned(t: torch.Tensor) -> bool:
+    try:
+        return bool(t.is_pinned())
+    except RuntimeError:
+        return False
+
+
 def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
     if t.dtype != dtype or not t.is_cuda or not t.is_contiguous():
         raise TypeError(f"{what}: expected a contiguous {dtype} tensor on the GPU")
@@ -85,9 +95,44 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
 
 
 def _dev_accessible(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
-    if t.dtype != dtype or not t.is_contiguous() or not (t.is_cuda or t.is_pinned()):
+    if t.dtype != dtype or not t.is_contiguous() or not (t.is_cuda or _is_pinned(t)):
         raise TypeError(f"{what}: expected a contiguous {dtype} tensor on the GPU or in pinned host memory")
     return t
+
+
+class PinnedBuffer:
+    """Pinned, GPU-mapped host memory from helios_host_alloc, seen as a torch tensor.
+    Unlike torch's pinned allocator it takes exactly the bytes asked for and gives them
+    back on free().  Keep the object alive while `tensor` (or a view of it) is in use."""
+
+    def __init__(self, shape, dtype: torch.dtype):
+        n = 1
+        for d in shape:
+            n *= int(d)
+        self.nbytes = max(n, 1) * torch.empty((), dtype=dtype).element_size()
+        self.ptr = _lib.helios_host_alloc(self.nbytes)
+        if not self.ptr:
+            raise MemoryError(f"helios_host_alloc({self.nbytes}) failed")
+        self._raw = (C.c_uint8 * self.nbytes).from_address(self.ptr)
+        flat = torch.frombuffer(self._raw, dtype=dtype)
+        self.tensor = flat[:n].reshape(tuple(int(d) for d in shape)) if n else flat[:0].reshape(tuple(shape))
+
+    def free(self) -> None:
+        if self.ptr:
+            self.tensor = None
+            self._raw = None
+            _lib.helios_host_free(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def pinned_empty(shape, dtype: torch.dtype) -> PinnedBuffer:
+    return PinnedBuffer(shape, dtype)
 
 
 @dataclass
@@ -174,7 +219,7 @@ class Helios:
         if hbm_table is not None and not hbm_table.is_cuda:
             raise TypeError("hbm_table must be on the GPU")
         for t, w in ((host_table, "host_table"), (standin_table, "standin_table")):
-            if t is not None and not (t.is_pinned() or t.is_cuda):
+            if t is not None and not (_is_pinned(t) or t.is_cuda):
                 raise TypeError(f"{w} must be pinned host memory")
         self._keep["cache"] = (order, hbm_table, host_table, standin_table)
         self.row_bytes = row_bytes

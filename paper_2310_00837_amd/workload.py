@@ -337,16 +337,22 @@ class Tiers:
     standin: torch.Tensor      # [max(n_rest,1), dim] pinned host memory (storage stand-in)
 
 
-def make_tiers(sp: WorkloadSpec, g: Graph, device, progress: Optional[Callable[[str], None]] = None) -> Tiers:
+def make_tiers(sp: WorkloadSpec, g: Graph, device, progress: Optional[Callable[[str], None]] = None,
+               pinned_empty: Optional[Callable] = None) -> Tiers:
     """Fill the three tier tables directly in rank order; the full feature table is never
-    materialised.  `device` is where the HBM tier lives and where rows are generated."""
+    materialised.  `device` is where the HBM tier lives and where rows are generated.
+    pinned_empty(shape, dtype) -> tensor allocates the two host tables (default: torch's
+    pinned allocator, which rounds sizes up to a power of two)."""
     n_hbm, n_host, n_rest = sp.tier_rows(g.n_nodes)
     dev = torch.device(device)
     order = g.order.to(dev)
     pin = dev.type == "cuda"
     hbm = torch.empty((max(n_hbm, 1), sp.dim), dtype=sp.dtype, device=dev)
-    host = torch.empty((max(n_host, 1), sp.dim), dtype=sp.dtype, pin_memory=pin)
-    standin = torch.empty((max(n_rest, 1), sp.dim), dtype=sp.dtype, pin_memory=pin)
+    if pinned_empty is None:
+        def pinned_empty(shape, dtype):
+            return torch.empty(shape, dtype=dtype, pin_memory=pin)
+    host = pinned_empty((max(n_host, 1), sp.dim), sp.dtype)
+    standin = pinned_empty((max(n_rest, 1), sp.dim), sp.dtype)
     fill_rows(hbm[:n_hbm], g.seed, order[:n_hbm], progress=progress)
     fill_rows(host[:n_host], g.seed, order[n_hbm:n_hbm + n_host], progress=progress)
     fill_rows(standin[:n_rest], g.seed, order[n_hbm + n_host:], progress=progress)
