@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--link-gbs", type=float, default=None,
+                    help="skip the host-link probe and use this rate (for runs under a counter profiler)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; the path shards by giving each GPU its own "
@@ -81,10 +83,24 @@ def main() -> int:
     tiers = W.make_tiers(sp, g, dev, progress=log if sp.n_nodes > 5_000_000 else None)
     log(f"tiers: hbm {tiers.n_hbm} host {tiers.n_host} stand-in {tiers.n_rest} rows x {sp.row_bytes} B "
         f"filled in {time.time() - t1:.1f}s")
-    link_gbs = measure_host_link(torch)
-    log(f"host link (pinned H2D copy): {link_gbs:.1f} GB/s")
+    link_gbs = args.link_gbs if args.link_gbs else measure_host_link(torch)
+    log(f"host link (pinned H2D copy): {link_gbs:.1f} GB/s" + (" (given)" if args.link_gbs else ""))
 
     h = helios.Helios(0)
+    # yardstick: a plain 1 GiB device copy with the row copy's accesses (known traffic: 1 GiB read + 1 GiB written)
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_src.fill_(3)
+    copy_gbs = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        h.calibration_copy(cal_src, cal_dst)
+        e1.record()
+        e1.synchronize()
+        copy_gbs = max(copy_gbs, 2.0 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del cal_src, cal_dst
+    log(f"plain device copy (1 GiB, read+write): {copy_gbs:.0f} GB/s")
     h.csr_load(offsets, indices)
     h.cache_build(order, tiers.n_hbm, tiers.n_host, sp.row_bytes, tiers.hbm, tiers.host, tiers.standin)
     h.sync()
@@ -167,11 +183,11 @@ def main() -> int:
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None,
                      "avg_kernel_us": acc["hbm_ms"] / K * 1e3, "avg_event_us": acc["hbm_ev_ms"] / K * 1e3,
                      "timer": "device clock, earliest workgroup start to latest end", "rows_per_launch": acc["hbm_rows"] / K,
-                     "bytes_per_row": 2 * rb},
+                     "bytes_per_row": 2 * rb, "plain_copy_GBs_on_this_box": copy_gbs},
         "roofline_host_link": {"kernel": "gather_rows_kernel (host tier)", "bound": "host_link",
                                "achieved": host_gbs, "peak": link_gbs, "unit": "GB/s",
                                "frac": host_gbs / link_gbs if link_gbs > 0 else None,
-                               "peak_source": "pinned H2D copy measured in this run",
+                               "peak_source": "given on the command line" if args.link_gbs else "pinned H2D copy measured in this run",
                                "avg_kernel_us": acc["host_ms"] / K * 1e3, "avg_event_us": acc["host_ev_ms"] / K * 1e3,
                                "rows_per_launch": acc["host_rows"] / K,
                                "bytes_per_row": rb},

@@ -188,6 +188,13 @@ int helios_prepare_batch(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
 void *helios_host_alloc(int64_t bytes);
 int helios_host_free(void *ptr);
 
+/* A plain streaming copy dst[0, bytes) = src[0, bytes) (bytes a multiple of
+ * 16; device-accessible pointers) with the row copy's 16-byte accesses.  It
+ * is the yardstick of the measurements: hardware byte counters are scaled by
+ * what they read for this kernel, whose traffic is known, and its rate is the
+ * copy bandwidth the part reaches. */
+int helios_calibration_copy(helios_ctx *ctx, const void *src, void *dst, int64_t bytes);
+
 /* Launch-shape parameters of the row-copy kernels (tuning; results do not
  * depend on them).  *_GATHER_BLOCKS: workgroups of the persistent grid that
  * copies the HBM tier / the host tier and stand-in (0 = built-in default; the

@@ -106,6 +106,15 @@ __global__ __launch_bounds__(kBlock) void gather_rows_long_kernel(GatherArgs a) 
     }
 }
 
+// plain streaming copy of known size: the yardstick for hardware counters and for the
+// bandwidth a copy can reach on this part
+__global__ __launch_bounds__(kBlock) void calibration_copy_kernel(const chunk16* __restrict__ src, chunk16* __restrict__ dst,
+                                                                  int64_t n_chunks) {
+    const int64_t step = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n_chunks; i += step)
+        store16(dst + i, load16(src + i));
+}
+
 template <int L, int CPL, int R>
 unsigned launch_shape(hipStream_t stream, const GatherArgs& a, int64_t n_max, unsigned max_blocks) {
     constexpr int kRowsPerBlockStep = (kBlock / L) * R;
@@ -117,6 +126,12 @@ unsigned launch_shape(hipStream_t stream, const GatherArgs& a, int64_t n_max, un
 }
 
 }  // namespace
+
+hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* dst, int64_t bytes) {
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(kGatherMaxBlocks), dim3(kBlock), 0, stream,
+                       static_cast<const chunk16*>(src), static_cast<chunk16*>(dst), bytes / 16);
+    return hipGetLastError();
+}
 
 hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
                               Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,

@@ -497,6 +497,13 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
 }
 
+int helios_calibration_copy(helios_ctx* c, const void* src, void* dst, int64_t bytes) {
+    if (!c || !src || !dst || bytes < 0 || bytes % 16 != 0) return fail(c, HELIOS_EINVAL, "helios_calibration_copy: bad argument");
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, launch_calibration_copy(c->stream, src, dst, bytes));
+    return HELIOS_OK;
+}
+
 void* helios_host_alloc(int64_t bytes) {
     if (bytes <= 0) return nullptr;
     void* p = nullptr;

@@ -69,4 +69,7 @@ hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32
                               Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,
                               uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit /* 0 = default */);
 
+// dst[0, bytes) = src[0, bytes) with the same 16-byte non-temporal accesses as the row copy
+hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* dst, int64_t bytes);
+
 }  // namespace helios

@@ -25,7 +25,7 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 # every symbol include/helios.h declares
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
-           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_set_param", "helios_set_timing",
+           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_set_param", "helios_set_timing",
            "helios_gather_times"]
 
 
@@ -62,6 +62,7 @@ def load_library() -> C.CDLL:
     lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
                                          vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.helios_calibration_copy.argtypes = [vp, vp, vp, i64]
     lib.helios_host_alloc.argtypes = [i64]
     lib.helios_host_alloc.restype = vp
     lib.helios_host_free.argtypes = [vp]
@@ -191,6 +192,11 @@ class Helios:
 
     def sync(self) -> None:
         self._check(_lib.helios_sync(self._h))
+
+    def calibration_copy(self, src: torch.Tensor, dst: torch.Tensor) -> None:
+        nbytes = src.numel() * src.element_size()
+        assert dst.numel() * dst.element_size() == nbytes and nbytes % 16 == 0
+        self._check(_lib.helios_calibration_copy(self._h, _ptr(src), _ptr(dst), nbytes))
 
     def set_param(self, param: int, value: int) -> None:
         self._check(_lib.helios_set_param(self._h, param, value))

@@ -1,0 +1,67 @@
+"""Turn the CSV output of `rocprofv3 --kernel-trace --stats --output-format csv` (and of
+`rocprofv3 --pmc ... --output-format csv`) into the short text summaries kept under profiles/.
+
+    python -m paper_2310_00837_amd.prof trace  <dir> <prefix>     # per-kernel durations
+    python -m paper_2310_00837_amd.prof pmc    <dir> <prefix> <COUNTER>   # per-kernel counter sums
+
+Kernels of this library are listed one line per (kernel, grid size), since the same row-copy
+kernel serves the HBM tier (large grid) and the host tier / stand-in (small grid).
+"""
+import collections
+import csv
+import os
+import sys
+
+
+def _short(name: str) -> str:
+    return name.replace("helios::(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+
+
+def trace(d: str, prefix: str) -> str:
+    rows = list(csv.DictReader(open(os.path.join(d, f"{prefix}_kernel_trace.csv"))))
+    agg = collections.OrderedDict()
+    for r in rows:
+        if "helios" not in r["Kernel_Name"]:
+            continue
+        key = (_short(r["Kernel_Name"]), int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1))
+        dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+        a = agg.setdefault(key, [0, 0, 1 << 62, 0])
+        a[0] += 1
+        a[1] += dur
+        a[2] = min(a[2], dur)
+        a[3] = max(a[3], dur)
+    total = sum(a[1] for a in agg.values()) or 1
+    out = [f"{'kernel':36s} {'workgroups':>10s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'share':>6s}"]
+    for (nm, wg), a in agg.items():
+        out.append(f"{nm:36s} {wg:10d} {a[0]:6d} {a[1] / a[0] / 1e3:9.2f} {a[2] / 1e3:9.2f} {a[3] / 1e3:9.2f} "
+                   f"{100.0 * a[1] / total:5.1f}%")
+    return "\n".join(out)
+
+
+def pmc(d: str, prefix: str, counter: str) -> str:
+    rows = list(csv.DictReader(open(os.path.join(d, f"{prefix}_counter_collection.csv"))))
+    agg = collections.OrderedDict()
+    for r in rows:
+        if r.get("Counter_Name") != counter:
+            continue
+        name = r["Kernel_Name"]
+        if "helios" not in name:
+            continue
+        key = (_short(name), int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1))
+        a = agg.setdefault(key, [0, 0.0])
+        a[0] += 1
+        a[1] += float(r["Counter_Value"])
+    out = [f"{'kernel':36s} {'workgroups':>10s} {'dispatches':>10s} {counter + ' avg/dispatch':>26s}"]
+    for (nm, wg), a in agg.items():
+        out.append(f"{nm:36s} {wg:10d} {a[0]:10d} {a[1] / a[0]:26.1f}")
+    return "\n".join(out)
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 4 and sys.argv[1] == "trace":
+        print(trace(sys.argv[2], sys.argv[3]))
+    elif len(sys.argv) >= 5 and sys.argv[1] == "pmc":
+        print(pmc(sys.argv[2], sys.argv[3], sys.argv[4]))
+    else:
+        print(__doc__)
+        sys.exit(2)
