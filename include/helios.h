@@ -47,8 +47,10 @@ typedef enum {
     HELIOS_ECAPACITY = -2, /* an output did not fit its capacity (from helios_sync)  */
     HELIOS_EHIP = -3,      /* a HIP runtime call failed                              */
     HELIOS_ESTATE = -4,    /* call order: graph or cache not loaded yet              */
-    HELIOS_EDATA = -5      /* a node ID outside [0, N), or an order that is not a
+    HELIOS_EDATA = -5,     /* a node ID outside [0, N), or an order that is not a
                               permutation (from helios_sync)                         */
+    HELIOS_EINTERNAL = -6  /* a bounded device-side wait ran out (from helios_sync);
+                              the results of that call are invalid                   */
 } helios_status;
 
 #define HELIOS_MAX_HOPS 8

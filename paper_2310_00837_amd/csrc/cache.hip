@@ -53,9 +53,9 @@ struct PartitionArgs {
 
 __global__ __launch_bounds__(kBlock) void lookup_partition_kernel(PartitionArgs a) {
     __shared__ uint32_t s_wave_cnt[3][kWavesPerBlock];
-    __shared__ uint32_t s_ticket, s_agg[3], s_excl[3];
+    __shared__ uint32_t s_agg[3], s_excl[3];
     __shared__ ScanLookbackLds<3> s_look;
-    const uint32_t tile = scan_take_ticket(a.scan, &s_ticket);
+    const uint32_t tile = blockIdx.x;
     const int64_t n = a.n.get();
     const int64_t n_tiles = (n + kBlock - 1) / kBlock;
     if (n == 0 && tile == 0 && threadIdx.x == 0) {
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kBlock) void lookup_partition_kernel(PartitionArgs 
         for (int w = 0; w < kWavesPerBlock; ++w) t += s_wave_cnt[threadIdx.x][w];
         s_agg[threadIdx.x] = t;
     }
-    scan_chained_prefix<3>(a.scan, tile, s_agg, s_excl, &s_look);
+    scan_chained_prefix<3>(a.scan, tile, s_agg, s_excl, &s_look, a.err);
     if (tier >= 0) {
         uint32_t before = 0;
         for (int w = 0; w < wave_id(); ++w) before += s_wave_cnt[tier][w];

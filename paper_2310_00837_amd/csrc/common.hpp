@@ -12,6 +12,7 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 // device-side error codes, same values as helios_status
 constexpr int kErrCapacity = -2;
 constexpr int kErrData = -5;
+constexpr int kErrInternal = -6;
 
 // A count that is known either on the host (dev == nullptr: the count is
 // `host`) or only on the device (read from *dev by the kernel and clamped to

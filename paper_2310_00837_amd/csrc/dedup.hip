@@ -71,9 +71,9 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
                                                                int64_t* n_unique_dev, int64_t* n_unique_out,
                                                                ScanState scan, int32_t* err) {
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
-    __shared__ uint32_t s_ticket, s_agg[1], s_excl[1];
+    __shared__ uint32_t s_agg[1], s_excl[1];
     __shared__ ScanLookbackLds<1> s_look;
-    const uint32_t tile = scan_take_ticket(scan, &s_ticket);
+    const uint32_t tile = blockIdx.x;
     const int64_t n = n_in.get();
     const int64_t n_tiles = (n + kBlock - 1) / kBlock;
     if (n == 0 && tile == 0 && threadIdx.x == 0) {
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
     uint32_t tile_total;
     const uint32_t local = block_exclusive_scan(is_first, s_wave, tile_total);
     if (threadIdx.x == 0) s_agg[0] = tile_total;
-    scan_chained_prefix<1>(scan, tile, s_agg, s_excl, &s_look);
+    scan_chained_prefix<1>(scan, tile, s_agg, s_excl, &s_look, err);
     const int64_t at = static_cast<int64_t>(s_excl[0]) + local;
     if (is_first) {
         s.index_of_first[j] = static_cast<int32_t>(at);

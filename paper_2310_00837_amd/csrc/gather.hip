@@ -5,12 +5,17 @@
 // the pinned-host tier and the storage stand-in).  A group of L lanes owns one
 // row and moves it as 16-byte pieces, so a row is read and written as whole
 // contiguous lines; L is the smallest power of two that covers the row (at most
-// a wave).  Each group takes R list entries per step and issues all their loads
-// before the first store, which keeps R * L * 16 bytes in flight per group; the
-// grid is persistent (a few workgroups per CU, striding over the list) and the
+// a wave).  Each group takes R list entries per step (R = 1 or 2: measured
+// best; the 32 waves a CU holds supply the requests in flight) and issues all
+// their loads before the first store.  The grid strides over the list and the
 // count is read on the device, so no host round trip sits between the lookup
-// and the copy.  Source and destination are touched once: non-temporal
-// accesses keep them from displacing the graph and the cache map in L2.
+// and the copy.  For an HBM source the grid is up to 8192 workgroups, four
+// times what the chip holds at once, so the dispatcher balances the load; a
+// far (host-link) source is limited per CU by the requests a CU keeps in
+// flight, not by waves, so it takes one workgroup on each of 32-128 CUs, which
+// fills the link and leaves the other CUs alone.  Source and destination are
+// touched once: non-temporal accesses keep them from displacing the graph and
+// the cache map in L2.
 #include "kernels.hpp"
 
 namespace helios {
@@ -26,13 +31,47 @@ struct GatherArgs {
     Count n;
     int32_t chunks;         // 16-byte pieces per row
     chunk16* out;
-    uint64_t* clock;        // nullable: [2 * gridDim.x] first and last tick of every workgroup
+    unsigned long long* clock;   // nullable: [2 * gridDim.x] first and last tick of every workgroup
 };
 
-// Optional per-workgroup time stamps of the constant-rate device clock: the
-// host takes the earliest start and the latest end as the kernel's duration.
-__device__ __forceinline__ void stamp(uint64_t* clock, unsigned slot) {
-    if (clock && threadIdx.x == 0) clock[slot] = wall_clock64();
+// Optional timing: every workgroup stores its first and last tick of the
+// constant-rate device clock (clock[b], clock[gridDim.x + b]; plain stores, no
+// contention); clock_publish_kernel reduces them to {earliest start, latest
+// end} in pinned host memory.  Latest end minus earliest start is the kernel's
+// duration.
+__device__ __forceinline__ void stamp_start(unsigned long long* clock) {
+    if (clock && threadIdx.x == 0) clock[blockIdx.x] = wall_clock64();
+}
+__device__ __forceinline__ void stamp_end(unsigned long long* clock) {
+    if (clock) {
+        __syncthreads();
+        if (threadIdx.x == 0) clock[gridDim.x + blockIdx.x] = wall_clock64();
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void clock_publish_kernel(const unsigned long long* clock, unsigned n_blocks,
+                                                               unsigned long long* host_out) {
+    __shared__ unsigned long long s_lo[kBlock], s_hi[kBlock];
+    unsigned long long lo = ~0ull, hi = 0ull;
+    for (unsigned b = threadIdx.x; b < n_blocks; b += kBlock) {
+        const unsigned long long a = clock[b], z = clock[n_blocks + b];
+        lo = a < lo ? a : lo;
+        hi = z > hi ? z : hi;
+    }
+    s_lo[threadIdx.x] = lo;
+    s_hi[threadIdx.x] = hi;
+    __syncthreads();
+    for (int d = kBlock / 2; d > 0; d >>= 1) {
+        if (static_cast<int>(threadIdx.x) < d) {
+            if (s_lo[threadIdx.x + d] < s_lo[threadIdx.x]) s_lo[threadIdx.x] = s_lo[threadIdx.x + d];
+            if (s_hi[threadIdx.x + d] > s_hi[threadIdx.x]) s_hi[threadIdx.x] = s_hi[threadIdx.x + d];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        host_out[0] = s_lo[0];
+        host_out[1] = s_hi[0];
+    }
 }
 
 __device__ __forceinline__ chunk16 load16(const chunk16* p) {
@@ -46,7 +85,7 @@ __device__ __forceinline__ void store16(chunk16* p, const chunk16& v) {
 template <int L, int CPL, int R>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
     constexpr int kGroups = kBlock / L;
-    stamp(a.clock, blockIdx.x);
+    stamp_start(a.clock);
     const int64_t n = a.n.get();
     const int l = threadIdx.x % L;
     const int g = threadIdx.x / L;
@@ -81,15 +120,12 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
             }
         }
     }
-    if (a.clock) {
-        __syncthreads();
-        stamp(a.clock, gridDim.x + blockIdx.x);
-    }
+    stamp_end(a.clock);
 }
 
 // any row length: a wave per row, looping over the pieces
 __global__ __launch_bounds__(kBlock) void gather_rows_long_kernel(GatherArgs a) {
-    stamp(a.clock, blockIdx.x);
+    stamp_start(a.clock);
     const int64_t n = a.n.get();
     const int l = lane_id();
     const int64_t step = static_cast<int64_t>(gridDim.x) * kWavesPerBlock;
@@ -100,10 +136,7 @@ __global__ __launch_bounds__(kBlock) void gather_rows_long_kernel(GatherArgs a) 
         chunk16* o = a.out + d * a.chunks;
         for (int idx = l; idx < a.chunks; idx += kWave) store16(o + idx, load16(src + idx));
     }
-    if (a.clock) {
-        __syncthreads();
-        stamp(a.clock, gridDim.x + blockIdx.x);
-    }
+    stamp_end(a.clock);
 }
 
 // plain streaming copy of known size: the yardstick for hardware counters and for the
@@ -133,21 +166,29 @@ hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* ds
     return hipGetLastError();
 }
 
+hipError_t launch_clock_publish(hipStream_t stream, const uint64_t* clock, unsigned n_blocks, uint64_t* host_out) {
+    hipLaunchKernelGGL(clock_publish_kernel, dim3(1), dim3(kBlock), 0, stream,
+                       reinterpret_cast<const unsigned long long*>(clock), n_blocks,
+                       reinterpret_cast<unsigned long long*>(host_out));
+    return hipGetLastError();
+}
+
 hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
                               Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,
                               uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit) {
-    GatherArgs a{static_cast<const chunk16*>(table), pos, slot, n, row_bytes / 16, static_cast<chunk16*>(out), clock};
-    unsigned nb = 0;
-    // persistent grid: 8 workgroups per CU for HBM sources; a far (host-link) source
-    // saturates with far fewer requests in flight and leaves the CUs to other kernels
-    unsigned max_blocks = far_source ? 256u : kGatherMaxBlocks;
-    if (blocks_limit > 0) max_blocks = blocks_limit < kGatherMaxBlocks ? blocks_limit : kGatherMaxBlocks;
+    GatherArgs a{static_cast<const chunk16*>(table), pos, slot, n, row_bytes / 16, static_cast<chunk16*>(out),
+                 reinterpret_cast<unsigned long long*>(clock)};
     const int c = a.chunks;
-    if (c <= 4) nb = launch_shape<4, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 8) nb = launch_shape<8, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 16) nb = launch_shape<16, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 32) nb = launch_shape<32, 1, 4>(stream, a, n_max, max_blocks);
-    else if (c <= 64) nb = launch_shape<64, 1, 4>(stream, a, n_max, max_blocks);
+    // far source: one workgroup per CU on as many CUs as fill the link (more for short rows)
+    unsigned max_blocks = far_source ? (c <= 16 ? 128u : c <= 32 ? 64u : 32u) : kGatherMaxBlocks;
+    if (blocks_limit > 0) max_blocks = blocks_limit < kGatherMaxBlocks ? blocks_limit : kGatherMaxBlocks;
+    unsigned nb = 0;
+    if (c <= 4) nb = launch_shape<4, 1, 2>(stream, a, n_max, max_blocks);
+    else if (c <= 8) nb = launch_shape<8, 1, 2>(stream, a, n_max, max_blocks);
+    else if (c <= 16) nb = launch_shape<16, 1, 2>(stream, a, n_max, max_blocks);
+    else if (c <= 32 && far_source) nb = launch_shape<32, 1, 4>(stream, a, n_max, max_blocks);
+    else if (c <= 32) nb = launch_shape<32, 1, 1>(stream, a, n_max, max_blocks);
+    else if (c <= 64) nb = launch_shape<64, 1, 2>(stream, a, n_max, max_blocks);
     else if (c <= 128) nb = launch_shape<64, 2, 2>(stream, a, n_max, max_blocks);
     else if (c <= 256) nb = launch_shape<64, 4, 1>(stream, a, n_max, max_blocks);
     else {

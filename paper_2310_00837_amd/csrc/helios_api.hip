@@ -30,9 +30,9 @@ struct helios_ctx {
     bool timing = false, timed = false;
     hipEvent_t t_hbm[2] = {nullptr, nullptr}, t_host[2] = {nullptr, nullptr};
     bool timed_hbm = false, timed_host = false;
-    uint64_t* clock = nullptr;                 // device [2][2 * kGatherMaxBlocks] workgroup time stamps
-    uint64_t* clock_host = nullptr;            // pinned copy
+    uint64_t* clock = nullptr;                 // device [2][2 * kGatherMaxBlocks] workgroup ticks per tier copy
     unsigned clock_blocks[2] = {0, 0};
+    uint64_t* clock_host = nullptr;            // pinned [2][2], written by the publish kernel
     double clock_khz = 100000.0;
     unsigned hbm_blocks = 0, host_blocks = 0;  // 0 = the launcher's default
     bool serial_tiers = true;                  // the host-tier copy follows the HBM-tier copy (see helios_set_param)
@@ -59,7 +59,6 @@ struct helios_ctx {
     int32_t* cat = nullptr;
     unsigned long long* scan_status = nullptr;
     uint32_t scan_stride = 0;
-    uint32_t* scan_ticket = nullptr;
     uint32_t epoch = 0;
 };
 
@@ -153,7 +152,7 @@ int next_scan(helios_ctx* c, ScanState* out) {
         c->epoch = 0;
     }
     c->epoch += 1;
-    *out = ScanState{c->scan_status, c->scan_ticket, c->scan_stride, c->epoch};
+    *out = ScanState{c->scan_status, c->scan_stride, c->epoch};
     return HELIOS_OK;
 }
 
@@ -257,14 +256,23 @@ int gather_impl(helios_ctx* c, const int32_t* ids, Count n, void* out, int32_t* 
         HIP_TRY(c, launch_gather_rows(c->stream, c->hbm_table, lists.pos[0], lists.slot[0],
                                       Count{c->cnt + kCntTier + 0, n.host}, n.host, c->row_bytes, out, false,
                                       c->timing ? c->clock : nullptr, &c->clock_blocks[0], c->hbm_blocks));
-        if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream)); c->timed_hbm = true; }
+        if (c->timing) {
+            HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream));
+            HIP_TRY(c, launch_clock_publish(c->stream, c->clock, c->clock_blocks[0], c->clock_host));
+            c->timed_hbm = true;
+        }
     }
     if (do_host) {
         if (c->timing) HIP_TRY(c, hipEventRecord(c->t_host[0], host_stream));
         HIP_TRY(c, launch_gather_rows(host_stream, c->host_table, lists.pos[1], lists.slot[1],
                                       Count{c->cnt + kCntTier + 1, n.host}, n.host, c->row_bytes, out, true,
                                       c->timing ? c->clock + 2 * kGatherMaxBlocks : nullptr, &c->clock_blocks[1], c->host_blocks));
-        if (c->timing) { HIP_TRY(c, hipEventRecord(c->t_host[1], host_stream)); c->timed_host = true; }
+        if (c->timing) {
+            HIP_TRY(c, hipEventRecord(c->t_host[1], host_stream));
+            HIP_TRY(c, launch_clock_publish(host_stream, c->clock + 2 * kGatherMaxBlocks, c->clock_blocks[1],
+                                            c->clock_host + 2));
+            c->timed_host = true;
+        }
         if (fork) {
             HIP_TRY(c, hipEventRecord(c->ev_join, c->aux));
             HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
@@ -294,15 +302,14 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipEventCreate(&c->t_host[0]) == hipSuccess && hipEventCreate(&c->t_host[1]) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->err), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
-              hipMalloc(&c->scan_ticket, 64) == hipSuccess &&
               hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
-              hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4 * kGatherMaxBlocks, hipHostMallocDefault) == hipSuccess;
+              hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
+                            hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
     if (ok) {
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;
         c->err[0] = c->err[1] = 0;
         ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
-             hipMemsetAsync(c->scan_ticket, 0, 64, c->stream) == hipSuccess &&
              hipStreamSynchronize(c->stream) == hipSuccess;
     }
     if (!ok) {
@@ -321,7 +328,6 @@ int helios_destroy(helios_ctx* c) {
     free_scratch(c);
     (void)hipFree(c->rank);
     (void)hipFree(c->cnt);
-    (void)hipFree(c->scan_ticket);
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
     if (c->err) (void)hipHostFree(c->err);
@@ -348,7 +354,8 @@ int helios_sync(helios_ctx* c) {
     if (code != 0) {
         c->err[0] = 0;
         return fail(c, code, code == HELIOS_ECAPACITY ? "an output did not fit its capacity"
-                                                      : "a node ID outside [0, n_nodes), or an order that is not a permutation");
+                             : code == HELIOS_EINTERNAL ? "a workgroup gave up waiting for an earlier one (chained scan)"
+                             : "a node ID outside [0, n_nodes), or an order that is not a permutation");
     }
     return HELIOS_OK;
 }
@@ -553,17 +560,12 @@ int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms, float* hbm
     if (!c->timed_hbm && !c->timed_host) return HELIOS_OK;
     if (c->timed_hbm) HIP_TRY(c, hipEventSynchronize(c->t_hbm[1]));
     if (c->timed_host) HIP_TRY(c, hipEventSynchronize(c->t_host[1]));
-    HIP_TRY(c, hipMemcpy(c->clock_host, c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks, hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));          // the publish kernels have written the pinned words
     for (int t = 0; t < 2; ++t) {
         if (!(t == 0 ? c->timed_hbm : c->timed_host)) continue;
-        const uint64_t* k = c->clock_host + static_cast<size_t>(t) * 2 * kGatherMaxBlocks;
-        const unsigned nb = c->clock_blocks[t];
-        uint64_t lo = ~0ull, hi = 0;
-        for (unsigned b = 0; b < nb; ++b) {
-            if (k[b] < lo) lo = k[b];
-            if (k[nb + b] > hi) hi = k[nb + b];
-        }
-        const float ms = nb && hi >= lo ? static_cast<float>(static_cast<double>(hi - lo) / c->clock_khz) : 0.f;
+        const volatile uint64_t* k = c->clock_host + 2 * t;
+        const uint64_t lo = k[0], hi = k[1];
+        const float ms = hi >= lo && lo != ~0ull ? static_cast<float>(static_cast<double>(hi - lo) / c->clock_khz) : 0.f;
         float ev = 0.f;
         HIP_TRY(c, hipEventElapsedTime(&ev, t == 0 ? c->t_hbm[0] : c->t_host[0], t == 0 ? c->t_hbm[1] : c->t_host[1]));
         if (t == 0) { *hbm_ms = ms; if (hbm_event_ms) *hbm_event_ms = ev; }

@@ -62,12 +62,14 @@ hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count
 // ---- gather.hip
 // out[pos[k], :] = table[slot[k], :] for k < n; pos == nullptr means pos[k] = k.
 // `wide` selects the launch shape tuned for a far (host-link) source.
-// clock (nullable): device uint64[2 * kGatherMaxBlocks]; every workgroup stores its first and last
-// tick of the constant-rate device clock at [b] and [blocks + b]; *blocks_out = workgroups launched.
-constexpr unsigned kGatherMaxBlocks = 2048;
+// clock (nullable): device uint64[2 * kGatherMaxBlocks]; workgroup b stores its first and last tick of
+// the constant-rate device clock at [b] and [blocks + b]; *blocks_out = workgroups launched.
+// launch_clock_publish reduces them to {earliest start, latest end} in pinned host memory.
+constexpr unsigned kGatherMaxBlocks = 8192;
 hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
                               Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,
                               uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit /* 0 = default */);
+hipError_t launch_clock_publish(hipStream_t stream, const uint64_t* clock, unsigned n_blocks, uint64_t* host_out);
 
 // dst[0, bytes) = src[0, bytes) with the same 16-byte non-temporal accesses as the row copy
 hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* dst, int64_t bytes);

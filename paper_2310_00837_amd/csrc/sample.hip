@@ -49,11 +49,11 @@ template <int G>
 __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     constexpr int kGroups = kBlock / G;          // nodes per tile
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
-    __shared__ uint32_t s_ticket, s_agg[1], s_excl[1];
+    __shared__ uint32_t s_agg[1], s_excl[1];
     __shared__ ScanLookbackLds<1> s_look;
     __shared__ int32_t s_chosen[(G == kWave) ? kWavesPerBlock * kMaxFanout : 1];
 
-    const uint32_t tile = scan_take_ticket(a.scan, &s_ticket);
+    const uint32_t tile = blockIdx.x;
     const int64_t n = a.n_frontier.get();
     const int64_t n_tiles = (n + kGroups - 1) / kGroups;
     if (tile == 0 && threadIdx.x == 0) {
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     uint32_t tile_total;
     const uint32_t local = block_exclusive_scan(l == 0 ? static_cast<uint32_t>(cnt) : 0u, s_wave, tile_total);
     if (threadIdx.x == 0) s_agg[0] = tile_total;
-    scan_chained_prefix<1>(a.scan, tile, s_agg, s_excl, &s_look);
+    scan_chained_prefix<1>(a.scan, tile, s_agg, s_excl, &s_look, a.err);
     const int64_t tile_base = s_excl[0];
     const int64_t out = tile_base + __shfl(local, 0, G);
     if (l == 0 && i < n) a.indptr[i] = out;

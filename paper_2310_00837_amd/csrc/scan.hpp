@@ -1,12 +1,21 @@
 // Single-pass chained prefix sum across workgroups (decoupled look-back).
 //
-// Each workgroup owns one tile, taken in launch order from a ticket counter so
-// that every tile a workgroup waits for is already running.  A tile publishes
-// its aggregate, then looks back over its predecessors, 256 at a time, until it
-// meets one that has published a full inclusive prefix.  One 64-bit status word
-// per tile and counter holds {epoch:30, flag:2, value:32}; the epoch changes on
-// every launch, so a stale word reads as "not published" and the buffer never
-// needs clearing between launches.
+// Workgroup b owns tile b.  A tile publishes its aggregate, then looks back
+// over its predecessors, 256 at a time, until it meets one that has published a
+// full inclusive prefix.  One 64-bit status word per tile and counter holds
+// {epoch:30, flag:2, value:32}; the epoch changes on every launch, so a stale
+// word reads as "not published" and the buffer never needs clearing between
+// launches.
+//
+// A tile waits only for tiles with a smaller index.  Workgroups are started in
+// index order, so those are running or done, and nothing a tile does before it
+// publishes depends on another tile: the wait ends.  (A ticket counter would
+// make that order explicit, but every workgroup of a launch would then hit one
+// address with a device-scope atomic; measured on this part that serialises at
+// ~20 ns per workgroup and was most of the run time of every scan kernel.)
+// The wait is bounded all the same: after kScanSpinBudget polls a tile gives up,
+// records kErrInternal and carries on with a zero, so a launch always drains
+// and the caller gets an error instead of a hang.
 #pragma once
 #include "common.hpp"
 
@@ -14,7 +23,6 @@ namespace helios {
 
 struct ScanState {
     unsigned long long* status;   // [n_counters][stride]
-    uint32_t* ticket;             // one counter, zero between launches
     uint32_t stride;              // tiles the status rows have room for
     uint32_t epoch;               // 1 .. 2^30-1, new for every launch
 };
@@ -33,20 +41,7 @@ __device__ __forceinline__ unsigned long long scan_load(unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Tile index of this workgroup (launch order).  The workgroup that takes the
-// last ticket puts the counter back to zero for the next launch: by then every
-// other workgroup of this launch has taken its ticket.  Contains a barrier.
-__device__ __forceinline__ uint32_t scan_take_ticket(const ScanState& st, uint32_t* s_ticket) {
-    if (threadIdx.x == 0) {
-        uint32_t t = atomicAdd(st.ticket, 1u);
-        if (t == gridDim.x - 1) __hip_atomic_store(st.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *s_ticket = t;
-    }
-    __syncthreads();
-    uint32_t t = *s_ticket;
-    __syncthreads();
-    return t;
-}
+constexpr uint32_t kScanSpinBudget = 1u << 20;     // polls of one status word before giving up (about a second)
 
 // LDS the look-back needs: per counter and wave, {prefix seen, partial sum}.
 template <int NC>
@@ -67,7 +62,7 @@ struct ScanLookbackLds {
 // uniform control flow; tile < st.stride is the caller's duty.
 template <int NC>
 __device__ __forceinline__ void scan_chained_prefix(const ScanState& st, uint32_t tile, const uint32_t* s_agg,
-                                                    uint32_t* s_excl, ScanLookbackLds<NC>* lds) {
+                                                    uint32_t* s_excl, ScanLookbackLds<NC>* lds, int32_t* err) {
     __syncthreads();
     if (threadIdx.x < NC) {
         const uint32_t c = threadIdx.x;
@@ -94,13 +89,19 @@ __device__ __forceinline__ void scan_chained_prefix(const ScanState& st, uint32_
             if (idx >= 0) {
                 unsigned long long* p = st.status + static_cast<size_t>(c) * st.stride + idx;
                 unsigned long long w;
+                uint32_t budget = kScanSpinBudget;
                 do {
                     w = scan_load(p);
                     flag = static_cast<uint32_t>(w >> 32) & 3u;
                     if (static_cast<uint32_t>(w >> 34) != st.epoch) flag = 0;
                     if (flag == 0) __builtin_amdgcn_s_sleep(1);
-                } while (flag == 0);
+                } while (flag == 0 && --budget != 0);
                 val = static_cast<uint32_t>(w);
+                if (flag == 0) {                             // gave up: report, and let the launch drain
+                    raise(err, kErrInternal);
+                    flag = kFlagPrefix;
+                    val = 0;
+                }
             }
             const unsigned long long has_prefix = __ballot(flag == kFlagPrefix);
             uint32_t part;

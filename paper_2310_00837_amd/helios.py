@@ -16,11 +16,11 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libhelios.so")
 
-OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 MAX_HOPS, MAX_FANOUT = 8, 1024
 PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SERIAL_TIERS = 1, 2, 3
 _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
-          -5: "HELIOS_EDATA"}
+          -5: "HELIOS_EDATA", -6: "HELIOS_EINTERNAL"}
 
 # every symbol include/helios.h declares
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
