@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--hbm-frac", type=float, default=None, help="config 4 only: HBM-tier fraction of the sweep")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg")
+    ap.add_argument("--depth", type=int, default=3,
+                    help="mini-batches in flight during the timed region (each on its own context and stream)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
                     help="skip the host-link probe and use this rate (for runs under a counter profiler)")
@@ -106,65 +108,116 @@ def main() -> int:
     h.sync()
 
     B = min(sp.batch, g.n_nodes)
-    hops = helios.alloc_hops(B, sp.fanouts, dev)
-    cat_cap = B + sum(hb.flat.numel() for hb in hops)
-    h.reserve(cat_cap)
-    unique = torch.empty(cat_cap, dtype=torch.int32, device=dev)
-    inverse = torch.empty(cat_cap, dtype=torch.int32, device=dev)
-    out = torch.empty((cat_cap, sp.row_bytes), dtype=torch.uint8, device=dev)
-    mp = torch.empty(cat_cap, dtype=torch.int32, device=dev)
-    mi, ms = torch.empty_like(mp), torch.empty_like(mp)
-    sizes = torch.zeros(2 * len(sp.fanouts), dtype=torch.int64).pin_memory()
-    n_unique = torch.zeros(1, dtype=torch.int64).pin_memory()
-    stats = torch.zeros(4, dtype=torch.int64).pin_memory()
     n_batches = K + Wm
     seeds = [W.seed_batch(sp, g, b).to(dev) for b in range(n_batches)]
     rng_seeds = [W.batch_rng_seed(args.seed, b) for b in range(n_batches)]
 
-    def step(b: int, serve_misses: bool) -> None:
-        h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], hops, sizes, unique, inverse, n_unique, out, mp, mi, ms,
-                        stats)
-        if serve_misses:
-            h.gather_miss(mp, ms, mp.numel(), stats[3:4], out)
-        h.sync()
+    class Lane:
+        """One library context on its own stream with its own output buffers: one mini-batch in flight."""
 
-    # ---------------- timed region: K steps, S1-S5, gather kernels bracketed by HIP events
-    h.set_timing(True)
-    for b in range(Wm):
-        step(b, False)
-    acc = dict(hbm_ms=0.0, host_ms=0.0, hbm_ev_ms=0.0, host_ev_ms=0.0, hbm_rows=0, host_rows=0, miss=0, unique=0, raw=0)
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for b in range(Wm, Wm + K):
-        step(b, False)
-        a_ms, b_ms, a_ev, b_ev = h.gather_times()
-        acc["hbm_ms"] += a_ms
-        acc["host_ms"] += b_ms
-        acc["hbm_ev_ms"] += a_ev
-        acc["host_ev_ms"] += b_ev
-        acc["hbm_rows"] += int(stats[1])
-        acc["host_rows"] += int(stats[2])
-        acc["miss"] += int(stats[3])
-        acc["unique"] += int(stats[0])
-        acc["raw"] += int(sizes[1::2].sum())
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    h.set_timing(False)
+        def __init__(self, ctx, stream):
+            self.h, self.stream = ctx, stream
+            self.hops = helios.alloc_hops(B, sp.fanouts, dev)
+            cap = B + sum(hb.flat.numel() for hb in self.hops)
+            self.h.reserve(cap)
+            self.unique = torch.empty(cap, dtype=torch.int32, device=dev)
+            self.inverse = torch.empty(cap, dtype=torch.int32, device=dev)
+            self.out = torch.empty((cap, sp.row_bytes), dtype=torch.uint8, device=dev)
+            self.mp = torch.empty(cap, dtype=torch.int32, device=dev)
+            self.mi, self.ms = torch.empty_like(self.mp), torch.empty_like(self.mp)
+            self.sizes = torch.zeros(2 * len(sp.fanouts), dtype=torch.int64).pin_memory()
+            self.n_unique = torch.zeros(1, dtype=torch.int64).pin_memory()
+            self.stats = torch.zeros(4, dtype=torch.int64).pin_memory()
 
-    # same K steps once more with the miss list served from the stand-in (reported, not `value`)
+        def launch(self, b: int, serve_misses: bool) -> None:
+            self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], self.hops, self.sizes, self.unique, self.inverse,
+                                 self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
+            if serve_misses:
+                self.h.gather_miss(self.mp, self.ms, self.mp.numel(), self.stats[3:4], self.out)
+
+    lanes = [Lane(h, None)]
+    for _ in range(1, max(1, args.depth)):
+        st = torch.cuda.Stream(device=dev)
+        ctx = helios.Helios(0, stream=st)
+        ctx.csr_load(offsets, indices)
+        ctx.cache_build(order, tiers.n_hbm, tiers.n_host, sp.row_bytes, tiers.hbm, tiers.host, tiers.standin)
+        ctx.sync()
+        lanes.append(Lane(ctx, st))
     torch.cuda.synchronize()
-    t_s6 = time.perf_counter()
-    for b in range(Wm, Wm + K):
-        step(b, True)
-    torch.cuda.synchronize()
-    elapsed_s6 = time.perf_counter() - t_s6
+
+    def run_region(first: int, count: int, depth: int, timing: int, serve_misses: bool):
+        """`count` whole steps with up to `depth` mini-batches in flight (lane b % depth); a lane's
+        previous batch is waited for (helios_sync) before the lane is reused.  Returns (seconds, sums)."""
+        acc = dict(hbm_ms=0.0, host_ms=0.0, hbm_ev_ms=0.0, host_ev_ms=0.0, hbm_rows=0, host_rows=0, miss=0, unique=0,
+                   raw=0)
+        use = lanes[:depth]
+        for ln in use:
+            ln.h.set_timing(timing)
+
+        def retire(ln):
+            ln.h.sync()
+            if timing:
+                a_ms, b_ms, a_ev, b_ev = ln.h.gather_times()
+                acc["hbm_ms"] += a_ms
+                acc["host_ms"] += b_ms
+                acc["hbm_ev_ms"] += a_ev
+                acc["host_ev_ms"] += b_ev
+            acc["hbm_rows"] += int(ln.stats[1])
+            acc["host_rows"] += int(ln.stats[2])
+            acc["miss"] += int(ln.stats[3])
+            acc["unique"] += int(ln.stats[0])
+            acc["raw"] += int(ln.sizes[1::2].sum())
+
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for k in range(count):
+            ln = use[k % depth]
+            if k >= depth:
+                retire(ln)
+            ln.launch(first + k, serve_misses)
+        for k in range(max(0, count - depth), count):
+            retire(use[k % depth])
+        torch.cuda.synchronize()
+        seconds = time.perf_counter() - t_begin
+        for ln in use:
+            ln.h.set_timing(0)
+        return seconds, acc
+
+    # ---------------- timed region: W warm-up steps, then K whole steps (S1-S5) with `depth` mini-batches in
+    # flight; the row-copy kernels are timed with the device clock inside the same region
+    D = len(lanes)
+    run_region(0, Wm, D, 1, False)
+    elapsed, acc = run_region(Wm, K, D, 1, False)
+    # the same K steps: one batch in flight; with the miss list served (S6); with HIP events around the copies
+    run_region(0, Wm, 1, 1, False)
+    one_elapsed, one_acc = run_region(Wm, K, 1, 1, False)
+    elapsed_s6, _ = run_region(Wm, K, D, 0, True)
+    _, ev_acc = run_region(Wm, min(K, 50), 1, 2, False)
 
     rb = sp.row_bytes
-    hbm_bytes = 2.0 * acc["hbm_rows"] * rb                 # every row is read from HBM and written to HBM
-    host_bytes = 1.0 * acc["host_rows"] * rb               # bytes that cross the host link
-    hbm_gbs = hbm_bytes / (acc["hbm_ms"] * 1e-3) / 1e9 if acc["hbm_ms"] > 0 else 0.0
-    host_gbs = host_bytes / (acc["host_ms"] * 1e-3) / 1e9 if acc["host_ms"] > 0 else 0.0
-    dominant_host = acc["host_ms"] > acc["hbm_ms"]
+
+    def rates(a):
+        hbm = 2.0 * a["hbm_rows"] * rb / (a["hbm_ms"] * 1e-3) / 1e9 if a["hbm_ms"] > 0 else 0.0     # read + write
+        host = 1.0 * a["host_rows"] * rb / (a["host_ms"] * 1e-3) / 1e9 if a["host_ms"] > 0 else 0.0  # bytes over the link
+        return hbm, host
+
+    hbm_gbs, host_gbs = rates(one_acc)              # kernel quality: nothing else runs beside the copies
+    ov_hbm_gbs, ov_host_gbs = rates(acc)            # the same kernels inside the pipelined region
+    dominant_host = one_acc["host_ms"] > one_acc["hbm_ms"]
+    link_whole_run = 1.0 * acc["host_rows"] * rb / elapsed / 1e9
+
+    # HBM bytes per launch of the HBM-tier copy from the committed counter runs (two rocprofv3 --pmc runs,
+    # scaled by the calibration copy); only for the workload they were taken on
+    traffic = None
+    names = {1: "hbm_traffic_cfg1_medium.txt"}
+    tpath = os.path.join(ROOT, "profiles", names.get(args.config, "none"))
+    if os.path.exists(tpath) and args.hbm_frac is None:
+        for line in open(tpath):
+            if line.startswith("TRAFFIC_JSON:"):
+                try:
+                    traffic = json.loads(line[len("TRAFFIC_JSON:"):])
+                except Exception:
+                    traffic = None
 
     result = {
         "metric": "sampled mini-batches/sec; feature gather GB/s vs HBM and host-link peak",
@@ -178,21 +231,35 @@ def main() -> int:
         "config": {"workload": f"BASELINE.json configs[{args.config}] {sp.name}", "n_nodes": g.n_nodes,
                    "n_edges": g.n_edges, "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
                    "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed,
-                   "step": "helios_prepare_batch (sample, dedup, lookup, HBM+host gather, miss list) + helios_sync"},
+                   "step": "helios_prepare_batch (sample, dedup, lookup, HBM+host gather, miss list) + helios_sync, "
+                           "%d mini-batches in flight, each on its own context and stream" % D},
         "roofline": {"kernel": "gather_rows_kernel (HBM tier)", "bound": "hbm", "achieved": hbm_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "avg_kernel_us": acc["hbm_ms"] / K * 1e3, "avg_event_us": acc["hbm_ev_ms"] / K * 1e3,
-                     "timer": "device clock, earliest workgroup start to latest end", "rows_per_launch": acc["hbm_rows"] / K,
-                     "bytes_per_row": 2 * rb, "plain_copy_GBs_on_this_box": copy_gbs},
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "avg_kernel_us": one_acc["hbm_ms"] / K * 1e3,
+                     "avg_event_us": ev_acc["hbm_ev_ms"] / min(K, 50) * 1e3,
+                     "region": "the K timed steps run with one mini-batch in flight (as a kernel trace sees them)",
+                     "timer": "device clock, earliest workgroup start to latest end; avg_event_us: HIP events on the kernel's stream",
+                     "rows_per_launch": one_acc["hbm_rows"] / K, "bytes_per_row": 2 * rb,
+                     "plain_copy_GBs_on_this_box": copy_gbs,
+                     "while_overlapped": {"achieved": ov_hbm_gbs, "frac": ov_hbm_gbs / HBM_PEAK_GBS,
+                                          "avg_kernel_us": acc["hbm_ms"] / K * 1e3,
+                                          "note": "same kernel inside the %d-in-flight region, beside other batches' host-link copies" % D}},
         "roofline_host_link": {"kernel": "gather_rows_kernel (host tier)", "bound": "host_link",
                                "achieved": host_gbs, "peak": link_gbs, "unit": "GB/s",
                                "frac": host_gbs / link_gbs if link_gbs > 0 else None,
                                "peak_source": "given on the command line" if args.link_gbs else "pinned H2D copy measured in this run",
-                               "avg_kernel_us": acc["host_ms"] / K * 1e3, "avg_event_us": acc["host_ev_ms"] / K * 1e3,
-                               "rows_per_launch": acc["host_rows"] / K,
-                               "bytes_per_row": rb},
+                               "avg_kernel_us": one_acc["host_ms"] / K * 1e3,
+                               "avg_event_us": ev_acc["host_ev_ms"] / min(K, 50) * 1e3,
+                               "rows_per_launch": one_acc["host_rows"] / K, "bytes_per_row": rb,
+                               "while_overlapped": {"link_GBs_over_the_whole_region": link_whole_run,
+                                                    "frac": link_whole_run / link_gbs if link_gbs > 0 else None,
+                                                    "per_kernel_GBs": ov_host_gbs,
+                                                    "note": "host-tier bytes of all K steps / wall time of the %d-in-flight region" % D}},
         "dominant_kernel": "host-tier gather" if dominant_host else "HBM-tier gather",
         "with_miss_service": {"value": K / elapsed_s6, "ms_per_step": elapsed_s6 / K * 1e3},
+        "batches_in_flight": D,
+        "one_batch_in_flight": {"value": K / one_elapsed, "ms_per_step": one_elapsed / K * 1e3,
+                                "note": "the same K steps with helios_sync after every batch"},
         "per_batch": {"raw_sampled_ids": acc["raw"] / K, "unique_ids": acc["unique"] / K,
                       "hit_ratio_hbm": acc["hbm_rows"] / max(acc["unique"], 1),
                       "hit_ratio_host": acc["host_rows"] / max(acc["unique"], 1),
@@ -229,7 +296,8 @@ def main() -> int:
                                   "kind": "oracle",
                                   "sample": f"{done} of the {K} timed batches (sample, dedup, lookup, gather, miss list), "
                                             f"{cpu_elapsed:.1f} s"}
-    h.close()
+    for ln in lanes:
+        ln.h.close()
     print(json.dumps(result))
     return 0
 

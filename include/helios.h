@@ -213,15 +213,16 @@ typedef enum {
 int helios_set_param(helios_ctx *ctx, int param, int64_t value);
 
 /* Timing of the two row-copy kernels (HBM tier, host tier) of the last
- * helios_gather / helios_prepare_batch on this context.  When enabled, every
+ * helios_gather / helios_prepare_batch on this context.  Level 1: every
  * workgroup of those kernels stores its first and last tick of the GPU's
- * constant-rate clock; helios_gather_times waits for the kernels and returns,
+ * constant-rate clock; helios_gather_times waits for the stream and returns,
  * per kernel, latest end minus earliest start in milliseconds (hbm_ms,
- * host_ms: the kernel's own duration, as a kernel trace reports it), and the
- * time between HIP events recorded around the launch on the kernel's stream
- * (hbm_event_ms, host_event_ms, nullable: these also contain launch gaps).
- * A tier that launched nothing reports 0. */
-int helios_set_timing(helios_ctx *ctx, int enabled);
+ * host_ms: the kernel's own duration, as a kernel trace reports it).  Level 2
+ * also records HIP events around the launch on the kernel's stream and
+ * returns the time between them (hbm_event_ms, host_event_ms, nullable; 0 at
+ * level 1): these also contain launch gaps.  Level 0 turns timing off.  A
+ * tier that launched nothing reports 0. */
+int helios_set_timing(helios_ctx *ctx, int level);
 int helios_gather_times(helios_ctx *ctx, float *hbm_ms, float *host_ms,
                         float *hbm_event_ms, float *host_event_ms);
 

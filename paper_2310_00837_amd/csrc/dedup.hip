@@ -34,13 +34,26 @@ __global__ __launch_bounds__(kBlock) void dedup_clear_kernel(unsigned long long*
     for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n_slots; i += gridDim.x * kBlock) table[i] = kEmpty;
 }
 
-__global__ __launch_bounds__(kBlock) void dedup_insert_kernel(const int32_t* __restrict__ ids, Count n_in, int64_t n_nodes,
-                                                              DedupScratch s, int32_t* err) {
-    const int64_t n = n_in.get();
+// The input is the concatenation of up to HELIOS_KERNELS_MAX_SEG segments whose lengths may be known
+// only on the device ([seeds | flat_0 | ...] for the whole-path call, one segment otherwise).  If
+// cat_out is given the concatenation is also written out, for the later passes to index.
+__global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int32_t* cat_out, int64_t* n_total_dev,
+                                                              int64_t n_nodes, DedupScratch s, int32_t* err) {
+    int64_t start[HELIOS_KERNELS_MAX_SEG + 1];
+    start[0] = 0;
+#pragma unroll
+    for (int k = 0; k < HELIOS_KERNELS_MAX_SEG; ++k) start[k + 1] = start[k] + (k < in.n_seg ? in.len[k].get() : 0);
+    const int64_t n = start[HELIOS_KERNELS_MAX_SEG];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_total_dev = n;
     const uint32_t mask = s.n_slots - 1;
     for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < n;
          j += static_cast<int64_t>(gridDim.x) * kBlock) {
-        const int32_t id = ids[j];
+        int k = 0;
+#pragma unroll
+        for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
+            if (q < in.n_seg && j >= start[q]) k = q;
+        const int32_t id = in.src[k][j - start[k]];
+        if (cat_out) cat_out[j] = id;
         if (id < 0 || static_cast<int64_t>(id) >= n_nodes) {
             raise(err, kErrData);
             s.slot_of[j] = -1;
@@ -119,23 +132,6 @@ __global__ __launch_bounds__(kBlock) void dedup_inverse_kernel(Count n_in, Dedup
     }
 }
 
-__global__ __launch_bounds__(kBlock) void concat_kernel(ConcatArgs a, int32_t* dst, int64_t* n_total_dev) {
-    int64_t start[HELIOS_KERNELS_MAX_SEG + 1];
-    start[0] = 0;
-#pragma unroll
-    for (int k = 0; k < HELIOS_KERNELS_MAX_SEG; ++k) start[k + 1] = start[k] + (k < a.n_seg ? a.len[k].get() : 0);
-    const int64_t total = start[HELIOS_KERNELS_MAX_SEG];
-    if (blockIdx.x == 0 && threadIdx.x == 0) *n_total_dev = total;
-    for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < total;
-         j += static_cast<int64_t>(gridDim.x) * kBlock) {
-        int k = 0;
-#pragma unroll
-        for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
-            if (q < a.n_seg && j >= start[q]) k = q;
-        dst[j] = a.src[k][j - start[k]];
-    }
-}
-
 unsigned grid_for(int64_t n_max, unsigned cap_blocks) {
     int64_t b = (n_max + kBlock - 1) / kBlock;
     if (b < 1) b = 1;
@@ -145,23 +141,22 @@ unsigned grid_for(int64_t n_max, unsigned cap_blocks) {
 
 }  // namespace
 
-hipError_t launch_dedup(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
-                        const DedupScratch& s, int32_t* unique, int64_t unique_cap, int32_t* inverse,
+hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat,
+                        int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
+                        bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
                         int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err) {
     const dim3 block(kBlock);
-    hipLaunchKernelGGL(dedup_clear_kernel, dim3(grid_for(s.n_slots, 2048)), block, 0, stream, s.table, s.n_slots);
-    hipLaunchKernelGGL(dedup_insert_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, ids, n, n_nodes, s, err);
+    if (!table_is_clear)
+        hipLaunchKernelGGL(dedup_clear_kernel, dim3(grid_for(s.n_slots, 2048)), block, 0, stream, s.table, s.n_slots);
+    hipLaunchKernelGGL(dedup_insert_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, in, cat_out, n_total_dev,
+                       n_nodes, s, err);
+    const Count n{n_total_dev, n_max};
     int64_t tiles = (n_max + kBlock - 1) / kBlock;
     if (tiles < 1) tiles = 1;
-    hipLaunchKernelGGL(dedup_compact_kernel, dim3(static_cast<unsigned>(tiles)), block, 0, stream, ids, n, s, unique,
+    hipLaunchKernelGGL(dedup_compact_kernel, dim3(static_cast<unsigned>(tiles)), block, 0, stream, ids_flat, n, s, unique,
                        unique_cap, n_unique_dev, n_unique_out, scan, err);
     if (inverse)
         hipLaunchKernelGGL(dedup_inverse_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, n, s, inverse);
-    return hipGetLastError();
-}
-
-hipError_t launch_concat(hipStream_t stream, const ConcatArgs& a, int64_t n_max, int32_t* dst, int64_t* n_total_dev) {
-    hipLaunchKernelGGL(concat_kernel, dim3(grid_for(n_max, 4096)), dim3(kBlock), 0, stream, a, dst, n_total_dev);
     return hipGetLastError();
 }
 

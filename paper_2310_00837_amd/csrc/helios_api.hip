@@ -27,7 +27,7 @@ struct helios_ctx {
     hipStream_t stream = nullptr;
     hipStream_t aux = nullptr;                 // host-tier row copies run here, beside the HBM-tier ones
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    bool timing = false, timed = false;
+    int timing = 0;                            // 0 off, 1 device clock, 2 device clock + HIP events
     hipEvent_t t_hbm[2] = {nullptr, nullptr}, t_host[2] = {nullptr, nullptr};
     bool timed_hbm = false, timed_host = false;
     uint64_t* clock = nullptr;                 // device [2][2 * kGatherMaxBlocks] workgroup ticks per tier copy
@@ -199,34 +199,54 @@ int plan_hops(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_
     return HELIOS_OK;
 }
 
-int dedup_impl(helios_ctx* c, const int32_t* ids, Count n, int32_t* unique, int64_t unique_cap, int32_t* inverse,
-               int64_t* n_unique_dev, int64_t* n_unique_out) {
+// slots of the hash table a de-duplication of up to n_max IDs uses (no more than it needs: a smaller
+// table is cheaper to clear and stays in cache)
+uint32_t dedup_slots(const helios_ctx* c, int64_t n_max) {
+    const uint32_t want = pow2_at_least(2 * n_max);
+    return want < c->dd.n_slots ? want : c->dd.n_slots;
+}
+
+int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat, int32_t* cat_out,
+               bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse, int64_t* n_unique_dev,
+               int64_t* n_unique_out) {
     ScanState scan;
     int rc = next_scan(c, &scan);
     if (rc) return rc;
     DedupScratch s = c->dd;
-    s.n_slots = pow2_at_least(2 * n.host);          // a table no larger than this call needs
-    if (s.n_slots > c->dd.n_slots) s.n_slots = c->dd.n_slots;
-    HIP_TRY(c, launch_dedup(c->stream, ids, n, n.host, c->g.n_nodes, s, unique, unique_cap, inverse, n_unique_dev,
-                            n_unique_out, scan, c->err));
+    s.n_slots = dedup_slots(c, n_max);
+    HIP_TRY(c, launch_dedup(c->stream, in, n_max, ids_flat, cat_out, c->cnt + kCntCat, c->g.n_nodes, s, table_is_clear,
+                            unique, unique_cap, inverse, n_unique_dev, n_unique_out, scan, c->err));
     return HELIOS_OK;
 }
 
+ConcatArgs one_segment(const int32_t* ids, Count n) {
+    ConcatArgs in{};
+    in.n_seg = 1;
+    in.src[0] = ids;
+    in.len[0] = n;
+    return in;
+}
+
+// final_dedup_max > 0: the last hop also empties the hash table for a de-duplication of that many IDs
 int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
-                uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p) {
-    if (n_seeds > 0)
-        HIP_TRY(c, hipMemcpyAsync(hops[0].frontier, seeds, sizeof(int32_t) * n_seeds, hipMemcpyDeviceToDevice, c->stream));
+                uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p,
+                int64_t final_dedup_max) {
     Count nf{nullptr, n_seeds};
     for (int h = 0; h < n_hops; ++h) {
         ScanState scan;
         int rc = next_scan(c, &scan);
         if (rc) return rc;
-        HIP_TRY(c, launch_sample_hop(c->stream, c->g, hops[h].frontier, nf, p.frontier_max[h], fanouts[h], h, rng_seed,
-                                     hops[h].indptr, hops[h].flat, hops[h].flat_cap, c->cnt + kCntFlat + h,
-                                     sizes ? sizes + 2 * h : nullptr, scan, c->err));
-        if (h + 1 < n_hops) {
-            rc = dedup_impl(c, hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}, hops[h + 1].frontier,
-                            hops[h + 1].frontier_cap, nullptr, c->cnt + kCntFrontier + h + 1, nullptr);
+        const bool last = h + 1 == n_hops;
+        const int64_t next_dedup = last ? final_dedup_max : p.flat_max[h];
+        const uint32_t clear_slots = next_dedup > 0 || !last ? dedup_slots(c, next_dedup) : 0u;
+        HIP_TRY(c, launch_sample_hop(c->stream, c->g, h == 0 ? seeds : hops[h].frontier, hops[h].frontier, nf,
+                                     p.frontier_max[h], fanouts[h], h, rng_seed, hops[h].indptr, hops[h].flat,
+                                     hops[h].flat_cap, c->cnt + kCntFlat + h, sizes ? sizes + 2 * h : nullptr,
+                                     clear_slots ? c->dd.table : nullptr, clear_slots, scan, c->err));
+        if (!last) {
+            rc = dedup_impl(c, one_segment(hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}), p.flat_max[h],
+                            hops[h].flat, nullptr, true, hops[h + 1].frontier, hops[h + 1].frontier_cap, nullptr,
+                            c->cnt + kCntFrontier + h + 1, nullptr);
             if (rc) return rc;
             nf = Count{c->cnt + kCntFrontier + h + 1, p.frontier_max[h + 1]};
         }
@@ -252,23 +272,23 @@ int gather_impl(helios_ctx* c, const int32_t* ids, Count n, void* out, int32_t* 
         HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_fork, 0));
     }
     if (do_hbm) {
-        if (c->timing) HIP_TRY(c, hipEventRecord(c->t_hbm[0], c->stream));
+        if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_hbm[0], c->stream));
         HIP_TRY(c, launch_gather_rows(c->stream, c->hbm_table, lists.pos[0], lists.slot[0],
                                       Count{c->cnt + kCntTier + 0, n.host}, n.host, c->row_bytes, out, false,
                                       c->timing ? c->clock : nullptr, &c->clock_blocks[0], c->hbm_blocks));
         if (c->timing) {
-            HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream));
+            if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream));
             HIP_TRY(c, launch_clock_publish(c->stream, c->clock, c->clock_blocks[0], c->clock_host));
             c->timed_hbm = true;
         }
     }
     if (do_host) {
-        if (c->timing) HIP_TRY(c, hipEventRecord(c->t_host[0], host_stream));
+        if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_host[0], host_stream));
         HIP_TRY(c, launch_gather_rows(host_stream, c->host_table, lists.pos[1], lists.slot[1],
                                       Count{c->cnt + kCntTier + 1, n.host}, n.host, c->row_bytes, out, true,
                                       c->timing ? c->clock + 2 * kGatherMaxBlocks : nullptr, &c->clock_blocks[1], c->host_blocks));
         if (c->timing) {
-            HIP_TRY(c, hipEventRecord(c->t_host[1], host_stream));
+            if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_host[1], host_stream));
             HIP_TRY(c, launch_clock_publish(host_stream, c->clock + 2 * kGatherMaxBlocks, c->clock_blocks[1],
                                             c->clock_host + 2));
             c->timed_host = true;
@@ -427,7 +447,7 @@ int helios_sample(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const in
     DeviceGuard guard(c->device);
     rc = ensure_capacity(c, p.ids_max);
     if (rc) return rc;
-    return sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p);
+    return sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, 0);
 }
 
 int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* unique, int64_t unique_cap,
@@ -439,7 +459,8 @@ int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* uniq
     DeviceGuard guard(c->device);
     int rc = ensure_capacity(c, n_ids);
     if (rc) return rc;
-    return dedup_impl(c, ids, Count{nullptr, n_ids}, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique);
+    return dedup_impl(c, one_segment(ids, Count{nullptr, n_ids}), n_ids, ids, nullptr, false, unique, unique_cap, inverse,
+                      c->cnt + kCntUnique, n_unique);
 }
 
 int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, int32_t* miss_pos, int32_t* miss_id,
@@ -486,7 +507,7 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     DeviceGuard guard(c->device);
     rc = ensure_capacity(c, p.ids_max);
     if (rc) return rc;
-    rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p);
+    rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, p.cat_max > 0 ? p.cat_max : 1);
     if (rc) return rc;
     ConcatArgs cat{};
     cat.n_seg = n_hops + 1;
@@ -496,9 +517,7 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
         cat.src[h + 1] = hops[h].flat;
         cat.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
     }
-    HIP_TRY(c, launch_concat(c->stream, cat, p.cat_max, c->cat, c->cnt + kCntCat));
-    rc = dedup_impl(c, c->cat, Count{c->cnt + kCntCat, p.cat_max}, unique, unique_cap, inverse, c->cnt + kCntUnique,
-                    n_unique);
+    rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique);
     if (rc) return rc;
     const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
     return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
@@ -546,7 +565,7 @@ int helios_set_param(helios_ctx* c, int param, int64_t value) {
 
 int helios_set_timing(helios_ctx* c, int enabled) {
     if (!c) return HELIOS_EINVAL;
-    c->timing = enabled != 0;
+    c->timing = enabled < 0 ? 0 : enabled > 2 ? 2 : enabled;
     c->timed_hbm = c->timed_host = false;
     return HELIOS_OK;
 }
@@ -558,8 +577,6 @@ int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms, float* hbm
     if (hbm_event_ms) *hbm_event_ms = 0.f;
     if (host_event_ms) *host_event_ms = 0.f;
     if (!c->timed_hbm && !c->timed_host) return HELIOS_OK;
-    if (c->timed_hbm) HIP_TRY(c, hipEventSynchronize(c->t_hbm[1]));
-    if (c->timed_host) HIP_TRY(c, hipEventSynchronize(c->t_host[1]));
     HIP_TRY(c, hipStreamSynchronize(c->stream));          // the publish kernels have written the pinned words
     for (int t = 0; t < 2; ++t) {
         if (!(t == 0 ? c->timed_hbm : c->timed_host)) continue;
@@ -567,7 +584,8 @@ int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms, float* hbm
         const uint64_t lo = k[0], hi = k[1];
         const float ms = hi >= lo && lo != ~0ull ? static_cast<float>(static_cast<double>(hi - lo) / c->clock_khz) : 0.f;
         float ev = 0.f;
-        HIP_TRY(c, hipEventElapsedTime(&ev, t == 0 ? c->t_hbm[0] : c->t_host[0], t == 0 ? c->t_hbm[1] : c->t_host[1]));
+        if (c->timing > 1)
+            HIP_TRY(c, hipEventElapsedTime(&ev, t == 0 ? c->t_hbm[0] : c->t_host[0], t == 0 ? c->t_hbm[1] : c->t_host[1]));
         if (t == 0) { *hbm_ms = ms; if (hbm_event_ms) *hbm_event_ms = ev; }
         else { *host_ms = ms; if (host_event_ms) *host_event_ms = ev; }
     }

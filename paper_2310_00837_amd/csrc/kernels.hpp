@@ -20,30 +20,36 @@ struct CsrView {
 // lanes that share one node, and workgroups (= scan tiles) a hop needs
 int sample_group_lanes(int32_t fanout);
 int64_t sample_hop_tiles(int64_t n_frontier_max, int32_t fanout);
-hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, Count n_frontier,
-                             int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
+// frontier_out (nullable, may equal frontier_in) receives a copy of the frontier; clear_table
+// (nullable) is set to all ones over clear_slots words on the way (the hash table of the
+// de-duplication that follows the hop).
+hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier_in, int32_t* frontier_out,
+                             Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
                              int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
-                             int64_t* size_out, const ScanState& scan, int32_t* err);
+                             int64_t* size_out, unsigned long long* clear_table, uint32_t clear_slots,
+                             const ScanState& scan, int32_t* err);
 
 // ---- dedup.hip
 struct DedupScratch {
-    unsigned long long* table;   // n_slots entries {id:32, first position:32}
+    unsigned long long* table;   // n_slots entries {id:32, first position:32}; all ones = empty
     uint32_t n_slots;            // power of two
     int32_t* slot_of;            // [n] table slot of every input position
     int32_t* index_of_first;     // [n] index in `unique` of a first occurrence
 };
-hipError_t launch_dedup(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
-                        const DedupScratch& s, int32_t* unique, int64_t unique_cap, int32_t* inverse,
-                        int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err);
-
-// Concatenate K+1 segments whose lengths are only known on the device:
-// dst = [seg0 | seg1 | ...], total length to *n_total_dev.
+// Up to HELIOS_KERNELS_MAX_SEG segments whose lengths may be known only on the device.
 struct ConcatArgs {
     const int32_t* src[HELIOS_KERNELS_MAX_SEG];
     Count len[HELIOS_KERNELS_MAX_SEG];
     int n_seg;
 };
-hipError_t launch_concat(hipStream_t stream, const ConcatArgs& a, int64_t n_max, int32_t* dst, int64_t* n_total_dev);
+// De-duplicates the concatenation of the segments of `in` (n_max bounds its length).  ids_flat is
+// where the concatenation can be indexed: the single segment itself, or cat_out, which the first
+// pass then fills.  *n_total_dev receives the input length.  table_is_clear: an earlier kernel on the
+// stream has already set s.table[0, s.n_slots) to all ones.
+hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat,
+                        int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
+                        bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
+                        int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err);
 
 // ---- cache.hip
 hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n_nodes, int32_t* rank, int32_t* err);

@@ -32,6 +32,7 @@ struct HopArgs {
     const int32_t* indices;
     int64_t n_nodes;
     const int32_t* frontier;
+    int32_t* frontier_out;
     Count n_frontier;
     int32_t fanout;
     int32_t hop;
@@ -41,6 +42,8 @@ struct HopArgs {
     int64_t flat_cap;
     int64_t* n_flat_dev;
     int64_t* size_out;
+    unsigned long long* clear_table;
+    uint32_t clear_slots;
     ScanState scan;
     int32_t* err;
 };
@@ -56,6 +59,8 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     const uint32_t tile = blockIdx.x;
     const int64_t n = a.n_frontier.get();
     const int64_t n_tiles = (n + kGroups - 1) / kGroups;
+    // side job: empty the hash table of the de-duplication that follows this hop
+    for (uint32_t w = blockIdx.x * kBlock + threadIdx.x; w < a.clear_slots; w += gridDim.x * kBlock) a.clear_table[w] = ~0ull;
     if (tile == 0 && threadIdx.x == 0) {
         if (a.size_out) a.size_out[0] = n;
         if (n == 0) {                            // empty frontier: empty hop
@@ -76,6 +81,7 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     int64_t base = 0;
     if (i < n) {
         v = a.frontier[i];
+        if (l == 0 && a.frontier_out && a.frontier_out != a.frontier) a.frontier_out[i] = v;
         if (v < 0 || static_cast<int64_t>(v) >= a.n_nodes) {
             raise(a.err, kErrData);
         } else {
@@ -178,12 +184,13 @@ int64_t sample_hop_tiles(int64_t n_frontier_max, int32_t fanout) {
     return tiles < 1 ? 1 : tiles;              // the first tile also writes the sizes of an empty hop
 }
 
-hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, Count n_frontier,
-                             int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
+hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier_in, int32_t* frontier_out,
+                             Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
                              int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
-                             int64_t* size_out, const ScanState& scan, int32_t* err) {
-    HopArgs a{g.offsets, g.indices, g.n_nodes, frontier, n_frontier, fanout, hop, rng_seed,
-              indptr, flat, flat_cap, n_flat_dev, size_out, scan, err};
+                             int64_t* size_out, unsigned long long* clear_table, uint32_t clear_slots,
+                             const ScanState& scan, int32_t* err) {
+    HopArgs a{g.offsets, g.indices, g.n_nodes, frontier_in, frontier_out, n_frontier, fanout, hop, rng_seed,
+              indptr, flat, flat_cap, n_flat_dev, size_out, clear_table, clear_table ? clear_slots : 0u, scan, err};
     const int lanes = sample_group_lanes(fanout);
     int64_t tiles = sample_hop_tiles(n_frontier_max, fanout);
     const dim3 grid(static_cast<unsigned>(tiles)), block(kBlock);

@@ -201,8 +201,9 @@ class Helios:
     def set_param(self, param: int, value: int) -> None:
         self._check(_lib.helios_set_param(self._h, param, value))
 
-    def set_timing(self, enabled: bool) -> None:
-        self._check(_lib.helios_set_timing(self._h, int(enabled)))
+    def set_timing(self, level: int) -> None:
+        """0 off, 1 device clock, 2 device clock and HIP events."""
+        self._check(_lib.helios_set_timing(self._h, int(level)))
 
     def gather_times(self):
         """(hbm_ms, host_ms, hbm_event_ms, host_event_ms) of the last gather."""
