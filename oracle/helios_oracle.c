@@ -35,6 +35,10 @@
  *   orc_rank_build / orc_lookup / orc_gather / orc_gather_miss
  *                       pinned: permutation inverse, closed-form tier ranges,
  *                       array indexing features[ids] (library routine).
+ *   orc_hotness_add / orc_hotness_order
+ *                       pinned: bincount and lexicographic sort (library
+ *                       routines); what counts as hotness is a reading.
+ *   orc_local_ids       pinned: dictionary lookup (library routine).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -285,6 +289,54 @@ void orc_gather_miss(const int32_t *miss_pos, const int32_t *miss_slot, int64_t 
     for (int64_t k = 0; k < n_miss; ++k)
         memcpy(out + (size_t)miss_pos[k] * (size_t)row_bytes,
                standin_table + (size_t)miss_slot[k] * (size_t)row_bytes, (size_t)row_bytes);
+}
+
+/* Pre-sampling hotness (Sec. 3.2.2 "Cache Initialization": one epoch of
+ * pre-sampling collects every vertex's hotness, then vertices are sorted by
+ * hotness, descending).  [reading] The hotness of a vertex is the number of
+ * mini-batches of the epoch whose de-duplicated ID list contains it, i.e. the
+ * number of times its feature row is fetched.  One call adds one batch's
+ * unique list. */
+void orc_hotness_add(const int32_t *unique, int64_t n_unique, int32_t *counts)
+{
+    for (int64_t j = 0; j < n_unique; ++j) counts[unique[j]] += 1;
+}
+
+static const int32_t *g_sort_counts;
+static int cmp_hotness(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    if (g_sort_counts[x] != g_sort_counts[y]) return g_sort_counts[x] > g_sort_counts[y] ? -1 : 1;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+/* order = nodes by hotness descending; [reading] ties by ascending node ID. */
+void orc_hotness_order(const int32_t *counts, int64_t n_nodes, int32_t *order)
+{
+    for (int64_t v = 0; v < n_nodes; ++v) order[v] = (int32_t)v;
+    g_sort_counts = counts;
+    qsort(order, (size_t)n_nodes, sizeof(int32_t), cmp_hotness);
+}
+
+/* Batch generation (Sec. 3.3 lists it as the operator between cache lookup
+ * and training): relabel node IDs to their index in the batch's unique list,
+ * so that hop h becomes a block in local numbering: row i = frontier_h[i],
+ * its columns = flat_h[indptr_h[i] .. indptr_h[i+1]).  out[j] = index in
+ * unique of ids[j]; returns -1 if some ID is not in unique. */
+int orc_local_ids(int64_t n_nodes, const int32_t *unique, int64_t n_unique,
+                  const int32_t *ids, int64_t n_ids, int32_t *out)
+{
+    int32_t *where = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    for (int64_t v = 0; v < n_nodes; ++v) where[v] = -1;
+    for (int64_t u = 0; u < n_unique; ++u) where[unique[u]] = (int32_t)u;
+    int bad = 0;
+    for (int64_t j = 0; j < n_ids; ++j) {
+        int32_t id = ids[j];
+        out[j] = (id >= 0 && (int64_t)id < n_nodes) ? where[id] : -1;
+        if (out[j] < 0) bad = 1;
+    }
+    free(where);
+    return bad ? -1 : 0;
 }
 
 /* Number of worker threads the parallel loops above use (1 without OpenMP). */

@@ -32,6 +32,7 @@ def lib():
         L.orc_sample_hop.restype = C.c_int
         L.orc_rank_build.restype = C.c_int
         L.orc_num_threads.restype = C.c_int
+        L.orc_local_ids.restype = C.c_int
     return _lib
 
 
@@ -164,6 +165,31 @@ def gather_miss(miss_pos, miss_slot, standin_table, out):
     assert standin_table.dtype == np.uint8 and standin_table.flags.c_contiguous
     lib().orc_gather_miss(_p(miss_pos), _p(miss_slot), C.c_int64(miss_pos.size),
                           C.c_int32(out.shape[1]), _p(standin_table), _p(out))
+
+
+def hotness_add(unique, counts):
+    """counts (int32[N]) is modified in place."""
+    unique = _arr(unique, np.int32)
+    assert counts.dtype == np.int32 and counts.flags.c_contiguous
+    lib().orc_hotness_add(_p(unique), C.c_int64(unique.size), _p(counts))
+
+
+def hotness_order(counts):
+    counts = _arr(counts, np.int32)
+    order = np.zeros(max(counts.size, 1), np.int32)
+    lib().orc_hotness_order(_p(counts), C.c_int64(counts.size), _p(order))
+    return order[:counts.size]
+
+
+def local_ids(n_nodes, unique, ids):
+    unique = _arr(unique, np.int32)
+    ids = _arr(ids, np.int32)
+    out = np.zeros(max(ids.size, 1), np.int32)
+    rc = lib().orc_local_ids(C.c_int64(n_nodes), _p(unique), C.c_int64(unique.size), _p(ids),
+                             C.c_int64(ids.size), _p(out))
+    if rc != 0:
+        raise ValueError("an id is not in the unique list")
+    return out[:ids.size]
 
 
 def num_threads():

@@ -304,3 +304,34 @@ def test_gather_and_miss_list_against_indexing(oracle, n_hbm, n_host):
     assert stats.tolist() == [700, int((want_tier == 0).sum()), int((want_tier == 1).sum()), int((~hit).sum())]
     oracle.gather_miss(mp, ms, standin, out)
     assert (out == feats[ids]).all()                                    # I6
+
+
+# ---------------------------------------------------------------- hotness, local ids
+def test_hotness_against_library_routines(oracle):
+    rng = np.random.default_rng(8)
+    n = 500
+    counts = np.zeros(n, np.int32)
+    want = np.zeros(n, np.int64)
+    for _ in range(40):
+        uniq = rng.choice(n, rng.integers(0, 120), replace=False).astype(np.int32)
+        oracle.hotness_add(uniq, counts)
+        want += np.bincount(uniq, minlength=n)
+    assert (counts == want).all()
+    order = oracle.hotness_order(counts)
+    assert order.tolist() == sorted(range(n), key=lambda v: (-int(counts[v]), v))
+    assert order.tolist() == np.lexsort((np.arange(n), -counts.astype(np.int64))).tolist()
+    assert oracle.hotness_order(np.zeros(7, np.int32)).tolist() == list(range(7))
+
+
+def test_local_ids_against_dictionary(oracle):
+    rng = np.random.default_rng(9)
+    ids = rng.integers(0, 300, 2000).astype(np.int32)
+    uniq, inv = oracle.dedup(300, ids)
+    where = {int(v): i for i, v in enumerate(uniq)}
+    probe = rng.choice(uniq, 777).astype(np.int32)
+    assert oracle.local_ids(300, uniq, probe).tolist() == [where[int(v)] for v in probe]
+    assert (oracle.local_ids(300, uniq, ids) == inv).all()             # the inverse map is the special case ids = input
+    missing = np.setdiff1d(np.arange(300), uniq)
+    if missing.size:
+        with pytest.raises(ValueError):
+            oracle.local_ids(300, uniq, missing[:1].astype(np.int32))
