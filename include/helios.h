@@ -190,6 +190,37 @@ int helios_prepare_batch(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
 void *helios_host_alloc(int64_t bytes);
 int helios_host_free(void *ptr);
 
+/* Batch generation (Sec. 3.3 names it as the operator between cache lookup
+ * and training): the hops of the last helios_prepare_batch on this context in
+ * local numbering.  For hop h, row_local[i] = index in `unique` of
+ * frontier_h[i] and col_local[e] = index in `unique` of flat_h[e]; together
+ * with indptr_h this is the hop's block in CSR form over the rows of `out`.
+ * hops: the descriptors given to helios_prepare_batch; blocks: host array of
+ * n_hops descriptors of device buffers, row_local[frontier_cap(h)],
+ * col_local[flat_cap(h)].  Must directly follow helios_prepare_batch (it
+ * reuses that call's hash table); otherwise HELIOS_ESTATE. */
+typedef struct {
+    int32_t *row_local;
+    int32_t *col_local;
+} helios_block_out;
+
+int helios_make_blocks(helios_ctx *ctx, const helios_hop_out *hops, int32_t n_hops,
+                       const helios_block_out *blocks);
+
+/* Pre-sampling hotness (Sec. 3.2.2 "Cache Initialization": an epoch of
+ * pre-sampling collects every vertex's hotness, then the GPU sorts the
+ * vertices by hotness, descending).  helios_hotness_add adds one to the
+ * counter of every ID of one batch's de-duplicated list (ids device int32,
+ * distinct; n_max bounds the list; n_dev, nullable, is a device-accessible
+ * count as in helios_gather_miss; counts device int32[n_nodes], zeroed by the
+ * caller before the epoch).  helios_hotness_order writes the nodes by counter
+ * descending, ties by ascending ID, to order (device int32[n_nodes]): the
+ * hotness_order argument of helios_cache_build.  It allocates and frees its
+ * scratch and waits for the stream. */
+int helios_hotness_add(helios_ctx *ctx, const int32_t *ids, int64_t n_max, const int64_t *n_dev,
+                       int32_t *counts);
+int helios_hotness_order(helios_ctx *ctx, const int32_t *counts, int32_t *order);
+
 /* A plain streaming copy dst[0, bytes) = src[0, bytes) (bytes a multiple of
  * 16; device-accessible pointers) with the row copy's 16-byte accesses.  It
  * is the yardstick of the measurements: hardware byte counters are scaled by

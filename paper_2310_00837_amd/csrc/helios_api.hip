@@ -60,6 +60,14 @@ struct helios_ctx {
     unsigned long long* scan_status = nullptr;
     uint32_t scan_stride = 0;
     uint32_t epoch = 0;
+
+    // what the last helios_prepare_batch left behind for helios_make_blocks
+    bool blocks_ready = false;
+    uint32_t last_slots = 0;
+    int64_t last_n_seeds = 0;
+    int32_t last_n_hops = 0;
+    int64_t last_frontier_max[HELIOS_MAX_HOPS] = {0};
+    int64_t last_flat_max[HELIOS_MAX_HOPS] = {0};
 };
 
 namespace {
@@ -214,6 +222,8 @@ int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t
     if (rc) return rc;
     DedupScratch s = c->dd;
     s.n_slots = dedup_slots(c, n_max);
+    c->blocks_ready = false;
+    c->last_slots = s.n_slots;
     HIP_TRY(c, launch_dedup(c->stream, in, n_max, ids_flat, cat_out, c->cnt + kCntCat, c->g.n_nodes, s, table_is_clear,
                             unique, unique_cap, inverse, n_unique_dev, n_unique_out, scan, c->err));
     return HELIOS_OK;
@@ -519,8 +529,65 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     }
     rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique);
     if (rc) return rc;
+    c->blocks_ready = true;
+    c->last_n_seeds = n_seeds;
+    c->last_n_hops = n_hops;
+    for (int h = 0; h < n_hops; ++h) {
+        c->last_frontier_max[h] = p.frontier_max[h];
+        c->last_flat_max[h] = p.flat_max[h];
+    }
     const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
     return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+}
+
+int helios_make_blocks(helios_ctx* c, const helios_hop_out* hops, int32_t n_hops, const helios_block_out* blocks) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->blocks_ready) return fail(c, HELIOS_ESTATE, "helios_make_blocks must follow helios_prepare_batch on this context");
+    if (!hops || !blocks || n_hops != c->last_n_hops) return fail(c, HELIOS_EINVAL, "hops / blocks do not match the last batch");
+    DeviceGuard guard(c->device);
+    DedupScratch s = c->dd;
+    s.n_slots = c->last_slots;
+    for (int h = 0; h < n_hops; ++h) {
+        if (!blocks[h].row_local || !blocks[h].col_local) return fail(c, HELIOS_EINVAL, "hop %d: NULL block buffer", h);
+        const Count nf = h == 0 ? Count{nullptr, c->last_n_seeds} : Count{c->cnt + kCntFrontier + h, c->last_frontier_max[h]};
+        HIP_TRY(c, launch_local_ids(c->stream, hops[h].frontier, nf, c->last_frontier_max[h], s, blocks[h].row_local, c->err));
+        HIP_TRY(c, launch_local_ids(c->stream, hops[h].flat, Count{c->cnt + kCntFlat + h, c->last_flat_max[h]},
+                                    c->last_flat_max[h], s, blocks[h].col_local, c->err));
+    }
+    return HELIOS_OK;
+}
+
+int helios_hotness_add(helios_ctx* c, const int32_t* ids, int64_t n_max, const int64_t* n_dev, int32_t* counts) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_graph) return fail(c, HELIOS_ESTATE, "helios_hotness_add before helios_csr_load");
+    if (n_max < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (n_max == 0) return HELIOS_OK;
+    if (!ids || !counts) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, launch_hotness_add(c->stream, ids, Count{n_dev, n_max}, n_max, c->g.n_nodes, counts, c->err));
+    return HELIOS_OK;
+}
+
+int helios_hotness_order(helios_ctx* c, const int32_t* counts, int32_t* order) {
+    if (!c) return HELIOS_EINVAL;
+    if (!c->has_graph) return fail(c, HELIOS_ESTATE, "helios_hotness_order before helios_csr_load");
+    const int64_t n = c->g.n_nodes;
+    if (n == 0) return HELIOS_OK;
+    if (!counts || !order) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    DeviceGuard guard(c->device);
+    const size_t temp_bytes = hotness_order_temp_bytes(n);
+    void* temp = nullptr;
+    int32_t *ids_in = nullptr, *counts_sorted = nullptr;
+    HIP_TRY(c, hipMalloc(&temp, temp_bytes ? temp_bytes : 16));
+    hipError_t e = hipMalloc(&ids_in, sizeof(int32_t) * n);
+    if (e == hipSuccess) e = hipMalloc(&counts_sorted, sizeof(int32_t) * n);
+    if (e == hipSuccess) e = launch_hotness_order(c->stream, counts, n, ids_in, counts_sorted, order, temp, temp_bytes);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);     // the scratch is freed below
+    (void)hipFree(temp);
+    (void)hipFree(ids_in);
+    (void)hipFree(counts_sorted);
+    if (e != hipSuccess) return fail(c, HELIOS_EHIP, "helios_hotness_order: %s", hipGetErrorString(e));
+    return HELIOS_OK;
 }
 
 int helios_calibration_copy(helios_ctx* c, const void* src, void* dst, int64_t bytes) {

@@ -77,6 +77,20 @@ hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32
                               uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit /* 0 = default */);
 hipError_t launch_clock_publish(hipStream_t stream, const uint64_t* clock, unsigned n_blocks, uint64_t* host_out);
 
+// ---- blocks.hip
+// out[j] = index in the last de-duplication's unique list of ids[j] (s = the scratch that
+// de-duplication used, untouched since); an ID that is not in the list raises kErrData.
+hipError_t launch_local_ids(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, const DedupScratch& s,
+                            int32_t* out, int32_t* err);
+
+// ---- hotness.hip
+hipError_t launch_hotness_add(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
+                              int32_t* counts, int32_t* err);
+size_t hotness_order_temp_bytes(int64_t n_nodes);
+// order = nodes by counts descending, ties by ascending ID; ids_in / counts_sorted: int32[n_nodes] scratch
+hipError_t launch_hotness_order(hipStream_t stream, const int32_t* counts, int64_t n_nodes, int32_t* ids_in,
+                                int32_t* counts_sorted, int32_t* order, void* temp, size_t temp_bytes);
+
 // dst[0, bytes) = src[0, bytes) with the same 16-byte non-temporal accesses as the row copy
 hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* dst, int64_t bytes);
 

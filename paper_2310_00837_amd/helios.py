@@ -25,13 +25,18 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 # every symbol include/helios.h declares
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
-           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_set_param", "helios_set_timing",
+           "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
+           "helios_hotness_add", "helios_hotness_order", "helios_set_param", "helios_set_timing",
            "helios_gather_times"]
 
 
 class HopOut(C.Structure):
     _fields_ = [("frontier", C.c_void_p), ("frontier_cap", C.c_int64), ("indptr", C.c_void_p),
                 ("flat", C.c_void_p), ("flat_cap", C.c_int64)]
+
+
+class BlockOut(C.Structure):
+    _fields_ = [("row_local", C.c_void_p), ("col_local", C.c_void_p)]
 
 
 class HeliosError(RuntimeError):
@@ -63,6 +68,9 @@ def load_library() -> C.CDLL:
     lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
                                          vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.helios_calibration_copy.argtypes = [vp, vp, vp, i64]
+    lib.helios_make_blocks.argtypes = [vp, C.POINTER(HopOut), i32, C.POINTER(BlockOut)]
+    lib.helios_hotness_add.argtypes = [vp, vp, i64, vp, vp]
+    lib.helios_hotness_order.argtypes = [vp, vp, vp]
     lib.helios_host_alloc.argtypes = [i64]
     lib.helios_host_alloc.restype = vp
     lib.helios_host_free.argtypes = [vp]
@@ -296,6 +304,29 @@ class Helios:
             _dev_accessible(n_miss_dev, torch.int64, "n_miss_dev")
         self._check(_lib.helios_gather_miss(self._h, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev),
                                             _ptr(out)))
+
+    # ---- batch generation, pre-sampling hotness
+    def make_blocks(self, hops: Sequence[HopBuffers], row_local: Sequence[torch.Tensor],
+                    col_local: Sequence[torch.Tensor]) -> None:
+        arr = (BlockOut * len(hops))()
+        for i, hb in enumerate(hops):
+            _dev(row_local[i], torch.int32, "row_local"), _dev(col_local[i], torch.int32, "col_local")
+            assert row_local[i].numel() >= min(hb.frontier.numel(), hb.indptr.numel() - 1)
+            assert col_local[i].numel() >= hb.flat.numel()
+            arr[i] = BlockOut(row_local[i].data_ptr(), col_local[i].data_ptr())
+        self._check(_lib.helios_make_blocks(self._h, self._hop_array(hops), len(hops), arr))
+
+    def hotness_add(self, ids: torch.Tensor, n_max: int, n_dev: Optional[torch.Tensor], counts: torch.Tensor) -> None:
+        _dev(ids, torch.int32, "ids"), _dev(counts, torch.int32, "counts")
+        assert n_max <= ids.numel() and counts.numel() >= self.n_nodes
+        if n_dev is not None:
+            _dev_accessible(n_dev, torch.int64, "n_dev")
+        self._check(_lib.helios_hotness_add(self._h, _ptr(ids), n_max, _ptr(n_dev), _ptr(counts)))
+
+    def hotness_order(self, counts: torch.Tensor, order: torch.Tensor) -> None:
+        _dev(counts, torch.int32, "counts"), _dev(order, torch.int32, "order")
+        assert counts.numel() >= self.n_nodes and order.numel() >= self.n_nodes
+        self._check(_lib.helios_hotness_order(self._h, _ptr(counts), _ptr(order)))
 
     # ---- whole path
     def prepare_batch(self, seeds: torch.Tensor, fanouts: Sequence[int], rng_seed: int, hops: Sequence[HopBuffers],
