@@ -12,6 +12,7 @@ import argparse
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -53,6 +54,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg")
     ap.add_argument("--depth", type=int, default=3,
                     help="mini-batches in flight during the timed region (each on its own context and stream)")
+    ap.add_argument("--threads", type=int, default=0, help="0: one host thread drives all lanes (default, fastest); 1: one host thread per lane")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
                     help="skip the host-link probe and use this rate (for runs under a counter profiler)")
@@ -168,15 +170,28 @@ def main() -> int:
             acc["unique"] += int(ln.stats[0])
             acc["raw"] += int(ln.sizes[1::2].sum())
 
+        def worker(w: int) -> None:          # lane w takes batches w, w + depth, ... one after the other
+            ln = use[w]
+            for k in range(w, count, depth):
+                ln.launch(first + k, serve_misses)
+                retire(ln)
+
         torch.cuda.synchronize()
         t_begin = time.perf_counter()
-        for k in range(count):
-            ln = use[k % depth]
-            if k >= depth:
-                retire(ln)
-            ln.launch(first + k, serve_misses)
-        for k in range(max(0, count - depth), count):
-            retire(use[k % depth])
+        if depth == 1 or not args.threads:
+            for k in range(count):
+                ln = use[k % depth]
+                if k >= depth:
+                    retire(ln)
+                ln.launch(first + k, serve_misses)
+            for k in range(max(0, count - depth), count):
+                retire(use[k % depth])
+        else:                                # one host thread per lane (the library calls release the GIL)
+            ts = [threading.Thread(target=worker, args=(w,)) for w in range(depth)]
+            for t in ts:
+                t.start()
+            for t in ts:
+                t.join()
         torch.cuda.synchronize()
         seconds = time.perf_counter() - t_begin
         for ln in use:
