@@ -252,3 +252,143 @@ def test_errors(h, helios):
         h.sync()
     assert e.value.code == helios.ECAPACITY and stats.tolist() == [5, 1, 0, 4]
     assert m.cpu().tolist() == [0, 1]
+
+
+# ------------------------------------------------------------------ limits and capacities
+def test_maximum_fanout_and_hops(h, helios, oracle):
+    rng = np.random.default_rng(11)
+    n = 6000
+    off, idx = _random_graph(rng, n, 30, hub_deg=3000)
+    h.csr_load(torch.from_numpy(off).cuda(), torch.from_numpy(idx).cuda())
+    hubs = np.nonzero(np.diff(off) == 3000)[0].astype(np.int32)
+    seeds = np.concatenate([hubs, rng.integers(0, n, 40).astype(np.int32)])
+    for fanouts in ([helios.MAX_FANOUT], [1000, 2], [2] * helios.MAX_HOPS):
+        print("limits", fanouts[:3], len(fanouts), flush=True)
+        hops = helios.alloc_hops(seeds.size, fanouts, h.device)
+        sizes = torch.zeros(2 * len(fanouts), dtype=torch.int64).pin_memory()
+        h.sample(torch.from_numpy(seeds).cuda(), fanouts, 7, hops, sizes)
+        h.sync()
+        for k, (fr, ip, fl) in enumerate(oracle.sample(off, idx, seeds, fanouts, 7)):
+            assert [int(sizes[2 * k]), int(sizes[2 * k + 1])] == [fr.size, fl.size]
+            assert np.array_equal(hops[k].indptr[:fr.size + 1].cpu().numpy(), ip)
+            assert np.array_equal(hops[k].flat[:fl.size].cpu().numpy(), fl)
+    with pytest.raises(helios.HeliosError) as e:
+        h.sample(torch.from_numpy(seeds).cuda(), [1] * (helios.MAX_HOPS + 1), 7,
+                 helios.alloc_hops(seeds.size, [1] * (helios.MAX_HOPS + 1), h.device),
+                 torch.zeros(2 * (helios.MAX_HOPS + 1), dtype=torch.int64).pin_memory())
+    assert e.value.code == helios.EINVAL
+
+
+def test_whole_path_capacity_errors(h, helios, workloads):
+    """Outputs of helios_prepare_batch that are too small: reported by helios_sync, required sizes
+    stored, nothing written past a capacity, and the context works again afterwards."""
+    sp, g, feats = workloads(0)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    h.csr_load(g.offsets.cuda(), g.indices.cuda())
+    cache = GpuCache(h, feats, g.order, n_hbm, n_host)  # noqa: F841
+    seeds = W.seed_batch(sp, g, 0).cuda()
+    good = gpu_path(h, helios, seeds, sp.fanouts, 3, fused=True)
+    U, n_miss = good["unique"].size, good["miss_pos"].size
+    assert n_miss > 4
+    dev = h.device
+    hops = helios.alloc_hops(seeds.numel(), sp.fanouts, dev)
+    cap = seeds.numel() + sum(hb.flat.numel() for hb in hops)
+    sizes = torch.zeros(4, dtype=torch.int64).pin_memory()
+    nu = torch.zeros(1, dtype=torch.int64).pin_memory()
+    stats = torch.zeros(4, dtype=torch.int64).pin_memory()
+    inverse = torch.empty(cap, dtype=torch.int32, device=dev)
+    out = torch.full((cap, sp.row_bytes), 0xA5, dtype=torch.uint8, device=dev)
+    full = torch.empty(cap, dtype=torch.int32, device=dev)
+    # unique list too small
+    small_unique = torch.full((U - 10 + 1,), -5, dtype=torch.int32, device=dev)
+    h.prepare_batch(seeds, sp.fanouts, 3, hops, sizes, small_unique[:U - 10], inverse, nu, out, full, full.clone(), full.clone(), stats)
+    with pytest.raises(helios.HeliosError) as e:
+        h.sync()
+    assert e.value.code == helios.ECAPACITY and int(nu[0]) == U
+    assert int(small_unique[U - 10]) == -5 and np.array_equal(small_unique[:U - 10].cpu().numpy(), good["unique"][:U - 10])
+    # miss list too small
+    unique = torch.empty(cap, dtype=torch.int32, device=dev)
+    mp = torch.full((n_miss - 3 + 1,), -5, dtype=torch.int32, device=dev)
+    h.prepare_batch(seeds, sp.fanouts, 3, hops, sizes, unique, inverse, nu, out, mp[:n_miss - 3], full[:n_miss - 3], full.clone()[:n_miss - 3], stats)
+    with pytest.raises(helios.HeliosError) as e:
+        h.sync()
+    assert e.value.code == helios.ECAPACITY and int(stats[3]) == n_miss
+    assert int(mp[n_miss - 3]) == -5 and np.array_equal(mp[:n_miss - 3].cpu().numpy(), good["miss_pos"][:n_miss - 3])
+    # a frontier buffer too small for hop 1
+    nf1 = good["hops"][1][0].size
+    tight = [hops[0], helios.HopBuffers(torch.full((nf1 - 5,), -5, dtype=torch.int32, device=dev),
+                                        torch.empty(nf1 - 5 + 1, dtype=torch.int64, device=dev), hops[1].flat)]
+    h.prepare_batch(seeds, sp.fanouts, 3, tight, sizes, unique, inverse, nu, out, full, full.clone(), full.clone(), stats)
+    with pytest.raises(helios.HeliosError) as e:
+        h.sync()
+    assert e.value.code == helios.ECAPACITY
+    # and the context still gives the right answer
+    assert_same(gpu_path(h, helios, seeds, sp.fanouts, 3, fused=True), good)
+
+
+def test_three_batches_in_flight(helios, oracle, workloads):
+    """The benchmark's launch configuration: three contexts, each on its own stream with its own
+    buffers, all sharing the graph and the cache tables; every batch must still match the oracle."""
+    sp, g, feats = workloads(1)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    dev = torch.device("cuda", 0)
+    off_d, idx_d = g.offsets.cuda(), g.indices.cuda()
+    first = helios.Helios(0)
+    first.csr_load(off_d, idx_d)
+    cache = GpuCache(first, feats, g.order, n_hbm, n_host)
+    lanes = [first]
+    for _ in range(2):
+        ctx = helios.Helios(0, stream=torch.cuda.Stream(device=dev))
+        ctx.csr_load(off_d, idx_d)
+        ctx.cache_build(cache.order, n_hbm, n_host, cache.row_bytes, cache.hbm, cache.host, cache.standin)
+        ctx.sync()
+        lanes.append(ctx)
+    torch.cuda.synchronize()
+    B = sp.batch
+    bufs = []
+    for ctx in lanes:
+        hops = helios.alloc_hops(B, sp.fanouts, dev)
+        cap = B + sum(hb.flat.numel() for hb in hops)
+        bufs.append(dict(hops=hops, unique=torch.empty(cap, dtype=torch.int32, device=dev),
+                         inverse=torch.empty(cap, dtype=torch.int32, device=dev),
+                         out=torch.full((cap, sp.row_bytes), SENTINEL, dtype=torch.uint8, device=dev),
+                         mp=torch.empty(cap, dtype=torch.int32, device=dev), mi=torch.empty(cap, dtype=torch.int32, device=dev),
+                         ms=torch.empty(cap, dtype=torch.int32, device=dev),
+                         sizes=torch.zeros(4, dtype=torch.int64).pin_memory(), nu=torch.zeros(1, dtype=torch.int64).pin_memory(),
+                         stats=torch.zeros(4, dtype=torch.int64).pin_memory()))
+    order = g.order.numpy()
+    rank = oracle.rank_build(order)
+    by_rank = to_bytes(feats)[order]
+    tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
+            np.ascontiguousarray(by_rank[n_hbm + n_host:])]
+    n_batches = 9
+    seeds = [W.seed_batch(sp, g, b).cuda() for b in range(n_batches)]
+    torch.cuda.synchronize()
+
+    def check(b):
+        ctx, bf = lanes[b % 3], bufs[b % 3]
+        ctx.sync()
+        want = oracle_path(oracle, g.offsets.numpy(), g.indices.numpy(), seeds[b].cpu().numpy(), sp.fanouts, 100 + b, rank,
+                           n_hbm, n_host, *tabs, sp.row_bytes)
+        U, nm = int(bf["nu"][0]), int(bf["stats"][3])
+        assert bf["stats"].tolist() == want["stats"].tolist()
+        assert np.array_equal(bf["unique"][:U].cpu().numpy(), want["unique"])
+        assert np.array_equal(bf["mp"][:nm].cpu().numpy(), want["miss_pos"])
+        assert np.array_equal(bf["out"][:U].cpu().numpy(), want["out"])
+        for k in range(len(sp.fanouts)):
+            nfl = int(bf["sizes"][2 * k + 1])
+            assert np.array_equal(bf["hops"][k].flat[:nfl].cpu().numpy(), want["hops"][k][2])
+
+    for b in range(n_batches):
+        ctx, bf = lanes[b % 3], bufs[b % 3]
+        if b >= 3:
+            check(b - 3)
+            bf["out"].fill_(SENTINEL)
+            torch.cuda.synchronize()
+        ctx.prepare_batch(seeds[b], sp.fanouts, 100 + b, bf["hops"], bf["sizes"], bf["unique"], bf["inverse"], bf["nu"],
+                          bf["out"], bf["mp"], bf["mi"], bf["ms"], bf["stats"])
+        ctx.gather_miss(bf["mp"], bf["ms"], bf["mp"].numel(), bf["stats"][3:4], bf["out"])
+    for b in range(n_batches - 3, n_batches):
+        check(b)
+    for ctx in lanes:
+        ctx.close()
