@@ -55,6 +55,7 @@ def main() -> int:
     ap.add_argument("--depth", type=int, default=3,
                     help="mini-batches in flight during the timed region (each on its own context and stream)")
     ap.add_argument("--threads", type=int, default=0, help="0: one host thread drives all lanes (default, fastest); 1: one host thread per lane")
+    ap.add_argument("--host-blocks", type=int, default=0, help="workgroups of the host-link copies (0 = library default)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
                     help="skip the host-link probe and use this rate (for runs under a counter profiler)")
@@ -137,6 +138,8 @@ def main() -> int:
             if serve_misses:
                 self.h.gather_miss(self.mp, self.ms, self.mp.numel(), self.stats[3:4], self.out)
 
+    if args.host_blocks:
+        h.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
     lanes = [Lane(h, None)]
     for _ in range(1, max(1, args.depth)):
         st = torch.cuda.Stream(device=dev)
@@ -144,6 +147,8 @@ def main() -> int:
         ctx.csr_load(offsets, indices)
         ctx.cache_build(order, tiers.n_hbm, tiers.n_host, sp.row_bytes, tiers.hbm, tiers.host, tiers.standin)
         ctx.sync()
+        if args.host_blocks:
+            ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
         lanes.append(Lane(ctx, st))
     torch.cuda.synchronize()
 
