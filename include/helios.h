@@ -243,6 +243,30 @@ typedef enum {
 } helios_param;
 int helios_set_param(helios_ctx *ctx, int param, int64_t value);
 
+/* A recorded batch: the kernel sequence of helios_prepare_batch for one fixed
+ * set of buffers, captured once into a HIP graph and replayed with one launch
+ * per mini-batch (the per-batch path is a dozen short kernels, so the host's
+ * launch cost matters).  helios_plan_create takes the arguments of
+ * helios_prepare_batch except seeds and rng_seed; all buffers, capacities,
+ * n_seeds and fan-outs are fixed by it.  helios_plan_launch(plan, seeds,
+ * rng_seed) enqueues one batch on the context's stream: seeds (device
+ * int32[n_seeds]) may be a different buffer every time.  Results, errors and
+ * helios_make_blocks behave as after helios_prepare_batch.  The context's
+ * stream must not be the NULL stream; the timing level in force at creation
+ * (0 or 1; level 2 cannot be recorded) is part of the recording.  A
+ * plan is bound to its context and becomes invalid (HELIOS_ESTATE) if the
+ * context's scratch grows afterwards; call helios_reserve first.  At most 255
+ * launches may be queued without a helios_sync (one more waits for the stream
+ * by itself).  Destroy the plan before the context. */
+typedef struct helios_plan helios_plan;
+int helios_plan_create(helios_ctx *ctx, int64_t n_seeds, const int32_t *fanouts, int32_t n_hops,
+                       const helios_hop_out *hops, int64_t *sizes,
+                       int32_t *unique, int64_t unique_cap, int32_t *inverse, int64_t *n_unique,
+                       void *out, int32_t *miss_pos, int32_t *miss_id, int32_t *miss_slot,
+                       int64_t miss_cap, helios_gather_stats *stats, helios_plan **plan_out);
+int helios_plan_launch(helios_plan *plan, const int32_t *seeds, uint64_t rng_seed);
+int helios_plan_destroy(helios_plan *plan);
+
 /* Timing of the two row-copy kernels (HBM tier, host tier) of the last
  * helios_gather / helios_prepare_batch on this context.  Level 1: every
  * workgroup of those kernels stores its first and last tick of the GPU's

@@ -27,6 +27,16 @@ struct Count {
     }
 };
 
+// What changes from one mini-batch to the next.  Kernels of a recorded (graph) batch read it
+// from device memory, so that one recording serves every batch; directly launched kernels get
+// the same values as arguments and a null pointer here.
+struct BatchVars {
+    uint64_t rng_seed;
+    const int32_t* seeds;
+    uint32_t epoch_base;     // added to the per-launch epoch of the chained scans
+    uint32_t pad;
+};
+
 // First error wins is not needed: any recorded error makes the call fail.
 // err points to pinned, GPU-mapped host memory (int32[2]: code, detail).
 __device__ __forceinline__ void raise(int32_t* err, int code) {

@@ -52,7 +52,8 @@ __global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int
 #pragma unroll
         for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
             if (q < in.n_seg && j >= start[q]) k = q;
-        const int32_t id = in.src[k][j - start[k]];
+        const int32_t* src = (k == 0 && in.vars) ? in.vars->seeds : in.src[k];
+        const int32_t id = src[j - start[k]];
         if (cat_out) cat_out[j] = id;
         if (id < 0 || static_cast<int64_t>(id) >= n_nodes) {
             raise(err, kErrData);

@@ -19,6 +19,7 @@ constexpr int kCntCat = 32;         // length of [seeds | flat_0 | ...]
 constexpr int kCntUnique = 33;
 constexpr int kCntTier = 40;        // [3] HBM hits, host hits, misses
 constexpr int kNumCounters = 64;
+constexpr uint32_t kVarsRing = 256;   // batch launches that may be queued on a context without a helios_sync
 
 }  // namespace
 
@@ -60,6 +61,15 @@ struct helios_ctx {
     unsigned long long* scan_status = nullptr;
     uint32_t scan_stride = 0;
     uint32_t epoch = 0;
+
+    // recorded batches (HIP graphs): per-batch values live in device memory (vars), fed from a ring
+    // of pinned slots; while recording, scans get epoch offsets 1, 2, ... instead of fresh epochs
+    BatchVars* vars = nullptr;                 // device
+    BatchVars* vars_ring = nullptr;            // pinned [kVarsRing]
+    uint32_t vars_next = 0, vars_unsynced = 0;
+    bool recording = false;
+    uint32_t rec_scans = 0;
+    uint64_t scratch_generation = 0;
 
     // what the last helios_prepare_batch left behind for helios_make_blocks
     bool blocks_ready = false;
@@ -130,6 +140,8 @@ void free_scratch(helios_ctx* c) {
 // old buffers may still be in use.
 int ensure_capacity(helios_ctx* c, int64_t n) {
     if (n <= c->cap_ids) return HELIOS_OK;
+    if (c->recording) return fail(c, HELIOS_ESTATE, "scratch must be reserved before a batch is recorded");
+    c->scratch_generation += 1;
     if (n >= (1ll << 31) - 1024) return fail(c, HELIOS_EINVAL, "a call handles fewer than 2^31 IDs (got %lld)", (long long)n);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     free_scratch(c);
@@ -155,12 +167,17 @@ int ensure_capacity(helios_ctx* c, int64_t n) {
 
 // scan state with a fresh epoch; stale status words of earlier launches read as unpublished
 int next_scan(helios_ctx* c, ScanState* out) {
-    if (c->epoch >= (1u << 30) - 2) {
+    if (!c->recording && c->epoch >= (1u << 30) - 64) {
         HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * c->scan_stride, c->stream));
         c->epoch = 0;
     }
+    if (c->recording) {                       // the batch's base epoch is added on the device
+        c->rec_scans += 1;
+        *out = ScanState{c->scan_status, c->scan_stride, c->rec_scans, c->vars};
+        return HELIOS_OK;
+    }
     c->epoch += 1;
-    *out = ScanState{c->scan_status, c->scan_stride, c->epoch};
+    *out = ScanState{c->scan_status, c->scan_stride, c->epoch, nullptr};
     return HELIOS_OK;
 }
 
@@ -250,7 +267,8 @@ int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int3
         const int64_t next_dedup = last ? final_dedup_max : p.flat_max[h];
         const uint32_t clear_slots = next_dedup > 0 || !last ? dedup_slots(c, next_dedup) : 0u;
         HIP_TRY(c, launch_sample_hop(c->stream, c->g, h == 0 ? seeds : hops[h].frontier, hops[h].frontier, nf,
-                                     p.frontier_max[h], fanouts[h], h, rng_seed, hops[h].indptr, hops[h].flat,
+                                     p.frontier_max[h], fanouts[h], h, rng_seed, c->recording ? c->vars : nullptr,
+                                     hops[h].indptr, hops[h].flat,
                                      hops[h].flat_cap, c->cnt + kCntFlat + h, sizes ? sizes + 2 * h : nullptr,
                                      clear_slots ? c->dd.table : nullptr, clear_slots, scan, c->err));
         if (!last) {
@@ -332,6 +350,8 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipEventCreate(&c->t_host[0]) == hipSuccess && hipEventCreate(&c->t_host[1]) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->err), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
+              hipMalloc(&c->vars, sizeof(BatchVars)) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&c->vars_ring), sizeof(BatchVars) * kVarsRing, hipHostMallocDefault) == hipSuccess &&
               hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
@@ -358,6 +378,8 @@ int helios_destroy(helios_ctx* c) {
     free_scratch(c);
     (void)hipFree(c->rank);
     (void)hipFree(c->cnt);
+    (void)hipFree(c->vars);
+    if (c->vars_ring) (void)hipHostFree(c->vars_ring);
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
     if (c->err) (void)hipHostFree(c->err);
@@ -380,6 +402,7 @@ int helios_sync(helios_ctx* c) {
     if (!c) return HELIOS_EINVAL;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->vars_unsynced = 0;
     const int code = *reinterpret_cast<volatile int32_t*>(c->err);
     if (code != 0) {
         c->err[0] = 0;
@@ -501,7 +524,7 @@ int helios_gather_miss(helios_ctx* c, const int32_t* miss_pos, const int32_t* mi
     return HELIOS_OK;
 }
 
-int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                          uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, int32_t* unique,
                          int64_t unique_cap, int32_t* inverse, int64_t* n_unique, void* out, int32_t* miss_pos,
                          int32_t* miss_id, int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
@@ -514,12 +537,12 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     if (unique_cap < 0 || miss_cap < 0) return fail(c, HELIOS_EINVAL, "negative size");
     if (unique_cap > 0 && (!unique || !out)) return fail(c, HELIOS_EINVAL, "NULL pointer");
     if (miss_cap > 0 && (!miss_pos || !miss_id || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL miss list");
-    DeviceGuard guard(c->device);
     rc = ensure_capacity(c, p.ids_max);
     if (rc) return rc;
     rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, p.cat_max > 0 ? p.cat_max : 1);
     if (rc) return rc;
     ConcatArgs cat{};
+    cat.vars = c->recording ? c->vars : nullptr;
     cat.n_seg = n_hops + 1;
     cat.src[0] = seeds;
     cat.len[0] = Count{nullptr, n_seeds};
@@ -538,6 +561,130 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     }
     const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
     return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+}
+
+int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                         uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, int32_t* unique,
+                         int64_t unique_cap, int32_t* inverse, int64_t* n_unique, void* out, int32_t* miss_pos,
+                         int32_t* miss_id, int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
+    if (!c) return HELIOS_EINVAL;
+    DeviceGuard guard(c->device);
+    return prepare_batch_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, unique, unique_cap, inverse,
+                              n_unique, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+}
+
+struct helios_plan {
+    helios_ctx* ctx = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    uint32_t n_scans = 0;
+    uint64_t scratch_generation = 0;
+    int64_t n_seeds = 0;
+    int32_t n_hops = 0;
+    int64_t frontier_max[HELIOS_MAX_HOPS] = {0};
+    int64_t flat_max[HELIOS_MAX_HOPS] = {0};
+    uint32_t slots = 0;
+};
+
+int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                       const helios_hop_out* hops, int64_t* sizes, int32_t* unique, int64_t unique_cap,
+                       int32_t* inverse, int64_t* n_unique, void* out, int32_t* miss_pos, int32_t* miss_id,
+                       int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats, helios_plan** plan_out) {
+    if (!c || !plan_out) return HELIOS_EINVAL;
+    *plan_out = nullptr;
+    if (!c->has_graph || !c->has_cache) return fail(c, HELIOS_ESTATE, "helios_plan_create needs the graph and the cache");
+    if (!c->stream) return fail(c, HELIOS_EINVAL, "a batch cannot be recorded on the default (NULL) stream");
+    if (c->timing > 1) return fail(c, HELIOS_ESTATE, "event timing cannot be recorded; use timing level 0 or 1");
+    DeviceGuard guard(c->device);
+    HopPlan p;
+    int rc = plan_hops(c, n_seeds, fanouts, n_hops, hops, &p);
+    if (rc) return rc;
+    rc = ensure_capacity(c, p.ids_max);          // allocate before recording starts
+    if (rc) return rc;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    helios_plan* pl = new helios_plan();
+    pl->ctx = c;
+    c->recording = true;
+    c->rec_scans = 0;
+    hipError_t e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal);
+    if (e == hipSuccess) {
+        // the seeds pointer and rng_seed passed here are placeholders: recorded kernels read both from c->vars
+        rc = prepare_batch_impl(c, reinterpret_cast<const int32_t*>(c->vars), n_seeds, fanouts, n_hops, 0, hops, sizes,
+                                unique, unique_cap, inverse, n_unique, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+        hipError_t e2 = hipStreamEndCapture(c->stream, &pl->graph);
+        if (rc == HELIOS_OK && e2 != hipSuccess) e = e2;
+    }
+    c->recording = false;
+    pl->n_scans = c->rec_scans;
+    if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&pl->exec, pl->graph, nullptr, nullptr, 0);
+    if (e != hipSuccess || rc != HELIOS_OK) {
+        if (pl->graph) (void)hipGraphDestroy(pl->graph);
+        delete pl;
+        c->blocks_ready = false;
+        if (rc != HELIOS_OK) return rc;
+        return fail(c, HELIOS_EHIP, "recording the batch failed: %s", hipGetErrorString(e));
+    }
+    pl->scratch_generation = c->scratch_generation;
+    pl->n_seeds = n_seeds;
+    pl->n_hops = n_hops;
+    for (int h = 0; h < n_hops; ++h) {
+        pl->frontier_max[h] = p.frontier_max[h];
+        pl->flat_max[h] = p.flat_max[h];
+    }
+    pl->slots = c->last_slots;
+    c->blocks_ready = false;                     // nothing has run yet
+    *plan_out = pl;
+    return HELIOS_OK;
+}
+
+int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed) {
+    if (!pl || !pl->ctx) return HELIOS_EINVAL;
+    helios_ctx* c = pl->ctx;
+    if (pl->n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
+    if (pl->scratch_generation != c->scratch_generation)
+        return fail(c, HELIOS_ESTATE, "the context's scratch was regrown after the batch was recorded; record it again");
+    DeviceGuard guard(c->device);
+    if (c->epoch + pl->n_scans >= (1u << 30) - 64) {
+        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * c->scan_stride, c->stream));
+        c->epoch = 0;
+    }
+    if (c->vars_unsynced + 1 >= kVarsRing) {     // the ring slot about to be reused may still be in flight
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        c->vars_unsynced = 0;
+    }
+    BatchVars* slot = c->vars_ring + (c->vars_next % kVarsRing);
+    c->vars_next += 1;
+    c->vars_unsynced += 1;
+    slot->rng_seed = rng_seed;
+    slot->seeds = seeds;
+    slot->epoch_base = c->epoch;
+    slot->pad = 0;
+    c->epoch += pl->n_scans;
+    HIP_TRY(c, hipMemcpyAsync(c->vars, slot, sizeof(BatchVars), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
+    c->blocks_ready = true;
+    c->last_slots = pl->slots;
+    c->last_n_seeds = pl->n_seeds;
+    c->last_n_hops = pl->n_hops;
+    for (int h = 0; h < pl->n_hops; ++h) {
+        c->last_frontier_max[h] = pl->frontier_max[h];
+        c->last_flat_max[h] = pl->flat_max[h];
+    }
+    c->timed_hbm = c->timing != 0 && c->n_hbm > 0 && pl->n_seeds > 0;
+    c->timed_host = c->timing != 0 && c->n_host > 0 && pl->n_seeds > 0;
+    return HELIOS_OK;
+}
+
+int helios_plan_destroy(helios_plan* pl) {
+    if (!pl) return HELIOS_EINVAL;
+    if (pl->ctx) {
+        DeviceGuard guard(pl->ctx->device);
+        (void)hipStreamSynchronize(pl->ctx->stream);
+    }
+    if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
+    if (pl->graph) (void)hipGraphDestroy(pl->graph);
+    delete pl;
+    return HELIOS_OK;
 }
 
 int helios_make_blocks(helios_ctx* c, const helios_hop_out* hops, int32_t n_hops, const helios_block_out* blocks) {

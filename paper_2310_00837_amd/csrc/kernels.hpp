@@ -25,6 +25,7 @@ int64_t sample_hop_tiles(int64_t n_frontier_max, int32_t fanout);
 // de-duplication that follows the hop).
 hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier_in, int32_t* frontier_out,
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
+                             const BatchVars* vars /* nullable: overrides rng_seed and the hop-0 frontier */,
                              int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
                              int64_t* size_out, unsigned long long* clear_table, uint32_t clear_slots,
                              const ScanState& scan, int32_t* err);
@@ -41,6 +42,7 @@ struct ConcatArgs {
     const int32_t* src[HELIOS_KERNELS_MAX_SEG];
     Count len[HELIOS_KERNELS_MAX_SEG];
     int n_seg;
+    const BatchVars* vars;       // nullable: if set, segment 0 is vars->seeds
 };
 // De-duplicates the concatenation of the segments of `in` (n_max bounds its length).  ids_flat is
 // where the concatenation can be indexed: the single segment itself, or cat_out, which the first

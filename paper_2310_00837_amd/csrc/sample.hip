@@ -37,6 +37,7 @@ struct HopArgs {
     int32_t fanout;
     int32_t hop;
     uint64_t rng_seed;
+    const BatchVars* vars;        // nullable: rng_seed (and, at hop 0, the frontier) come from here
     int64_t* indptr;
     int32_t* flat;
     int64_t flat_cap;
@@ -59,6 +60,8 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     const uint32_t tile = blockIdx.x;
     const int64_t n = a.n_frontier.get();
     const int64_t n_tiles = (n + kGroups - 1) / kGroups;
+    const uint64_t rng_seed = a.vars ? a.vars->rng_seed : a.rng_seed;
+    const int32_t* frontier = (a.vars && a.hop == 0) ? a.vars->seeds : a.frontier;
     // side job: empty the hash table of the de-duplication that follows this hop
     for (uint32_t w = blockIdx.x * kBlock + threadIdx.x; w < a.clear_slots; w += gridDim.x * kBlock) a.clear_table[w] = ~0ull;
     if (tile == 0 && threadIdx.x == 0) {
@@ -80,8 +83,8 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     int32_t v = 0, deg = 0;
     int64_t base = 0;
     if (i < n) {
-        v = a.frontier[i];
-        if (l == 0 && a.frontier_out && a.frontier_out != a.frontier) a.frontier_out[i] = v;
+        v = frontier[i];
+        if (l == 0 && a.frontier_out && a.frontier_out != frontier) a.frontier_out[i] = v;
         if (v < 0 || static_cast<int64_t>(v) >= a.n_nodes) {
             raise(a.err, kErrData);
         } else {
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
         if (deg > f) {
             const int32_t j = deg - f + l;                // position looked at in step l
             const int32_t t = static_cast<int32_t>(
-                bounded(node_draw(a.rng_seed, v, a.hop, static_cast<uint32_t>(l)), static_cast<uint64_t>(j) + 1u));
+                bounded(node_draw(rng_seed, v, a.hop, static_cast<uint32_t>(l)), static_cast<uint64_t>(j) + 1u));
             pos = t;
         }
         nbr = pos;                                        // settled below
@@ -152,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
             const int32_t j = deg - f + k;
             int32_t t = -1, s = -1;
             if (active) {
-                t = static_cast<int32_t>(bounded(node_draw(a.rng_seed, v, a.hop, static_cast<uint32_t>(k)),
+                t = static_cast<int32_t>(bounded(node_draw(rng_seed, v, a.hop, static_cast<uint32_t>(k)),
                                                  static_cast<uint64_t>(j) + 1u));
                 s = t;
                 for (int p = 0; p < c0; ++p)
@@ -186,10 +189,10 @@ int64_t sample_hop_tiles(int64_t n_frontier_max, int32_t fanout) {
 
 hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier_in, int32_t* frontier_out,
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
-                             int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
+                             const BatchVars* vars, int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
                              int64_t* size_out, unsigned long long* clear_table, uint32_t clear_slots,
                              const ScanState& scan, int32_t* err) {
-    HopArgs a{g.offsets, g.indices, g.n_nodes, frontier_in, frontier_out, n_frontier, fanout, hop, rng_seed,
+    HopArgs a{g.offsets, g.indices, g.n_nodes, frontier_in, frontier_out, n_frontier, fanout, hop, rng_seed, vars,
               indptr, flat, flat_cap, n_flat_dev, size_out, clear_table, clear_table ? clear_slots : 0u, scan, err};
     const int lanes = sample_group_lanes(fanout);
     int64_t tiles = sample_hop_tiles(n_frontier_max, fanout);

@@ -25,7 +25,14 @@ struct ScanState {
     unsigned long long* status;   // [n_counters][stride]
     uint32_t stride;              // tiles the status rows have room for
     uint32_t epoch;               // 1 .. 2^30-1, new for every launch
+    const BatchVars* vars;        // nullable: if set, vars->epoch_base is added to epoch on the device
 };
+
+// the launch's epoch: the argument, plus the batch's base when the launch is part of a recorded batch
+__device__ __forceinline__ ScanState scan_resolve(ScanState st) {
+    if (st.vars) st.epoch += st.vars->epoch_base;
+    return st;
+}
 
 constexpr uint32_t kFlagAggregate = 1u;
 constexpr uint32_t kFlagPrefix = 2u;
@@ -61,8 +68,9 @@ struct ScanLookbackLds {
 // of a launch with T tiles takes about T/256 rounds at worst.  Call from
 // uniform control flow; tile < st.stride is the caller's duty.
 template <int NC>
-__device__ __forceinline__ void scan_chained_prefix(const ScanState& st, uint32_t tile, const uint32_t* s_agg,
+__device__ __forceinline__ void scan_chained_prefix(const ScanState& st_in, uint32_t tile, const uint32_t* s_agg,
                                                     uint32_t* s_excl, ScanLookbackLds<NC>* lds, int32_t* err) {
+    const ScanState st = scan_resolve(st_in);
     __syncthreads();
     if (threadIdx.x < NC) {
         const uint32_t c = threadIdx.x;

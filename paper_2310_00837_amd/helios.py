@@ -26,7 +26,7 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
-           "helios_hotness_add", "helios_hotness_order", "helios_set_param", "helios_set_timing",
+           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
            "helios_gather_times"]
 
 
@@ -71,6 +71,10 @@ def load_library() -> C.CDLL:
     lib.helios_make_blocks.argtypes = [vp, C.POINTER(HopOut), i32, C.POINTER(BlockOut)]
     lib.helios_hotness_add.argtypes = [vp, vp, i64, vp, vp]
     lib.helios_hotness_order.argtypes = [vp, vp, vp]
+    lib.helios_plan_create.argtypes = [vp, i64, C.POINTER(i32), i32, C.POINTER(HopOut), vp, vp, i64, vp, vp, vp, vp, vp,
+                                       vp, i64, vp, C.POINTER(vp)]
+    lib.helios_plan_launch.argtypes = [vp, vp, C.c_uint64]
+    lib.helios_plan_destroy.argtypes = [vp]
     lib.helios_host_alloc.argtypes = [i64]
     lib.helios_host_alloc.restype = vp
     lib.helios_host_free.argtypes = [vp]
@@ -162,6 +166,29 @@ def alloc_hops(n_seeds: int, fanouts: Sequence[int], device) -> List[HopBuffers]
         fl = torch.empty(max(cap, 1), dtype=torch.int32, device=device)
         hops.append(HopBuffers(fr, ip, fl))
     return hops
+
+
+class Plan:
+    """A recorded batch (see helios_plan_create).  launch(seeds, rng_seed) enqueues one mini-batch."""
+
+    def __init__(self, ctx: "Helios", handle, n_seeds: int, keep):
+        self._ctx, self._p, self.n_seeds, self._keep = ctx, handle, n_seeds, keep
+
+    def launch(self, seeds: torch.Tensor, rng_seed: int) -> None:
+        _dev(seeds, torch.int32, "seeds")
+        assert seeds.numel() == self.n_seeds
+        self._ctx._check(_lib.helios_plan_launch(self._p, _ptr(seeds), C.c_uint64(rng_seed)))
+
+    def destroy(self) -> None:
+        if self._p is not None and self._p.value:
+            _lib.helios_plan_destroy(self._p)
+            self._p = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 class Helios:
@@ -304,6 +331,29 @@ class Helios:
             _dev_accessible(n_miss_dev, torch.int64, "n_miss_dev")
         self._check(_lib.helios_gather_miss(self._h, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev),
                                             _ptr(out)))
+
+    # ---- recorded batch (HIP graph)
+    def plan_create(self, n_seeds: int, fanouts: Sequence[int], hops: Sequence[HopBuffers], sizes: torch.Tensor,
+                    unique: torch.Tensor, inverse: Optional[torch.Tensor], n_unique: torch.Tensor, out: torch.Tensor,
+                    miss_pos: torch.Tensor, miss_id: torch.Tensor, miss_slot: torch.Tensor,
+                    stats: torch.Tensor) -> "Plan":
+        _dev(unique, torch.int32, "unique")
+        _dev_accessible(sizes, torch.int64, "sizes"), _dev_accessible(n_unique, torch.int64, "n_unique")
+        _dev_accessible(stats, torch.int64, "stats")
+        if inverse is not None:
+            _dev(inverse, torch.int32, "inverse")
+            assert inverse.numel() >= n_seeds + sum(h.flat.numel() for h in hops)
+        if not out.is_cuda or out.numel() * out.element_size() < unique.numel() * self.row_bytes:
+            raise TypeError("out must be a GPU tensor with room for unique_cap rows")
+        cap = min(miss_pos.numel(), miss_id.numel(), miss_slot.numel())
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        handle = C.c_void_p()
+        self._check(_lib.helios_plan_create(
+            self._h, n_seeds, fan, len(fanouts), self._hop_array(hops), _ptr(sizes), _ptr(unique), unique.numel(),
+            _ptr(inverse), _ptr(n_unique), _ptr(out), _ptr(miss_pos), _ptr(miss_id), _ptr(miss_slot), cap, _ptr(stats),
+            C.byref(handle)))
+        keep = (hops, sizes, unique, inverse, n_unique, out, miss_pos, miss_id, miss_slot, stats)
+        return Plan(self, handle, n_seeds, keep)
 
     # ---- batch generation, pre-sampling hotness
     def make_blocks(self, hops: Sequence[HopBuffers], row_local: Sequence[torch.Tensor],
