@@ -55,6 +55,7 @@ def main() -> int:
     ap.add_argument("--depth", type=int, default=3,
                     help="mini-batches in flight during the timed region (each on its own context and stream)")
     ap.add_argument("--threads", type=int, default=0, help="0: one host thread drives all lanes (default, fastest); 1: one host thread per lane")
+    ap.add_argument("--graph", type=int, default=1, help="1: replay a recorded batch (HIP graph) per step; 0: launch directly")
     ap.add_argument("--host-blocks", type=int, default=0, help="workgroups of the host-link copies (0 = library default)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
@@ -132,16 +133,30 @@ def main() -> int:
             self.n_unique = torch.zeros(1, dtype=torch.int64).pin_memory()
             self.stats = torch.zeros(4, dtype=torch.int64).pin_memory()
 
-        def launch(self, b: int, serve_misses: bool) -> None:
-            self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], self.hops, self.sizes, self.unique, self.inverse,
-                                 self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
+            self.plans = {}
+
+        def record(self) -> None:
+            """One recording (HIP graph) of the whole-path call per timing level."""
+            for level in (0, 1):
+                self.h.set_timing(level)
+                self.plans[level] = self.h.plan_create(B, sp.fanouts, self.hops, self.sizes, self.unique, self.inverse,
+                                                       self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
+            self.h.set_timing(0)
+
+        def launch(self, b: int, serve_misses: bool, timing: int = 0) -> None:
+            plan = self.plans.get(timing) if args.graph else None
+            if plan is not None:
+                plan.launch(seeds[b], rng_seeds[b])
+            else:
+                self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], self.hops, self.sizes, self.unique,
+                                     self.inverse, self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
             if serve_misses:
                 self.h.gather_miss(self.mp, self.ms, self.mp.numel(), self.stats[3:4], self.out)
 
-    if args.host_blocks:
-        h.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
-    lanes = [Lane(h, None)]
-    for _ in range(1, max(1, args.depth)):
+    # every lane gets a stream of its own (a batch cannot be recorded on the NULL stream); `h` keeps the
+    # default stream and is used for set-up and the parity check only
+    lanes = []
+    for _ in range(max(1, args.depth)):
         st = torch.cuda.Stream(device=dev)
         ctx = helios.Helios(0, stream=st)
         ctx.csr_load(offsets, indices)
@@ -151,6 +166,10 @@ def main() -> int:
             ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
         lanes.append(Lane(ctx, st))
     torch.cuda.synchronize()
+    if args.graph:
+        for ln in lanes:
+            ln.record()
+        torch.cuda.synchronize()
 
     def run_region(first: int, count: int, depth: int, timing: int, serve_misses: bool):
         """`count` whole steps with up to `depth` mini-batches in flight (lane b % depth); a lane's
@@ -178,7 +197,7 @@ def main() -> int:
         def worker(w: int) -> None:          # lane w takes batches w, w + depth, ... one after the other
             ln = use[w]
             for k in range(w, count, depth):
-                ln.launch(first + k, serve_misses)
+                ln.launch(first + k, serve_misses, timing)
                 retire(ln)
 
         torch.cuda.synchronize()
@@ -188,7 +207,7 @@ def main() -> int:
                 ln = use[k % depth]
                 if k >= depth:
                     retire(ln)
-                ln.launch(first + k, serve_misses)
+                ln.launch(first + k, serve_misses, timing)
             for k in range(max(0, count - depth), count):
                 retire(use[k % depth])
         else:                                # one host thread per lane (the library calls release the GIL)
@@ -251,7 +270,8 @@ def main() -> int:
         "config": {"workload": f"BASELINE.json configs[{args.config}] {sp.name}", "n_nodes": g.n_nodes,
                    "n_edges": g.n_edges, "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
                    "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed,
-                   "step": "helios_prepare_batch (sample, dedup, lookup, HBM+host gather, miss list) + helios_sync, "
+                   "step": ("helios_plan_launch (recorded helios_prepare_batch" if args.graph else "helios_prepare_batch (") +
+                           ": sample, dedup, lookup, HBM+host gather, miss list) + helios_sync, "
                            "%d mini-batches in flight, each on its own context and stream" % D},
         "roofline": {"kernel": "gather_rows_kernel (HBM tier)", "bound": "hbm", "achieved": hbm_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": traffic,
@@ -317,7 +337,10 @@ def main() -> int:
                                   "sample": f"{done} of the {K} timed batches (sample, dedup, lookup, gather, miss list), "
                                             f"{cpu_elapsed:.1f} s"}
     for ln in lanes:
+        for pl in ln.plans.values():
+            pl.destroy()
         ln.h.close()
+    h.close()
     print(json.dumps(result))
     return 0
 

@@ -56,6 +56,12 @@ __global__ __launch_bounds__(kBlock) void lookup_partition_kernel(PartitionArgs 
     __shared__ uint32_t s_agg[3], s_excl[3];
     __shared__ ScanLookbackLds<3> s_look;
     const uint32_t tile = blockIdx.x;
+    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    // the ID and its rank are fetched before the device-side count has arrived (ids has room for
+    // a.n.host entries; a value that is no node ID is simply not looked up)
+    int32_t id = j < a.n.host ? a.ids[j] : -1;
+    const bool id_ok = id >= 0 && static_cast<int64_t>(id) < a.n_nodes;
+    const int64_t r = id_ok ? static_cast<int64_t>(a.rank[id]) : 0;
     const int64_t n = a.n.get();
     const int64_t n_tiles = (n + kBlock - 1) / kBlock;
     if (n == 0 && tile == 0 && threadIdx.x == 0) {
@@ -64,15 +70,12 @@ __global__ __launch_bounds__(kBlock) void lookup_partition_kernel(PartitionArgs 
     }
     if (static_cast<int64_t>(tile) >= n_tiles) return;
 
-    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
     int tier = -1;                       // -1: no ID here (tail of the last tile, or a bad ID)
-    int32_t id = 0, slot = 0;
+    int32_t slot = 0;
     if (j < n) {
-        id = a.ids[j];
-        if (id < 0 || static_cast<int64_t>(id) >= a.n_nodes) {
+        if (!id_ok) {
             raise(a.err, kErrData);
         } else {
-            const int64_t r = a.rank[id];
             if (r < a.n_hbm) { tier = 0; slot = static_cast<int32_t>(r); }
             else if (r < a.n_hbm + a.n_host) { tier = 1; slot = static_cast<int32_t>(r - a.n_hbm); }
             else { tier = 2; slot = static_cast<int32_t>(r - a.n_hbm - a.n_host); }

@@ -39,6 +39,12 @@ __global__ __launch_bounds__(kBlock) void dedup_clear_kernel(unsigned long long*
 // cat_out is given the concatenation is also written out, for the later passes to index.
 __global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int32_t* cat_out, int64_t* n_total_dev,
                                                               int64_t n_nodes, DedupScratch s, int32_t* err) {
+    // With one segment the first ID is fetched before the device-side count has arrived (the buffer
+    // holds len.host entries, so the read is in bounds whatever the count turns out to be).
+    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const bool one = in.n_seg == 1 && !in.vars;
+    int32_t early = 0;
+    if (one && j0 < in.len[0].host) early = in.src[0][j0];
     int64_t start[HELIOS_KERNELS_MAX_SEG + 1];
     start[0] = 0;
 #pragma unroll
@@ -46,14 +52,18 @@ __global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int
     const int64_t n = start[HELIOS_KERNELS_MAX_SEG];
     if (blockIdx.x == 0 && threadIdx.x == 0) *n_total_dev = n;
     const uint32_t mask = s.n_slots - 1;
-    for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < n;
-         j += static_cast<int64_t>(gridDim.x) * kBlock) {
-        int k = 0;
+    for (int64_t j = j0; j < n; j += static_cast<int64_t>(gridDim.x) * kBlock) {
+        int32_t id;
+        if (one && j == j0) {
+            id = early;
+        } else {
+            int k = 0;
 #pragma unroll
-        for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
-            if (q < in.n_seg && j >= start[q]) k = q;
-        const int32_t* src = (k == 0 && in.vars) ? in.vars->seeds : in.src[k];
-        const int32_t id = src[j - start[k]];
+            for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
+                if (q < in.n_seg && j >= start[q]) k = q;
+            const int32_t* src = (k == 0 && in.vars) ? in.vars->seeds : in.src[k];
+            id = src[j - start[k]];
+        }
         if (cat_out) cat_out[j] = id;
         if (id < 0 || static_cast<int64_t>(id) >= n_nodes) {
             raise(err, kErrData);
@@ -65,11 +75,9 @@ __global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int
         uint32_t slot = hash_id(static_cast<uint32_t>(id), mask);
         // the table is at most half full, so an empty slot is always reached
         while (true) {
-            unsigned long long cur = __hip_atomic_load(s.table + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (cur == kEmpty) {
-                cur = atomicCAS(s.table + slot, kEmpty, mine);
-                if (cur == kEmpty) break;                       // claimed
-            }
+            // try to claim straight away: one round trip when the slot is free (the common case)
+            const unsigned long long cur = atomicCAS(s.table + slot, kEmpty, mine);
+            if (cur == kEmpty) break;                           // claimed
             if (static_cast<uint32_t>(cur >> 32) == static_cast<uint32_t>(id)) {
                 if (mine < cur) atomicMin(s.table + slot, mine);
                 break;
@@ -88,6 +96,9 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
     __shared__ uint32_t s_agg[1], s_excl[1];
     __shared__ ScanLookbackLds<1> s_look;
     const uint32_t tile = blockIdx.x;
+    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    // fetched before the device-side count has arrived; slot_of has room for n_in.host entries
+    const int32_t slot_early = j < n_in.host ? s.slot_of[j] : -1;
     const int64_t n = n_in.get();
     const int64_t n_tiles = (n + kBlock - 1) / kBlock;
     if (n == 0 && tile == 0 && threadIdx.x == 0) {
@@ -95,11 +106,10 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
         if (n_unique_out) *n_unique_out = 0;
     }
     if (static_cast<int64_t>(tile) >= n_tiles) return;
-    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
     uint32_t is_first = 0;
     int32_t id = 0;
     if (j < n) {
-        const int32_t slot = s.slot_of[j];
+        const int32_t slot = slot_early;
         if (slot >= 0) {
             id = ids[j];
             is_first = static_cast<uint32_t>(s.table[slot]) == static_cast<uint32_t>(j) ? 1u : 0u;

@@ -86,10 +86,10 @@ template <int L, int CPL, int R>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
     constexpr int kGroups = kBlock / L;
     stamp_start(a.clock);
-    const int64_t n = a.n.get();
     const int l = threadIdx.x % L;
     const int g = threadIdx.x / L;
     const int64_t step = static_cast<int64_t>(gridDim.x) * kGroups * R;
+    const int64_t n = a.n.get();
     for (int64_t k0 = (static_cast<int64_t>(blockIdx.x) * kGroups + g) * R; k0 < n; k0 += step) {
         chunk16 v[R][CPL];
         int64_t dst[R];

@@ -58,10 +58,15 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     __shared__ int32_t s_chosen[(G == kWave) ? kWavesPerBlock * kMaxFanout : 1];
 
     const uint32_t tile = blockIdx.x;
-    const int64_t n = a.n_frontier.get();
-    const int64_t n_tiles = (n + kGroups - 1) / kGroups;
+    const int group = threadIdx.x / G;
+    const int l = threadIdx.x % G;
+    const int64_t i = static_cast<int64_t>(tile) * kGroups + group;     // this group's frontier entry
     const uint64_t rng_seed = a.vars ? a.vars->rng_seed : a.rng_seed;
     const int32_t* frontier = (a.vars && a.hop == 0) ? a.vars->seeds : a.frontier;
+    // fetched before the device-side frontier size has arrived; the buffer holds n_frontier.host entries
+    const int32_t v_early = i < a.n_frontier.host ? frontier[i] : -1;
+    const int64_t n = a.n_frontier.get();
+    const int64_t n_tiles = (n + kGroups - 1) / kGroups;
     // side job: empty the hash table of the de-duplication that follows this hop
     for (uint32_t w = blockIdx.x * kBlock + threadIdx.x; w < a.clear_slots; w += gridDim.x * kBlock) a.clear_table[w] = ~0ull;
     if (tile == 0 && threadIdx.x == 0) {
@@ -74,16 +79,13 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     }
     if (static_cast<int64_t>(tile) >= n_tiles) return;
 
-    const int group = threadIdx.x / G;
-    const int l = threadIdx.x % G;
-    const int64_t i = static_cast<int64_t>(tile) * kGroups + group;     // this group's frontier entry
     const int f = a.fanout;
 
     // ---- row bounds and sample count (the lanes of a group read the same words)
     int32_t v = 0, deg = 0;
     int64_t base = 0;
     if (i < n) {
-        v = frontier[i];
+        v = v_early;
         if (l == 0 && a.frontier_out && a.frontier_out != frontier) a.frontier_out[i] = v;
         if (v < 0 || static_cast<int64_t>(v) >= a.n_nodes) {
             raise(a.err, kErrData);
