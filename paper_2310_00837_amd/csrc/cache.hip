@@ -4,9 +4,9 @@
 //
 // lookup_partition: one thread per ID reads rank[id] (one random 4-byte read),
 // classifies it into the HBM tier, the host tier or a miss by two compares, and
-// the three classes are compacted *stably* in one pass: wave ballots give the
-// in-wave ranks, LDS the in-workgroup ranks, and a three-counter chained scan
-// (scan.hpp) the ranks across workgroups.  The two hit lists (position, slot)
+// the three classes are compacted *stably* in one pass: a thread takes four
+// consecutive IDs, a workgroup scan gives the in-tile ranks and a three-counter
+// chained scan (scan.hpp) the ranks across workgroups.  The two hit lists (position, slot)
 // feed the row-copy kernels; the miss list (position, id, slot) is the request
 // list of the storage tier and comes out ascending in position.
 #include "kernels.hpp"
@@ -52,63 +52,66 @@ struct PartitionArgs {
 };
 
 __global__ __launch_bounds__(kBlock) void lookup_partition_kernel(PartitionArgs a) {
-    __shared__ uint32_t s_wave_cnt[3][kWavesPerBlock];
-    __shared__ uint32_t s_agg[3], s_excl[3];
+    __shared__ uint32_t s_wave[kWavesPerBlock + 1];
+    __shared__ uint32_t s_ticket, s_agg[3], s_excl[3];
     __shared__ ScanLookbackLds<3> s_look;
-    const uint32_t tile = blockIdx.x;
-    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
-    // the ID and its rank are fetched before the device-side count has arrived (ids has room for
-    // a.n.host entries; a value that is no node ID is simply not looked up)
-    int32_t id = j < a.n.host ? a.ids[j] : -1;
-    const bool id_ok = id >= 0 && static_cast<int64_t>(id) < a.n_nodes;
-    const int64_t r = id_ok ? static_cast<int64_t>(a.rank[id]) : 0;
     const int64_t n = a.n.get();
-    const int64_t n_tiles = (n + kBlock - 1) / kBlock;
-    if (n == 0 && tile == 0 && threadIdx.x == 0) {
+    const int64_t n_tiles = (n + kTileItems - 1) / kTileItems;
+    if (n == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
         a.lists.count[0] = a.lists.count[1] = a.lists.count[2] = 0;
         if (a.stats_out) { a.stats_out[0] = 0; a.stats_out[1] = 0; a.stats_out[2] = 0; a.stats_out[3] = 0; }
     }
-    if (static_cast<int64_t>(tile) >= n_tiles) return;
+    if (static_cast<int64_t>(blockIdx.x) >= n_tiles) return;
+    const uint32_t tile = scan_take_ticket(a.scan, static_cast<uint32_t>(n_tiles), &s_ticket);
 
-    int tier = -1;                       // -1: no ID here (tail of the last tile, or a bad ID)
-    int32_t slot = 0;
-    if (j < n) {
-        if (!id_ok) {
-            raise(a.err, kErrData);
-        } else {
-            if (r < a.n_hbm) { tier = 0; slot = static_cast<int32_t>(r); }
-            else if (r < a.n_hbm + a.n_host) { tier = 1; slot = static_cast<int32_t>(r - a.n_hbm); }
-            else { tier = 2; slot = static_cast<int32_t>(r - a.n_hbm - a.n_host); }
+    // a thread takes four consecutive IDs: all four rank reads are in flight together
+    const int64_t j0 = static_cast<int64_t>(tile) * kTileItems + static_cast<int64_t>(threadIdx.x) * kItemsPerThread;
+    int32_t id[kItemsPerThread], slot[kItemsPerThread];
+    int tier[kItemsPerThread];               // -1: no ID here (tail of the last tile, or a bad ID)
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) id[k] = j0 + k < n ? a.ids[j0 + k] : -1;
+    int64_t r[kItemsPerThread];
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        const bool ok = id[k] >= 0 && static_cast<int64_t>(id[k]) < a.n_nodes;
+        if (j0 + k < n && !ok) raise(a.err, kErrData);
+        r[k] = ok ? static_cast<int64_t>(a.rank[id[k]]) : -1;
+    }
+    uint32_t c_hbm = 0, c_host = 0, c_miss = 0;
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        tier[k] = -1;
+        slot[k] = 0;
+        if (r[k] >= 0) {
+            if (r[k] < a.n_hbm) { tier[k] = 0; slot[k] = static_cast<int32_t>(r[k]); ++c_hbm; }
+            else if (r[k] < a.n_hbm + a.n_host) { tier[k] = 1; slot[k] = static_cast<int32_t>(r[k] - a.n_hbm); ++c_host; }
+            else { tier[k] = 2; slot[k] = static_cast<int32_t>(r[k] - a.n_hbm - a.n_host); ++c_miss; }
         }
     }
-    // rank inside the wave, per class
-    const int lane = lane_id();
-    const unsigned long long below = (1ull << lane) - 1ull;
-    uint32_t in_wave = 0;
-#pragma unroll
-    for (int c = 0; c < 3; ++c) {
-        const unsigned long long m = __ballot(tier == c);
-        if (tier == c) in_wave = static_cast<uint32_t>(__popcll(m & below));
-        if (lane == 0) s_wave_cnt[c][wave_id()] = static_cast<uint32_t>(__popcll(m));
-    }
-    __syncthreads();
-    if (threadIdx.x < 3) {
-        uint32_t t = 0;
-        for (int w = 0; w < kWavesPerBlock; ++w) t += s_wave_cnt[threadIdx.x][w];
-        s_agg[threadIdx.x] = t;
+    // ranks inside the workgroup: the two hit classes share one scan (16 bits each, a tile has 1024 IDs)
+    uint32_t tot_hits, tot_miss;
+    const uint32_t before_hits = block_exclusive_scan(c_hbm | (c_host << 16), s_wave, tot_hits);
+    const uint32_t before_miss = block_exclusive_scan(c_miss, s_wave, tot_miss);
+    if (threadIdx.x == 0) {
+        s_agg[0] = tot_hits & 0xffffu;
+        s_agg[1] = tot_hits >> 16;
+        s_agg[2] = tot_miss;
     }
     scan_chained_prefix<3>(a.scan, tile, s_agg, s_excl, &s_look, a.err);
-    if (tier >= 0) {
-        uint32_t before = 0;
-        for (int w = 0; w < wave_id(); ++w) before += s_wave_cnt[tier][w];
-        const int64_t at = static_cast<int64_t>(s_excl[tier]) + before + in_wave;
-        if (tier < 2) {
-            a.lists.pos[tier][at] = static_cast<int32_t>(j);
-            a.lists.slot[tier][at] = slot;
-        } else if (at < a.miss_cap) {
-            a.miss_pos[at] = static_cast<int32_t>(j);
-            a.miss_id[at] = id;
-            a.miss_slot[at] = slot;
+    int64_t at[3] = {static_cast<int64_t>(s_excl[0]) + (before_hits & 0xffffu),
+                     static_cast<int64_t>(s_excl[1]) + (before_hits >> 16),
+                     static_cast<int64_t>(s_excl[2]) + before_miss};
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        if (tier[k] < 0) continue;
+        const int64_t w = tier[k] == 0 ? at[0]++ : tier[k] == 1 ? at[1]++ : at[2]++;
+        if (tier[k] < 2) {
+            a.lists.pos[tier[k]][w] = static_cast<int32_t>(j0 + k);
+            a.lists.slot[tier[k]][w] = slot[k];
+        } else if (w < a.miss_cap) {
+            a.miss_pos[w] = static_cast<int32_t>(j0 + k);
+            a.miss_id[w] = id[k];
+            a.miss_slot[w] = slot[k];
         }
     }
     if (static_cast<int64_t>(tile) == n_tiles - 1 && threadIdx.x == 0) {
@@ -145,7 +148,7 @@ hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count
                                    const ScanState& scan, int32_t* err) {
     PartitionArgs a{ids, n, rank, n_nodes, n_hbm, n_host, lists, miss_pos, miss_id, miss_slot, miss_cap,
                     stats_out, scan, err};
-    int64_t tiles = (n_max + kBlock - 1) / kBlock;
+    int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
     if (tiles < 1) tiles = 1;
     hipLaunchKernelGGL(lookup_partition_kernel, dim3(static_cast<unsigned>(tiles)), dim3(kBlock), 0, stream, a);
     return hipGetLastError();

@@ -82,4 +82,26 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
     return base + inc - v;
 }
 
+// Scan kernels give every thread kItemsPerThread consecutive items, so a tile is 1024 items and a
+// launch has few tiles (each tile costs a ticket, see scan.hpp).
+constexpr int kItemsPerThread = 4;
+constexpr int kTileItems = kBlock * kItemsPerThread;
+
+// min(deg(v), fanout): how many samples node v yields at a hop.  A value that is no node ID, or a
+// row of 2^31 entries or more, is reported and yields nothing.
+__device__ __forceinline__ uint32_t sample_count(const int64_t* offsets, int64_t n_nodes, int32_t v, int32_t fanout,
+                                                 int32_t* err) {
+    if (v < 0 || static_cast<int64_t>(v) >= n_nodes) {
+        raise(err, kErrData);
+        return 0;
+    }
+    const int64_t d = offsets[v + 1] - offsets[v];
+    if (d < 0 || d > 0x7fffffffLL) {
+        raise(err, kErrData);
+        return 0;
+    }
+    const int64_t f = fanout > 0 ? fanout : 0;
+    return static_cast<uint32_t>(d < f ? d : f);
+}
+
 }  // namespace helios

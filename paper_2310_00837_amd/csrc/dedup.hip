@@ -9,7 +9,8 @@
 //      the minimum orders by position).  The slot of every input is remembered.
 //   2. compact: input j is a first occurrence iff its slot's position is j; the
 //      flags are scanned in-workgroup and chained across workgroups, so the
-//      unique list comes out in input order in the same pass.
+//      unique list comes out in input order in the same pass.  Between hops
+//      this pass also counts the samples of every new frontier node.
 //   3. inverse (optional): every input looks up the unique index of its ID's
 //      first occurrence.
 // The table has at least twice as many slots as inputs and is cleared by the
@@ -88,47 +89,92 @@ __global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int
     }
 }
 
+// Pass 2.  Input j is a first occurrence iff its slot's position is j.  A thread takes four
+// consecutive inputs; the flags are scanned in the workgroup and chained across workgroups, so
+// `unique` comes out in input order.  When the unique list is the frontier of the next hop
+// (WITH_NEXT), the same pass reads every new frontier node's row bounds and scans the sample counts
+// min(deg, fanout) as a second counter, which gives that hop its indptr without a kernel of its own.
+template <bool WITH_NEXT>
 __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __restrict__ ids, Count n_in, DedupScratch s,
                                                                int32_t* unique, int64_t unique_cap,
                                                                int64_t* n_unique_dev, int64_t* n_unique_out,
-                                                               ScanState scan, int32_t* err) {
+                                                               NextHopCount next, ScanState scan, int32_t* err) {
+    constexpr int NC = WITH_NEXT ? 2 : 1;
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
-    __shared__ uint32_t s_agg[1], s_excl[1];
-    __shared__ ScanLookbackLds<1> s_look;
-    const uint32_t tile = blockIdx.x;
-    const int64_t j = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
-    // fetched before the device-side count has arrived; slot_of has room for n_in.host entries
-    const int32_t slot_early = j < n_in.host ? s.slot_of[j] : -1;
+    __shared__ uint32_t s_ticket, s_agg[NC], s_excl[NC];
+    __shared__ ScanLookbackLds<NC> s_look;
     const int64_t n = n_in.get();
-    const int64_t n_tiles = (n + kBlock - 1) / kBlock;
-    if (n == 0 && tile == 0 && threadIdx.x == 0) {
+    const int64_t n_tiles = (n + kTileItems - 1) / kTileItems;
+    if (n == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
         *n_unique_dev = 0;
         if (n_unique_out) *n_unique_out = 0;
-    }
-    if (static_cast<int64_t>(tile) >= n_tiles) return;
-    uint32_t is_first = 0;
-    int32_t id = 0;
-    if (j < n) {
-        const int32_t slot = slot_early;
-        if (slot >= 0) {
-            id = ids[j];
-            is_first = static_cast<uint32_t>(s.table[slot]) == static_cast<uint32_t>(j) ? 1u : 0u;
+        if (WITH_NEXT) {
+            next.indptr[0] = 0;
+            *next.n_flat_dev = 0;
+            if (next.size_out) { next.size_out[0] = 0; next.size_out[1] = 0; }
         }
     }
-    uint32_t tile_total;
-    const uint32_t local = block_exclusive_scan(is_first, s_wave, tile_total);
-    if (threadIdx.x == 0) s_agg[0] = tile_total;
-    scan_chained_prefix<1>(scan, tile, s_agg, s_excl, &s_look, err);
-    const int64_t at = static_cast<int64_t>(s_excl[0]) + local;
-    if (is_first) {
-        s.index_of_first[j] = static_cast<int32_t>(at);
-        if (at < unique_cap) unique[at] = id;
+    if (static_cast<int64_t>(blockIdx.x) >= n_tiles) return;
+    const uint32_t tile = scan_take_ticket(scan, static_cast<uint32_t>(n_tiles), &s_ticket);
+    const int64_t j0 = static_cast<int64_t>(tile) * kTileItems + static_cast<int64_t>(threadIdx.x) * kItemsPerThread;
+    int32_t slot[kItemsPerThread], id[kItemsPerThread];
+    uint32_t first[kItemsPerThread], cnt[kItemsPerThread];
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) slot[k] = j0 + k < n ? s.slot_of[j0 + k] : -1;
+    uint32_t n_first = 0, n_cnt = 0;
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        first[k] = 0;
+        cnt[k] = 0;
+        id[k] = 0;
+        if (slot[k] >= 0) {
+            id[k] = ids[j0 + k];
+            first[k] = static_cast<uint32_t>(s.table[slot[k]]) == static_cast<uint32_t>(j0 + k) ? 1u : 0u;
+        }
+    }
+    if (WITH_NEXT) {
+#pragma unroll
+        for (int k = 0; k < kItemsPerThread; ++k)
+            if (first[k]) cnt[k] = sample_count(next.offsets, next.n_nodes, id[k], next.fanout, err);
+    }
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) { n_first += first[k]; n_cnt += cnt[k]; }
+
+    uint32_t tile_first, tile_cnt = 0;
+    const uint32_t local_first = block_exclusive_scan(n_first, s_wave, tile_first);
+    uint32_t local_cnt = 0;
+    if (WITH_NEXT) local_cnt = block_exclusive_scan(n_cnt, s_wave, tile_cnt);
+    if (threadIdx.x == 0) {
+        s_agg[0] = tile_first;
+        if (WITH_NEXT) s_agg[NC - 1] = tile_cnt;
+    }
+    scan_chained_prefix<NC>(scan, tile, s_agg, s_excl, &s_look, err);
+    int64_t at = static_cast<int64_t>(s_excl[0]) + local_first;
+    int64_t at_cnt = WITH_NEXT ? static_cast<int64_t>(s_excl[NC - 1]) + local_cnt : 0;
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        if (first[k]) {
+            s.index_of_first[j0 + k] = static_cast<int32_t>(at);
+            if (at < unique_cap) {
+                unique[at] = id[k];
+                if (WITH_NEXT) next.indptr[at] = at_cnt;
+            }
+            at += 1;
+            at_cnt += cnt[k];
+        }
     }
     if (static_cast<int64_t>(tile) == n_tiles - 1 && threadIdx.x == 0) {
-        const int64_t total = static_cast<int64_t>(s_excl[0]) + tile_total;
+        const int64_t total = static_cast<int64_t>(s_excl[0]) + tile_first;
         *n_unique_dev = total;
         if (n_unique_out) *n_unique_out = total;
         if (total > unique_cap) raise(err, kErrCapacity);
+        if (WITH_NEXT) {
+            const int64_t total_cnt = static_cast<int64_t>(s_excl[NC - 1]) + tile_cnt;
+            next.indptr[total < unique_cap ? total : unique_cap] = total_cnt;
+            *next.n_flat_dev = total_cnt;
+            if (next.size_out) { next.size_out[0] = total; next.size_out[1] = total_cnt; }
+            if (total_cnt > next.flat_cap) raise(err, kErrCapacity);
+        }
     }
 }
 
@@ -155,17 +201,22 @@ unsigned grid_for(int64_t n_max, unsigned cap_blocks) {
 hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat,
                         int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
                         bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
-                        int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err) {
+                        int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next,
+                        const ScanState& scan, int32_t* err) {
     const dim3 block(kBlock);
     if (!table_is_clear)
         hipLaunchKernelGGL(dedup_clear_kernel, dim3(grid_for(s.n_slots, 2048)), block, 0, stream, s.table, s.n_slots);
     hipLaunchKernelGGL(dedup_insert_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, in, cat_out, n_total_dev,
                        n_nodes, s, err);
     const Count n{n_total_dev, n_max};
-    int64_t tiles = (n_max + kBlock - 1) / kBlock;
+    int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
     if (tiles < 1) tiles = 1;
-    hipLaunchKernelGGL(dedup_compact_kernel, dim3(static_cast<unsigned>(tiles)), block, 0, stream, ids_flat, n, s, unique,
-                       unique_cap, n_unique_dev, n_unique_out, scan, err);
+    if (next)
+        hipLaunchKernelGGL(dedup_compact_kernel<true>, dim3(static_cast<unsigned>(tiles)), block, 0, stream, ids_flat, n,
+                           s, unique, unique_cap, n_unique_dev, n_unique_out, *next, scan, err);
+    else
+        hipLaunchKernelGGL(dedup_compact_kernel<false>, dim3(static_cast<unsigned>(tiles)), block, 0, stream, ids_flat, n,
+                           s, unique, unique_cap, n_unique_dev, n_unique_out, NextHopCount{}, scan, err);
     if (inverse)
         hipLaunchKernelGGL(dedup_inverse_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, n, s, inverse);
     return hipGetLastError();

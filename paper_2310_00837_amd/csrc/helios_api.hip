@@ -60,6 +60,7 @@ struct helios_ctx {
     int32_t* cat = nullptr;
     unsigned long long* scan_status = nullptr;
     uint32_t scan_stride = 0;
+    uint32_t* scan_ticket = nullptr;           // device, zero between launches
     uint32_t epoch = 0;
 
     // recorded batches (HIP graphs): per-batch values live in device memory (vars), fed from a ring
@@ -147,7 +148,7 @@ int ensure_capacity(helios_ctx* c, int64_t n) {
     free_scratch(c);
     const int64_t cap = (n + 4095) / 4096 * 4096;
     const uint32_t slots = pow2_at_least(2 * cap);
-    const uint32_t stride = static_cast<uint32_t>(cap / (kBlock / kWave) + 2);   // most tiles: a hop with one wave per node
+    const uint32_t stride = static_cast<uint32_t>(cap / kTileItems + 2);
     HIP_TRY(c, hipMalloc(&c->dd.table, sizeof(unsigned long long) * slots));
     HIP_TRY(c, hipMalloc(&c->dd.slot_of, sizeof(int32_t) * cap));
     HIP_TRY(c, hipMalloc(&c->dd.index_of_first, sizeof(int32_t) * cap));
@@ -173,11 +174,11 @@ int next_scan(helios_ctx* c, ScanState* out) {
     }
     if (c->recording) {                       // the batch's base epoch is added on the device
         c->rec_scans += 1;
-        *out = ScanState{c->scan_status, c->scan_stride, c->rec_scans, c->vars};
+        *out = ScanState{c->scan_status, c->scan_ticket, c->scan_stride, c->rec_scans, c->vars};
         return HELIOS_OK;
     }
     c->epoch += 1;
-    *out = ScanState{c->scan_status, c->scan_stride, c->epoch, nullptr};
+    *out = ScanState{c->scan_status, c->scan_ticket, c->scan_stride, c->epoch, nullptr};
     return HELIOS_OK;
 }
 
@@ -233,7 +234,7 @@ uint32_t dedup_slots(const helios_ctx* c, int64_t n_max) {
 
 int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat, int32_t* cat_out,
                bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse, int64_t* n_unique_dev,
-               int64_t* n_unique_out) {
+               int64_t* n_unique_out, const NextHopCount* next) {
     ScanState scan;
     int rc = next_scan(c, &scan);
     if (rc) return rc;
@@ -242,7 +243,7 @@ int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t
     c->blocks_ready = false;
     c->last_slots = s.n_slots;
     HIP_TRY(c, launch_dedup(c->stream, in, n_max, ids_flat, cat_out, c->cnt + kCntCat, c->g.n_nodes, s, table_is_clear,
-                            unique, unique_cap, inverse, n_unique_dev, n_unique_out, scan, c->err));
+                            unique, unique_cap, inverse, n_unique_dev, n_unique_out, next, scan, c->err));
     return HELIOS_OK;
 }
 
@@ -254,27 +255,35 @@ ConcatArgs one_segment(const int32_t* ids, Count n) {
     return in;
 }
 
-// final_dedup_max > 0: the last hop also empties the hash table for a de-duplication of that many IDs
+// Hop 0: count pass over the seeds, sampling pass.  Hop h > 0: the de-duplication of flat_{h-1}
+// yields frontier_h together with its indptr, then the sampling pass.  Each sampling pass empties
+// the hash table of the de-duplication that follows it (final_dedup_max > 0: also the last one, for
+// a de-duplication of that many IDs).
 int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                 uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p,
                 int64_t final_dedup_max) {
+    const BatchVars* vars = c->recording ? c->vars : nullptr;
     Count nf{nullptr, n_seeds};
-    for (int h = 0; h < n_hops; ++h) {
+    {
         ScanState scan;
         int rc = next_scan(c, &scan);
         if (rc) return rc;
+        HIP_TRY(c, launch_frontier_count(c->stream, c->g, seeds, vars, hops[0].frontier, nf, n_seeds, fanouts[0],
+                                         hops[0].indptr, hops[0].flat_cap, c->cnt + kCntFlat + 0, sizes, scan, c->err));
+    }
+    for (int h = 0; h < n_hops; ++h) {
         const bool last = h + 1 == n_hops;
         const int64_t next_dedup = last ? final_dedup_max : p.flat_max[h];
         const uint32_t clear_slots = next_dedup > 0 || !last ? dedup_slots(c, next_dedup) : 0u;
-        HIP_TRY(c, launch_sample_hop(c->stream, c->g, h == 0 ? seeds : hops[h].frontier, hops[h].frontier, nf,
-                                     p.frontier_max[h], fanouts[h], h, rng_seed, c->recording ? c->vars : nullptr,
-                                     hops[h].indptr, hops[h].flat,
-                                     hops[h].flat_cap, c->cnt + kCntFlat + h, sizes ? sizes + 2 * h : nullptr,
-                                     clear_slots ? c->dd.table : nullptr, clear_slots, scan, c->err));
+        HIP_TRY(c, launch_sample_hop(c->stream, c->g, hops[h].frontier, hops[h].indptr, nf, p.frontier_max[h], fanouts[h],
+                                     h, rng_seed, vars, hops[h].flat, hops[h].flat_cap,
+                                     clear_slots ? c->dd.table : nullptr, clear_slots));
         if (!last) {
-            rc = dedup_impl(c, one_segment(hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}), p.flat_max[h],
-                            hops[h].flat, nullptr, true, hops[h + 1].frontier, hops[h + 1].frontier_cap, nullptr,
-                            c->cnt + kCntFrontier + h + 1, nullptr);
+            NextHopCount next{c->g.offsets, c->g.n_nodes, fanouts[h + 1], hops[h + 1].indptr, hops[h + 1].flat_cap,
+                              c->cnt + kCntFlat + h + 1, sizes ? sizes + 2 * (h + 1) : nullptr};
+            int rc = dedup_impl(c, one_segment(hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}), p.flat_max[h],
+                                hops[h].flat, nullptr, true, hops[h + 1].frontier, hops[h + 1].frontier_cap, nullptr,
+                                c->cnt + kCntFrontier + h + 1, nullptr, &next);
             if (rc) return rc;
             nf = Count{c->cnt + kCntFrontier + h + 1, p.frontier_max[h + 1]};
         }
@@ -351,6 +360,7 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipHostMalloc(reinterpret_cast<void**>(&c->err), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
               hipMalloc(&c->vars, sizeof(BatchVars)) == hipSuccess &&
+              hipMalloc(&c->scan_ticket, 64) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->vars_ring), sizeof(BatchVars) * kVarsRing, hipHostMallocDefault) == hipSuccess &&
               hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
@@ -360,6 +370,7 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;
         c->err[0] = c->err[1] = 0;
         ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
+             hipMemsetAsync(c->scan_ticket, 0, 64, c->stream) == hipSuccess &&
              hipStreamSynchronize(c->stream) == hipSuccess;
     }
     if (!ok) {
@@ -379,6 +390,7 @@ int helios_destroy(helios_ctx* c) {
     (void)hipFree(c->rank);
     (void)hipFree(c->cnt);
     (void)hipFree(c->vars);
+    (void)hipFree(c->scan_ticket);
     if (c->vars_ring) (void)hipHostFree(c->vars_ring);
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
@@ -493,7 +505,7 @@ int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* uniq
     int rc = ensure_capacity(c, n_ids);
     if (rc) return rc;
     return dedup_impl(c, one_segment(ids, Count{nullptr, n_ids}), n_ids, ids, nullptr, false, unique, unique_cap, inverse,
-                      c->cnt + kCntUnique, n_unique);
+                      c->cnt + kCntUnique, n_unique, nullptr);
 }
 
 int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, int32_t* miss_pos, int32_t* miss_id,
@@ -550,7 +562,8 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
         cat.src[h + 1] = hops[h].flat;
         cat.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
     }
-    rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique);
+    rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique,
+                    nullptr);
     if (rc) return rc;
     c->blocks_ready = true;
     c->last_n_seeds = n_seeds;

@@ -14,21 +14,21 @@ struct CsrView {
 };
 
 // ---- sample.hip
-// One hop: for i < n_frontier, indptr[i] = start of frontier[i]'s samples in flat,
-// indptr[n_frontier] = total; writes n_frontier and total to size_out[0], size_out[1]
-// (device-accessible, nullable) and total to *n_flat_dev.
-// lanes that share one node, and workgroups (= scan tiles) a hop needs
-int sample_group_lanes(int32_t fanout);
-int64_t sample_hop_tiles(int64_t n_frontier_max, int32_t fanout);
-// frontier_out (nullable, may equal frontier_in) receives a copy of the frontier; clear_table
-// (nullable) is set to all ones over clear_slots words on the way (the hash table of the
-// de-duplication that follows the hop).
-hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier_in, int32_t* frontier_out,
+// Count pass of hop 0: indptr[i] = start of frontier[i]'s samples in flat, indptr[n] = total
+// (also to *n_flat_dev); size_out (nullable, device-accessible) gets {n, total}.  frontier_out
+// (nullable, may equal frontier) receives a copy of the frontier; vars (nullable): the frontier
+// is vars->seeds.  The later hops get their indptr from launch_dedup.
+hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchVars* vars,
+                                 int32_t* frontier_out, Count n, int64_t n_max, int32_t fanout, int64_t* indptr,
+                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, const ScanState& scan,
+                                 int32_t* err);
+// Sampling pass: flat[indptr[i] + k] = k-th sample of frontier[i].  vars (nullable) overrides
+// rng_seed.  clear_table (nullable) is set to all ones over clear_slots words on the way (the hash
+// table of the de-duplication that follows the hop).
+hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, const int64_t* indptr,
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
-                             const BatchVars* vars /* nullable: overrides rng_seed and the hop-0 frontier */,
-                             int64_t* indptr, int32_t* flat, int64_t flat_cap, int64_t* n_flat_dev,
-                             int64_t* size_out, unsigned long long* clear_table, uint32_t clear_slots,
-                             const ScanState& scan, int32_t* err);
+                             const BatchVars* vars, int32_t* flat, int64_t flat_cap, unsigned long long* clear_table,
+                             uint32_t clear_slots);
 
 // ---- dedup.hip
 struct DedupScratch {
@@ -44,6 +44,18 @@ struct ConcatArgs {
     int n_seg;
     const BatchVars* vars;       // nullable: if set, segment 0 is vars->seeds
 };
+// What the de-duplication between two hops also computes for the hop that follows: the sample
+// counts min(deg, fanout) of the new frontier, scanned into indptr (indptr[n_unique] = total, also
+// to *n_flat_dev); size_out (nullable, device-accessible) gets {n_unique, total}.
+struct NextHopCount {
+    const int64_t* offsets;
+    int64_t n_nodes;
+    int32_t fanout;
+    int64_t* indptr;
+    int64_t flat_cap;
+    int64_t* n_flat_dev;
+    int64_t* size_out;
+};
 // De-duplicates the concatenation of the segments of `in` (n_max bounds its length).  ids_flat is
 // where the concatenation can be indexed: the single segment itself, or cat_out, which the first
 // pass then fills.  *n_total_dev receives the input length.  table_is_clear: an earlier kernel on the
@@ -51,7 +63,8 @@ struct ConcatArgs {
 hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat,
                         int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
                         bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
-                        int64_t* n_unique_dev, int64_t* n_unique_out, const ScanState& scan, int32_t* err);
+                        int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next /* nullable */,
+                        const ScanState& scan, int32_t* err);
 
 // ---- cache.hip
 hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n_nodes, int32_t* rank, int32_t* err);

@@ -1,18 +1,24 @@
 // Single-pass chained prefix sum across workgroups (decoupled look-back).
 //
-// Workgroup b owns tile b.  A tile publishes its aggregate, then looks back
-// over its predecessors, 256 at a time, until it meets one that has published a
-// full inclusive prefix.  One 64-bit status word per tile and counter holds
+// Each participating workgroup owns one tile, taken in start order from a
+// ticket counter.  A tile publishes its aggregate, then looks back over its
+// predecessors, 256 at a time, until it meets one that has published a full
+// inclusive prefix.  One 64-bit status word per tile and counter holds
 // {epoch:30, flag:2, value:32}; the epoch changes on every launch, so a stale
 // word reads as "not published" and the buffer never needs clearing between
 // launches.
 //
-// A tile waits only for tiles with a smaller index.  Workgroups are started in
-// index order, so those are running or done, and nothing a tile does before it
-// publishes depends on another tile: the wait ends.  (A ticket counter would
-// make that order explicit, but every workgroup of a launch would then hit one
-// address with a device-scope atomic; measured on this part that serialises at
-// ~20 ns per workgroup and was most of the run time of every scan kernel.)
+// Why tickets: a tile waits only for tiles with a smaller index, and with
+// tickets those have all started already, whatever else runs on the GPU.  With
+// tile = workgroup index that is not so once several scan kernels from
+// different streams oversubscribe the chip: the waiting workgroups of one
+// kernel can hold the slots of an XCD on which another kernel's lower tile is
+// still to start, and the other way round (seen on this part with six streams:
+// the bounded wait below fired).  The price is one device-scope atomic on one
+// address per participating workgroup, which serialises at ~20 ns each, so the
+// kernels keep the number of tiles low: 1024 items per tile, and only
+// workgroups that own a tile take a ticket.
+//
 // The wait is bounded all the same: after kScanSpinBudget polls a tile gives up,
 // records kErrInternal and carries on with a zero, so a launch always drains
 // and the caller gets an error instead of a hang.
@@ -23,6 +29,7 @@ namespace helios {
 
 struct ScanState {
     unsigned long long* status;   // [n_counters][stride]
+    uint32_t* ticket;             // one counter, zero between launches
     uint32_t stride;              // tiles the status rows have room for
     uint32_t epoch;               // 1 .. 2^30-1, new for every launch
     const BatchVars* vars;        // nullable: if set, vars->epoch_base is added to epoch on the device
@@ -49,6 +56,22 @@ __device__ __forceinline__ unsigned long long scan_load(unsigned long long* p) {
 }
 
 constexpr uint32_t kScanSpinBudget = 1u << 20;     // polls of one status word before giving up (about a second)
+
+// Tile index of this workgroup: its place in the start order of the n_tiles workgroups that take
+// part (the caller lets exactly the workgroups with blockIdx.x < n_tiles call this).  The one that
+// draws the last ticket puts the counter back to zero for the next launch: by then every other
+// participant has drawn.  Contains barriers; s_ticket is one word of LDS.
+__device__ __forceinline__ uint32_t scan_take_ticket(const ScanState& st, uint32_t n_tiles, uint32_t* s_ticket) {
+    if (threadIdx.x == 0) {
+        const uint32_t t = atomicAdd(st.ticket, 1u);
+        if (t == n_tiles - 1) __hip_atomic_store(st.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_ticket = t;
+    }
+    __syncthreads();
+    const uint32_t t = *s_ticket;
+    __syncthreads();
+    return t;
+}
 
 // LDS the look-back needs: per counter and wave, {prefix seen, partial sum}.
 template <int NC>
