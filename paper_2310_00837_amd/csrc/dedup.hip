@@ -120,25 +120,27 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
     int32_t slot[kItemsPerThread], id[kItemsPerThread];
     uint32_t first[kItemsPerThread], cnt[kItemsPerThread];
 #pragma unroll
-    for (int k = 0; k < kItemsPerThread; ++k) slot[k] = j0 + k < n ? s.slot_of[j0 + k] : -1;
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        slot[k] = j0 + k < n ? s.slot_of[j0 + k] : -1;
+        id[k] = j0 + k < n ? ids[j0 + k] : 0;
+    }
+    // The table word and, between hops, the row bounds are fetched together: the bounds of a
+    // repeated ID are read for nothing, but they are in cache and nobody waits for the flag first.
+    unsigned long long word[kItemsPerThread];
+#pragma unroll
+    for (int k = 0; k < kItemsPerThread; ++k) {
+        word[k] = slot[k] >= 0 ? s.table[slot[k]] : ~0ull;
+        cnt[k] = 0;
+        if (WITH_NEXT && slot[k] >= 0) cnt[k] = sample_count(next.offsets, next.n_nodes, id[k], next.fanout, err);
+    }
     uint32_t n_first = 0, n_cnt = 0;
 #pragma unroll
     for (int k = 0; k < kItemsPerThread; ++k) {
-        first[k] = 0;
-        cnt[k] = 0;
-        id[k] = 0;
-        if (slot[k] >= 0) {
-            id[k] = ids[j0 + k];
-            first[k] = static_cast<uint32_t>(s.table[slot[k]]) == static_cast<uint32_t>(j0 + k) ? 1u : 0u;
-        }
+        first[k] = slot[k] >= 0 && static_cast<uint32_t>(word[k]) == static_cast<uint32_t>(j0 + k) ? 1u : 0u;
+        if (!first[k]) cnt[k] = 0;
+        n_first += first[k];
+        n_cnt += cnt[k];
     }
-    if (WITH_NEXT) {
-#pragma unroll
-        for (int k = 0; k < kItemsPerThread; ++k)
-            if (first[k]) cnt[k] = sample_count(next.offsets, next.n_nodes, id[k], next.fanout, err);
-    }
-#pragma unroll
-    for (int k = 0; k < kItemsPerThread; ++k) { n_first += first[k]; n_cnt += cnt[k]; }
 
     uint32_t tile_first, tile_cnt = 0;
     const uint32_t local_first = block_exclusive_scan(n_first, s_wave, tile_first);

@@ -62,6 +62,7 @@ constexpr uint32_t kScanSpinBudget = 1u << 20;     // polls of one status word b
 // draws the last ticket puts the counter back to zero for the next launch: by then every other
 // participant has drawn.  Contains barriers; s_ticket is one word of LDS.
 __device__ __forceinline__ uint32_t scan_take_ticket(const ScanState& st, uint32_t n_tiles, uint32_t* s_ticket) {
+    if (n_tiles == 1) return 0;               // a single tile waits for nobody: no ticket, no atomic
     if (threadIdx.x == 0) {
         const uint32_t t = atomicAdd(st.ticket, 1u);
         if (t == n_tiles - 1) __hip_atomic_store(st.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
