@@ -49,28 +49,36 @@ __device__ __forceinline__ void stamp_end(unsigned long long* clock) {
     }
 }
 
-__global__ __launch_bounds__(kBlock) void clock_publish_kernel(const unsigned long long* clock, unsigned n_blocks,
-                                                               unsigned long long* host_out) {
-    __shared__ unsigned long long s_lo[kBlock], s_hi[kBlock];
+constexpr int kPublishThreads = 1024;
+
+__global__ __launch_bounds__(kPublishThreads) void clock_publish_kernel(const unsigned long long* clock, unsigned n_blocks,
+                                                                        unsigned long long* host_out) {
+    __shared__ unsigned long long s_lo[kPublishThreads / kWave], s_hi[kPublishThreads / kWave];
     unsigned long long lo = ~0ull, hi = 0ull;
-    for (unsigned b = threadIdx.x; b < n_blocks; b += kBlock) {
+#pragma unroll 8
+    for (unsigned b = threadIdx.x; b < n_blocks; b += kPublishThreads) {      // independent loads, issued together
         const unsigned long long a = clock[b], z = clock[n_blocks + b];
         lo = a < lo ? a : lo;
         hi = z > hi ? z : hi;
     }
-    s_lo[threadIdx.x] = lo;
-    s_hi[threadIdx.x] = hi;
-    __syncthreads();
-    for (int d = kBlock / 2; d > 0; d >>= 1) {
-        if (static_cast<int>(threadIdx.x) < d) {
-            if (s_lo[threadIdx.x + d] < s_lo[threadIdx.x]) s_lo[threadIdx.x] = s_lo[threadIdx.x + d];
-            if (s_hi[threadIdx.x + d] > s_hi[threadIdx.x]) s_hi[threadIdx.x] = s_hi[threadIdx.x + d];
-        }
-        __syncthreads();
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) {
+        const unsigned long long lo2 = __shfl_xor(lo, d, kWave), hi2 = __shfl_xor(hi, d, kWave);
+        lo = lo2 < lo ? lo2 : lo;
+        hi = hi2 > hi ? hi2 : hi;
     }
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        s_lo[threadIdx.x / kWave] = lo;
+        s_hi[threadIdx.x / kWave] = hi;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        host_out[0] = s_lo[0];
-        host_out[1] = s_hi[0];
+        for (int w = 1; w < kPublishThreads / kWave; ++w) {
+            lo = s_lo[w] < lo ? s_lo[w] : lo;
+            hi = s_hi[w] > hi ? s_hi[w] : hi;
+        }
+        host_out[0] = lo;
+        host_out[1] = hi;
     }
 }
 
@@ -167,7 +175,7 @@ hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* ds
 }
 
 hipError_t launch_clock_publish(hipStream_t stream, const uint64_t* clock, unsigned n_blocks, uint64_t* host_out) {
-    hipLaunchKernelGGL(clock_publish_kernel, dim3(1), dim3(kBlock), 0, stream,
+    hipLaunchKernelGGL(clock_publish_kernel, dim3(1), dim3(kPublishThreads), 0, stream,
                        reinterpret_cast<const unsigned long long*>(clock), n_blocks,
                        reinterpret_cast<unsigned long long*>(host_out));
     return hipGetLastError();

@@ -392,3 +392,50 @@ def test_three_batches_in_flight(helios, oracle, workloads):
         check(b)
     for ctx in lanes:
         ctx.close()
+
+
+def test_many_streams_with_large_scans(helios, oracle):
+    """Six contexts on six streams, each with scan kernels of about 1500 tiles queued back to back:
+    more waiting workgroups than the chip holds at once.  Every tile must still only wait for tiles
+    that have started (no HELIOS_EINTERNAL, no hang), and every result must match the oracle."""
+    dev = torch.device("cuda", 0)
+    n_nodes, n_ids, lanes = 3_000_000, 1_500_000, 6
+    rng = np.random.default_rng(21)
+    off = torch.zeros(n_nodes + 1, dtype=torch.int64, device=dev)
+    idx = torch.zeros(1, dtype=torch.int32, device=dev)
+    order = torch.from_numpy(rng.permutation(n_nodes).astype(np.int32)).to(dev)
+    table = torch.zeros((1, 16), dtype=torch.uint8, device=dev)
+    ctxs, bufs = [], []
+    for k in range(lanes):
+        ctx = helios.Helios(0, stream=torch.cuda.Stream(device=dev))
+        ctx.csr_load(off, idx)
+        ctx.cache_build(order, 0, 0, 16, None, None, None)        # every ID is a miss: the miss list is the third scan
+        ids = rng.integers(0, n_nodes, n_ids).astype(np.int32)
+        ids[rng.random(n_ids) < 0.3] = ids[0]                     # a hot ID, as a sampled hub is
+        bufs.append(dict(ids_np=ids, ids=torch.from_numpy(ids).to(dev),
+                         uniq=torch.empty(n_ids, dtype=torch.int32, device=dev), inv=torch.empty(n_ids, dtype=torch.int32, device=dev),
+                         nu=torch.zeros(1, dtype=torch.int64).pin_memory(), out=torch.zeros((n_ids, 16), dtype=torch.uint8, device=dev),
+                         mp=torch.empty(n_ids, dtype=torch.int32, device=dev), mi=torch.empty(n_ids, dtype=torch.int32, device=dev),
+                         ms=torch.empty(n_ids, dtype=torch.int32, device=dev), stats=torch.zeros(4, dtype=torch.int64).pin_memory()))
+        ctx.reserve(n_ids)
+        ctxs.append(ctx)
+    for ctx in ctxs:
+        ctx.sync()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for ctx, b in zip(ctxs, bufs):                            # queue everything, then wait
+            ctx.dedup(b["ids"], b["uniq"], b["inv"], b["nu"])
+            ctx.gather(b["ids"], b["out"], b["mp"], b["mi"], b["ms"], b["stats"])
+        for ctx in ctxs:
+            ctx.sync()
+        print(" rep", rep, "done", flush=True)
+    rank = oracle.rank_build(order.cpu().numpy())
+    for ctx, b in zip(ctxs, bufs):
+        wu, wi = oracle.dedup(n_nodes, b["ids_np"])
+        assert int(b["nu"][0]) == wu.size
+        assert np.array_equal(b["uniq"][:wu.size].cpu().numpy(), wu) and np.array_equal(b["inv"].cpu().numpy(), wi)
+        assert b["stats"].tolist() == [n_ids, 0, 0, n_ids]
+        assert np.array_equal(b["mp"].cpu().numpy(), np.arange(n_ids, dtype=np.int32))
+        assert np.array_equal(b["ms"].cpu().numpy(), rank[b["ids_np"]])
+        ctx.close()
+    del table
