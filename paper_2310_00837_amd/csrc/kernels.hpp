@@ -82,7 +82,7 @@ hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count
 
 // ---- gather.hip
 // out[pos[k], :] = table[slot[k], :] for k < n; pos == nullptr means pos[k] = k.
-// `wide` selects the launch shape tuned for a far (host-link) source.
+// far_source selects the launch shape for a source behind the host link (few workgroups, one per CU).
 // clock (nullable): device uint64[2 * kGatherMaxBlocks]; workgroup b stores its first and last tick of
 // the constant-rate device clock at [b] and [blocks + b]; *blocks_out = workgroups launched.
 // launch_clock_publish reduces them to {earliest start, latest end} in pinned host memory.
