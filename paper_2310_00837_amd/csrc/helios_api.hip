@@ -234,7 +234,7 @@ uint32_t dedup_slots(const helios_ctx* c, int64_t n_max) {
 
 int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat, int32_t* cat_out,
                bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse, int64_t* n_unique_dev,
-               int64_t* n_unique_out, const NextHopCount* next) {
+               int64_t* n_unique_out, const NextHopCount* next, const LookupOut* look) {
     ScanState scan;
     int rc = next_scan(c, &scan);
     if (rc) return rc;
@@ -243,7 +243,7 @@ int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t
     c->blocks_ready = false;
     c->last_slots = s.n_slots;
     HIP_TRY(c, launch_dedup(c->stream, in, n_max, ids_flat, cat_out, c->cnt + kCntCat, c->g.n_nodes, s, table_is_clear,
-                            unique, unique_cap, inverse, n_unique_dev, n_unique_out, next, scan, c->err));
+                            unique, unique_cap, inverse, n_unique_dev, n_unique_out, next, look, scan, c->err));
     return HELIOS_OK;
 }
 
@@ -283,7 +283,7 @@ int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int3
                               c->cnt + kCntFlat + h + 1, sizes ? sizes + 2 * (h + 1) : nullptr};
             int rc = dedup_impl(c, one_segment(hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}), p.flat_max[h],
                                 hops[h].flat, nullptr, true, hops[h + 1].frontier, hops[h + 1].frontier_cap, nullptr,
-                                c->cnt + kCntFrontier + h + 1, nullptr, &next);
+                                c->cnt + kCntFrontier + h + 1, nullptr, &next, nullptr);
             if (rc) return rc;
             nf = Count{c->cnt + kCntFrontier + h + 1, p.frontier_max[h + 1]};
         }
@@ -291,15 +291,26 @@ int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int3
     return HELIOS_OK;
 }
 
+TierLists tier_lists(helios_ctx* c) {
+    return TierLists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier};
+}
+
+int copy_tiers(helios_ctx* c, Count n, void* out);
+
 int gather_impl(helios_ctx* c, const int32_t* ids, Count n, void* out, int32_t* miss_pos, int32_t* miss_id,
                 int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
     ScanState scan;
     int rc = next_scan(c, &scan);
     if (rc) return rc;
-    TierLists lists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier};
-    HIP_TRY(c, launch_lookup_partition(c->stream, ids, n, n.host, c->rank, c->g.n_nodes, c->n_hbm, c->n_host, lists,
-                                       miss_pos, miss_id, miss_slot, miss_cap, reinterpret_cast<int64_t*>(stats), scan,
-                                       c->err));
+    HIP_TRY(c, launch_lookup_partition(c->stream, ids, n, n.host, c->rank, c->g.n_nodes, c->n_hbm, c->n_host,
+                                       tier_lists(c), miss_pos, miss_id, miss_slot, miss_cap,
+                                       reinterpret_cast<int64_t*>(stats), scan, c->err));
+    return copy_tiers(c, n, out);
+}
+
+// The two row copies over the per-tier lists that a lookup has left behind; n bounds the lists.
+int copy_tiers(helios_ctx* c, Count n, void* out) {
+    const TierLists lists = tier_lists(c);
     c->timed_hbm = c->timed_host = false;
     const bool do_hbm = c->n_hbm > 0 && n.host > 0, do_host = c->n_host > 0 && n.host > 0;
     const bool fork = do_host && !c->serial_tiers;
@@ -505,7 +516,7 @@ int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* uniq
     int rc = ensure_capacity(c, n_ids);
     if (rc) return rc;
     return dedup_impl(c, one_segment(ids, Count{nullptr, n_ids}), n_ids, ids, nullptr, false, unique, unique_cap, inverse,
-                      c->cnt + kCntUnique, n_unique, nullptr);
+                      c->cnt + kCntUnique, n_unique, nullptr, nullptr);
 }
 
 int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, int32_t* miss_pos, int32_t* miss_id,
@@ -562,8 +573,11 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
         cat.src[h + 1] = hops[h].flat;
         cat.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
     }
+    // the final de-duplication classifies the unique IDs by cache tier in the same pass
+    LookupOut look{c->rank, c->n_hbm, c->n_host, tier_lists(c), miss_pos, miss_id, miss_slot, miss_cap,
+                   reinterpret_cast<int64_t*>(stats)};
     rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique,
-                    nullptr);
+                    nullptr, &look);
     if (rc) return rc;
     c->blocks_ready = true;
     c->last_n_seeds = n_seeds;
@@ -573,7 +587,7 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
         c->last_flat_max[h] = p.flat_max[h];
     }
     const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
-    return gather_impl(c, unique, Count{c->cnt + kCntUnique, u_max}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+    return copy_tiers(c, Count{c->cnt + kCntUnique, u_max}, out);
 }
 
 int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,

@@ -56,6 +56,21 @@ struct NextHopCount {
     int64_t* n_flat_dev;
     int64_t* size_out;
 };
+struct TierLists {
+    int32_t* pos[2];    // positions in the ID list, per cached tier (0 = HBM, 1 = host)
+    int32_t* slot[2];   // row in the tier table
+    int64_t* count;     // device int64[3]: tier 0, tier 1, misses
+};
+// What the batch's final de-duplication also computes: the cache lookup of the unique IDs (see
+// launch_lookup_partition, whose outputs these are, with positions = indices into `unique`).
+struct LookupOut {
+    const int32_t* rank;
+    int64_t n_hbm, n_host;
+    TierLists lists;
+    int32_t *miss_pos, *miss_id, *miss_slot;
+    int64_t miss_cap;
+    int64_t* stats_out;          // device-accessible int64[4], nullable
+};
 // De-duplicates the concatenation of the segments of `in` (n_max bounds its length).  ids_flat is
 // where the concatenation can be indexed: the single segment itself, or cat_out, which the first
 // pass then fills.  *n_total_dev receives the input length.  table_is_clear: an earlier kernel on the
@@ -64,16 +79,12 @@ hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max,
                         int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
                         bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
                         int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next /* nullable */,
-                        const ScanState& scan, int32_t* err);
+                        const LookupOut* look /* nullable; not together with next */, const ScanState& scan,
+                        int32_t* err);
 
 // ---- cache.hip
 hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n_nodes, int32_t* rank, int32_t* err);
 
-struct TierLists {
-    int32_t* pos[2];    // positions in the ID list, per cached tier (0 = HBM, 1 = host)
-    int32_t* slot[2];   // row in the tier table
-    int64_t* count;     // device int64[3]: tier 0, tier 1, misses
-};
 hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max,
                                    const int32_t* rank, int64_t n_nodes, int64_t n_hbm, int64_t n_host,
                                    const TierLists& lists, int32_t* miss_pos, int32_t* miss_id,
