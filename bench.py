@@ -56,6 +56,7 @@ def main() -> int:
                     help="mini-batches in flight during the timed region (each on its own context and stream)")
     ap.add_argument("--threads", type=int, default=0, help="0: one host thread drives all lanes (default, fastest); 1: one host thread per lane")
     ap.add_argument("--graph", type=int, default=1, help="1: replay a recorded batch (HIP graph) per step; 0: launch directly")
+    ap.add_argument("--hbm-blocks", type=int, default=0, help="workgroups of the HBM-tier copy (0 = library default)")
     ap.add_argument("--host-blocks", type=int, default=0, help="workgroups of the host-link copies (0 = library default)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
@@ -166,6 +167,8 @@ def main() -> int:
         ctx.sync()
         if args.host_blocks:
             ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
+        if args.hbm_blocks:
+            ctx.set_param(helios.PARAM_HBM_GATHER_BLOCKS, args.hbm_blocks)
         lanes.append(Lane(ctx, st))
     torch.cuda.synchronize()
     if args.graph:
