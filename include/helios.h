@@ -235,11 +235,17 @@ int helios_calibration_copy(helios_ctx *ctx, const void *src, void *dst, int64_t
  * leave more of the memory system to the HBM-tier copy that runs beside them,
  * cf. Sec. 3.3 "Operator Resources Allocation").  SERIAL_TIERS: non-zero (the
  * default) runs the host-tier copy after the HBM-tier copy on the context's
- * stream; zero runs the two side by side on two streams. */
+ * stream; zero runs the two side by side on two streams.
+ * MISSQ_TIMEOUT_US: how long a wave of helios_missq_complete's kernel waits
+ * without seeing a new completion before it gives up (default 2 000 000);
+ * MISSQ_WAVES: waves of that kernel (0 = default 256; at least one per 64
+ * queues, at most one per queue). */
 typedef enum {
     HELIOS_PARAM_HBM_GATHER_BLOCKS = 1,
     HELIOS_PARAM_HOST_GATHER_BLOCKS = 2,
-    HELIOS_PARAM_SERIAL_TIERS = 3
+    HELIOS_PARAM_SERIAL_TIERS = 3,
+    HELIOS_PARAM_MISSQ_TIMEOUT_US = 4,
+    HELIOS_PARAM_MISSQ_WAVES = 5
 } helios_param;
 int helios_set_param(helios_ctx *ctx, int param, int64_t value);
 
@@ -266,6 +272,55 @@ int helios_plan_create(helios_ctx *ctx, int64_t n_seeds, const int32_t *fanouts,
                        int64_t miss_cap, helios_gather_stats *stats, helios_plan **plan_out);
 int helios_plan_launch(helios_plan *plan, const int32_t *seeds, uint64_t rng_seed);
 int helios_plan_destroy(helios_plan *plan);
+
+/* Asynchronous service of the miss list in the shape of the GPU-initiated IO
+ * stack of Sec. 3.1, with host threads over the storage stand-in in the place
+ * of the SSDs: a submission kernel (Sec. 3.1.1: one thread per miss builds a
+ * command {storage row, staging row} and writes it to one of n_queues
+ * submission queues; each queue's doorbell is rung once, after all commands
+ * are written), service threads (a thread owns every n_service_threads-th
+ * queue, copies each command's row from the stand-in table into a pinned
+ * staging buffer and posts a completion entry, not in submission order), and
+ * a completion kernel (Sec. 3.1.2: a wave owns several completion queues,
+ * polls their entries and moves completed rows from the staging buffer to
+ * out[miss_pos]).  Nothing on the GPU waits between the two kernels.  The
+ * result equals helios_gather_miss's.
+ *
+ * helios_missq_create: queue memory for up to n_queues * queue_depth misses
+ * per round (1..4096 queues of 1..2^20 entries; the staging buffer of that
+ * many rows must stay below 8 GiB) on the context's current cache; starts the
+ * service threads (0..64; with 0 nothing is ever served: for tests of the
+ * time limit).  The queue is bound to the context and to that cache: after
+ * another helios_cache_build its calls return HELIOS_ESTATE.
+ * helios_missq_submit enqueues the submission kernel on the context's stream
+ * (arguments as helios_gather_miss); helios_missq_complete enqueues the
+ * completion kernel.  The two alternate (else HELIOS_ESTATE): one round at a
+ * time per queue; to keep several batches in flight give each context a queue.
+ * A round with more misses than the queues hold reports HELIOS_ECAPACITY at
+ * helios_sync and serves the first n_queues * queue_depth.  If the service
+ * stops answering (or met a command it had to refuse: helios_missq_faulted
+ * returns 1), the completion kernel ends after the time limit and
+ * helios_sync returns HELIOS_EINTERNAL; the queue must then be destroyed.
+ * helios_missq_attach(ctx, q): from now on every helios_prepare_batch and
+ * every batch recorded by helios_plan_create on ctx submits its own miss list
+ * right after the cache lookup, before the cached tiers are copied, so the
+ * service runs beside those copies; the caller follows each batch with
+ * helios_missq_complete.  q = NULL detaches.  A recorded batch can only be
+ * launched while the queue it was recorded with is attached.
+ * helios_missq_destroy waits for the stream, detaches the queue and stops the
+ * threads; destroy a queue before its context. */
+typedef struct helios_missq helios_missq;
+int helios_missq_create(helios_ctx *ctx, int32_t n_queues, int32_t queue_depth,
+                        int32_t n_service_threads, helios_missq **out);
+int helios_missq_submit(helios_missq *q, const int32_t *miss_pos, const int32_t *miss_slot,
+                        int64_t n_miss_max, const int64_t *n_miss_dev);
+int helios_missq_complete(helios_missq *q, void *out);
+int helios_missq_attach(helios_ctx *ctx, helios_missq *q);
+int helios_missq_faulted(const helios_missq *q);
+/* out[0] = rounds opened, out[1] = rounds every service thread has finished,
+ * out[2] = commands served since the queue was created */
+int helios_missq_counters(const helios_missq *q, int64_t *out3);
+int helios_missq_destroy(helios_missq *q);
 
 /* Timing of the two row-copy kernels (HBM tier, host tier) of the last
  * helios_gather / helios_prepare_batch on this context.  Level 1: every

@@ -34,7 +34,7 @@ struct BatchVars {
     uint64_t rng_seed;
     const int32_t* seeds;
     uint32_t epoch_base;     // added to the per-launch epoch of the chained scans
-    uint32_t pad;
+    uint32_t io_round;       // round number of the miss queue the batch submits to (0 if none)
 };
 
 // First error wins is not needed: any recorded error makes the call fail.

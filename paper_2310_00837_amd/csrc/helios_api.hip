@@ -1,117 +1,12 @@
 // Host runtime and C ABI of the Helios library: context, scratch memory,
 // launch order of the kernels, device-side error word.  See include/helios.h
 // for the contract of every entry point.
-#include "../../include/helios.h"
-#include "kernels.hpp"
-
-#include <cstdarg>
-#include <cstdio>
-#include <cstring>
+#include "context.hpp"
+#include "missq.hpp"
 
 using namespace helios;
 
 namespace {
-
-// device counters (int64 each)
-constexpr int kCntFrontier = 0;     // [HELIOS_MAX_HOPS + 1] frontier sizes
-constexpr int kCntFlat = 16;        // [HELIOS_MAX_HOPS] sample-list sizes
-constexpr int kCntCat = 32;         // length of [seeds | flat_0 | ...]
-constexpr int kCntUnique = 33;
-constexpr int kCntTier = 40;        // [3] HBM hits, host hits, misses
-constexpr int kNumCounters = 64;
-constexpr uint32_t kVarsRing = 256;   // batch launches that may be queued on a context without a helios_sync
-
-}  // namespace
-
-struct helios_ctx {
-    int device = 0;
-    hipStream_t stream = nullptr;
-    hipStream_t aux = nullptr;                 // host-tier row copies run here, beside the HBM-tier ones
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    int timing = 0;                            // 0 off, 1 device clock, 2 device clock + HIP events
-    hipEvent_t t_hbm[2] = {nullptr, nullptr}, t_host[2] = {nullptr, nullptr};
-    bool timed_hbm = false, timed_host = false;
-    uint64_t* clock = nullptr;                 // device [2][2 * kGatherMaxBlocks] workgroup ticks per tier copy
-    unsigned clock_blocks[2] = {0, 0};
-    uint64_t* clock_host = nullptr;            // pinned [2][2], written by the publish kernel
-    double clock_khz = 100000.0;
-    unsigned hbm_blocks = 0, host_blocks = 0;  // 0 = the launcher's default
-    bool serial_tiers = true;                  // the host-tier copy follows the HBM-tier copy (see helios_set_param)
-    char errmsg[256] = {0};
-
-    CsrView g{nullptr, nullptr, 0};
-    int64_t n_edges = 0;
-    bool has_graph = false;
-
-    int32_t* rank = nullptr;
-    int64_t rank_cap = 0;
-    int64_t n_hbm = 0, n_host = 0;
-    int32_t row_bytes = 0;
-    const void *hbm_table = nullptr, *host_table = nullptr, *standin_table = nullptr;
-    bool has_cache = false;
-
-    int32_t* err = nullptr;                    // pinned, GPU-mapped int32[2]
-    int64_t* cnt = nullptr;                    // device int64[kNumCounters]
-
-    int64_t cap_ids = 0;                       // IDs per call the scratch below has room for
-    DedupScratch dd{nullptr, 0, nullptr, nullptr};
-    int32_t* list_pos[2] = {nullptr, nullptr};
-    int32_t* list_slot[2] = {nullptr, nullptr};
-    int32_t* cat = nullptr;
-    unsigned long long* scan_status = nullptr;
-    uint32_t scan_stride = 0;
-    uint32_t* scan_ticket = nullptr;           // device, zero between launches
-    uint32_t epoch = 0;
-
-    // recorded batches (HIP graphs): per-batch values live in device memory (vars), fed from a ring
-    // of pinned slots; while recording, scans get epoch offsets 1, 2, ... instead of fresh epochs
-    BatchVars* vars = nullptr;                 // device
-    BatchVars* vars_ring = nullptr;            // pinned [kVarsRing]
-    uint32_t vars_next = 0, vars_unsynced = 0;
-    bool recording = false;
-    uint32_t rec_scans = 0;
-    uint64_t scratch_generation = 0;
-
-    // what the last helios_prepare_batch left behind for helios_make_blocks
-    bool blocks_ready = false;
-    uint32_t last_slots = 0;
-    int64_t last_n_seeds = 0;
-    int32_t last_n_hops = 0;
-    int64_t last_frontier_max[HELIOS_MAX_HOPS] = {0};
-    int64_t last_flat_max[HELIOS_MAX_HOPS] = {0};
-};
-
-namespace {
-
-int fail(helios_ctx* c, int code, const char* fmt, ...) {
-    if (c) {
-        va_list ap;
-        va_start(ap, fmt);
-        vsnprintf(c->errmsg, sizeof(c->errmsg), fmt, ap);
-        va_end(ap);
-    }
-    return code;
-}
-
-#define HIP_TRY(c, expr)                                                                       \
-    do {                                                                                       \
-        hipError_t e_ = (expr);                                                                \
-        if (e_ != hipSuccess) return fail((c), HELIOS_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
-    } while (0)
-
-// keeps the caller's current device
-struct DeviceGuard {
-    int prev = -1;
-    bool ok = false;
-    explicit DeviceGuard(int dev) {
-        if (hipGetDevice(&prev) == hipSuccess && (prev == dev || hipSetDevice(dev) == hipSuccess)) ok = true;
-        want = dev;
-    }
-    ~DeviceGuard() {
-        if (ok && prev != want) (void)hipSetDevice(prev);
-    }
-    int want;
-};
 
 uint32_t pow2_at_least(int64_t n) {
     uint32_t p = 1024;
@@ -476,6 +371,7 @@ int helios_cache_build(helios_ctx* c, const int32_t* order, int64_t hbm_rows, in
     c->host_table = host_table;
     c->standin_table = standin_table;
     c->has_cache = true;
+    c->cache_generation += 1;
     return HELIOS_OK;
 }
 
@@ -579,6 +475,12 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
     rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique,
                     nullptr, &look);
     if (rc) return rc;
+    const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
+    if (c->missq) {                 // the misses are on their way while the cached tiers are copied
+        const int64_t m_max = miss_cap < u_max ? miss_cap : u_max;
+        rc = missq_submit_from_batch(c, miss_pos, miss_slot, Count{c->cnt + kCntTier + 2, m_max}, m_max);
+        if (rc) return rc;
+    }
     c->blocks_ready = true;
     c->last_n_seeds = n_seeds;
     c->last_n_hops = n_hops;
@@ -586,7 +488,6 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
         c->last_frontier_max[h] = p.frontier_max[h];
         c->last_flat_max[h] = p.flat_max[h];
     }
-    const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
     return copy_tiers(c, Count{c->cnt + kCntUnique, u_max}, out);
 }
 
@@ -611,6 +512,7 @@ struct helios_plan {
     int64_t frontier_max[HELIOS_MAX_HOPS] = {0};
     int64_t flat_max[HELIOS_MAX_HOPS] = {0};
     uint32_t slots = 0;
+    helios_missq* missq = nullptr;     // the queue attached when the batch was recorded
 };
 
 int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
@@ -659,6 +561,7 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
         pl->flat_max[h] = p.flat_max[h];
     }
     pl->slots = c->last_slots;
+    pl->missq = c->missq;
     c->blocks_ready = false;                     // nothing has run yet
     *plan_out = pl;
     return HELIOS_OK;
@@ -670,7 +573,14 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     if (pl->n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
     if (pl->scratch_generation != c->scratch_generation)
         return fail(c, HELIOS_ESTATE, "the context's scratch was regrown after the batch was recorded; record it again");
+    if (pl->missq != c->missq)
+        return fail(c, HELIOS_ESTATE, "the miss queue attached to the context is not the one the batch was recorded with");
     DeviceGuard guard(c->device);
+    uint32_t io_round = 0;
+    if (pl->missq) {
+        int rc = missq_open_round(c, pl->missq, &io_round);
+        if (rc) return rc;
+    }
     if (c->epoch + pl->n_scans >= (1u << 30) - 64) {
         HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * c->scan_stride, c->stream));
         c->epoch = 0;
@@ -685,7 +595,7 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     slot->rng_seed = rng_seed;
     slot->seeds = seeds;
     slot->epoch_base = c->epoch;
-    slot->pad = 0;
+    slot->io_round = io_round;
     c->epoch += pl->n_scans;
     HIP_TRY(c, hipMemcpyAsync(c->vars, slot, sizeof(BatchVars), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
@@ -798,6 +708,12 @@ int helios_set_param(helios_ctx* c, int param, int64_t value) {
             return HELIOS_OK;
         case HELIOS_PARAM_SERIAL_TIERS:
             c->serial_tiers = value != 0;
+            return HELIOS_OK;
+        case HELIOS_PARAM_MISSQ_TIMEOUT_US:
+            c->missq_timeout_us = value < 1 ? 1 : value > 60000000 ? 60000000 : value;
+            return HELIOS_OK;
+        case HELIOS_PARAM_MISSQ_WAVES:
+            c->missq_waves = static_cast<unsigned>(value > 4096 ? 4096 : value);
             return HELIOS_OK;
         default:
             return fail(c, HELIOS_EINVAL, "helios_set_param: unknown parameter %d", param);

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libhelios.so")
 OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 MAX_HOPS, MAX_FANOUT = 8, 1024
 PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SERIAL_TIERS = 1, 2, 3
+PARAM_MISSQ_TIMEOUT_US, PARAM_MISSQ_WAVES = 4, 5
 _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
           -5: "HELIOS_EDATA", -6: "HELIOS_EINTERNAL"}
 
@@ -27,7 +28,8 @@ EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reser
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
            "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
-           "helios_gather_times"]
+           "helios_gather_times", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
+           "helios_missq_attach", "helios_missq_faulted", "helios_missq_counters", "helios_missq_destroy"]
 
 
 class HopOut(C.Structure):
@@ -81,6 +83,13 @@ def load_library() -> C.CDLL:
     lib.helios_set_param.argtypes = [vp, C.c_int, i64]
     lib.helios_set_timing.argtypes = [vp, C.c_int]
     lib.helios_gather_times.argtypes = [vp] + [C.POINTER(C.c_float)] * 4
+    lib.helios_missq_create.argtypes = [vp, i32, i32, i32, C.POINTER(vp)]
+    lib.helios_missq_submit.argtypes = [vp, vp, vp, i64, vp]
+    lib.helios_missq_complete.argtypes = [vp, vp]
+    lib.helios_missq_attach.argtypes = [vp, vp]
+    lib.helios_missq_faulted.argtypes = [vp]
+    lib.helios_missq_counters.argtypes = [vp, C.POINTER(i64)]
+    lib.helios_missq_destroy.argtypes = [vp]
     return lib
 
 
@@ -173,6 +182,7 @@ class Plan:
 
     def __init__(self, ctx: "Helios", handle, n_seeds: int, keep):
         self._ctx, self._p, self.n_seeds, self._keep = ctx, handle, n_seeds, keep
+        ctx._children.append(self)
 
     def launch(self, seeds: torch.Tensor, rng_seed: int) -> None:
         _dev(seeds, torch.int32, "seeds")
@@ -191,12 +201,62 @@ class Plan:
             pass
 
 
+class MissQueue:
+    """An asynchronous miss queue of a context (see helios_missq_create): submit() and complete()
+    alternate; attach() makes every batch of the context submit its own misses."""
+
+    def __init__(self, ctx: "Helios", n_queues: int, queue_depth: int, n_service_threads: int):
+        self._ctx, self._q = ctx, C.c_void_p()
+        ctx._check(_lib.helios_missq_create(ctx._h, n_queues, queue_depth, n_service_threads, C.byref(self._q)))
+        ctx._children.append(self)
+
+    def submit(self, miss_pos: torch.Tensor, miss_slot: torch.Tensor, n_miss_max: int,
+               n_miss_dev: Optional[torch.Tensor]) -> None:
+        _dev(miss_pos, torch.int32, "miss_pos"), _dev(miss_slot, torch.int32, "miss_slot")
+        assert n_miss_max <= min(miss_pos.numel(), miss_slot.numel())
+        if n_miss_dev is not None:
+            _dev_accessible(n_miss_dev, torch.int64, "n_miss_dev")
+        self._ctx._check(_lib.helios_missq_submit(self._q, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev)))
+
+    def complete(self, out: torch.Tensor) -> None:
+        if not out.is_cuda or not out.is_contiguous():
+            raise TypeError("out must be a contiguous GPU tensor")
+        self._ctx._check(_lib.helios_missq_complete(self._q, _ptr(out)))
+
+    def attach(self) -> None:
+        self._ctx._check(_lib.helios_missq_attach(self._ctx._h, self._q))
+
+    def detach(self) -> None:
+        self._ctx._check(_lib.helios_missq_attach(self._ctx._h, None))
+
+    def faulted(self) -> bool:
+        return bool(_lib.helios_missq_faulted(self._q))
+
+    def counters(self):
+        """(rounds opened, rounds the service threads have finished, commands served)"""
+        v = (C.c_int64 * 3)()
+        self._ctx._check(_lib.helios_missq_counters(self._q, v))
+        return tuple(v)
+
+    def destroy(self) -> None:
+        if self._q is not None and self._q.value:
+            _lib.helios_missq_destroy(self._q)
+            self._q = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
 class Helios:
     """One library context on one device and stream."""
 
     def __init__(self, device: int = 0, stream: Optional[torch.cuda.Stream] = None):
         self._h = C.c_void_p()
         self._keep = {}
+        self._children = []          # plans and miss queues: destroyed before the context
         s = stream.cuda_stream if stream is not None else torch.cuda.current_stream(device).cuda_stream
         rc = _lib.helios_create(C.byref(self._h), device, C.c_void_p(s))
         if rc != OK:
@@ -207,6 +267,9 @@ class Helios:
 
     def close(self) -> None:
         if getattr(self, "_h", None) is not None and self._h.value:
+            for child in self._children:
+                child.destroy()
+            self._children = []
             _lib.helios_destroy(self._h)
             self._h = C.c_void_p()
             self._keep.clear()
