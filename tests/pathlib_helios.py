@@ -82,6 +82,74 @@ def gpu_path(h, helios, seeds: torch.Tensor, fanouts, rng_seed: int, fused: bool
     return res
 
 
+def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, tabs_dev, batch, fanouts, jobs,
+                    n_lanes: int = 3, recorded: bool = True):
+    """bench.py's launch configuration: n_lanes contexts, each on its own stream with its own buffers
+    and (recorded=True) its own recorded batch, sharing the graph and the cache tables; up to n_lanes
+    mini-batches are in flight.  jobs: list of (seeds on the GPU, rng_seed).  Returns one result dict
+    per job, as gpu_path does (misses served)."""
+    import torch as T
+    dev = offsets.device
+    lanes = []
+    for _ in range(n_lanes):
+        ctx = helios.Helios(dev.index or 0, stream=T.cuda.Stream(device=dev))
+        ctx.csr_load(offsets, indices)
+        ctx.cache_build(order, n_hbm, n_host, row_bytes, *tabs_dev)
+        ctx.sync()
+        hops = helios.alloc_hops(batch, fanouts, dev)
+        cap = batch + sum(hb.flat.numel() for hb in hops)
+        ctx.reserve(cap)
+        bf = dict(ctx=ctx, hops=hops, unique=T.empty(cap, dtype=T.int32, device=dev),
+                  inverse=T.empty(cap, dtype=T.int32, device=dev),
+                  out=T.full((cap, row_bytes), SENTINEL, dtype=T.uint8, device=dev),
+                  mp=T.empty(cap, dtype=T.int32, device=dev), mi=T.empty(cap, dtype=T.int32, device=dev),
+                  ms=T.empty(cap, dtype=T.int32, device=dev), sizes=T.zeros(2 * len(fanouts), dtype=T.int64).pin_memory(),
+                  nu=T.zeros(1, dtype=T.int64).pin_memory(), stats=T.zeros(4, dtype=T.int64).pin_memory(), plan=None)
+        lanes.append(bf)
+    T.cuda.synchronize()
+    if recorded:
+        for bf in lanes:
+            bf["plan"] = bf["ctx"].plan_create(batch, fanouts, bf["hops"], bf["sizes"], bf["unique"], bf["inverse"],
+                                               bf["nu"], bf["out"], bf["mp"], bf["mi"], bf["ms"], bf["stats"])
+        T.cuda.synchronize()
+    K = len(fanouts)
+
+    def collect(bf):
+        bf["ctx"].sync()
+        sizes, U, nm = bf["sizes"], int(bf["nu"][0]), int(bf["stats"][3])
+        res = {"hops": []}
+        for k in range(K):
+            nf, nfl = int(sizes[2 * k]), int(sizes[2 * k + 1])
+            hb = bf["hops"][k]
+            res["hops"].append((hb.frontier[:nf].cpu().numpy(), hb.indptr[:nf + 1].cpu().numpy(), hb.flat[:nfl].cpu().numpy()))
+        n_cat = batch + sum(int(sizes[2 * k + 1]) for k in range(K))
+        res.update(unique=bf["unique"][:U].cpu().numpy(), inverse=bf["inverse"][:n_cat].cpu().numpy(),
+                   stats=bf["stats"].numpy().copy(), miss_pos=bf["mp"][:nm].cpu().numpy(),
+                   miss_id=bf["mi"][:nm].cpu().numpy(), miss_slot=bf["ms"][:nm].cpu().numpy(), out=bf["out"][:U].cpu().numpy())
+        return res
+
+    results = [None] * len(jobs)
+    for j, (seeds, rs) in enumerate(jobs):
+        bf = lanes[j % n_lanes]
+        if j >= n_lanes:
+            results[j - n_lanes] = collect(bf)
+            bf["out"].fill_(SENTINEL)
+            T.cuda.synchronize()
+        if recorded:
+            bf["plan"].launch(seeds, rs)
+        else:
+            bf["ctx"].prepare_batch(seeds, fanouts, rs, bf["hops"], bf["sizes"], bf["unique"], bf["inverse"], bf["nu"],
+                                    bf["out"], bf["mp"], bf["mi"], bf["ms"], bf["stats"])
+        bf["ctx"].gather_miss(bf["mp"], bf["ms"], bf["mp"].numel(), bf["stats"][3:4], bf["out"])
+    for j in range(max(0, len(jobs) - n_lanes), len(jobs)):
+        results[j] = collect(lanes[j % n_lanes])
+    for bf in lanes:
+        if bf["plan"] is not None:
+            bf["plan"].destroy()
+        bf["ctx"].close()
+    return results
+
+
 def oracle_path(oracle, off, idx, seeds, fanouts, rng_seed, rank, n_hbm, n_host, hbm_tab, host_tab, standin_tab,
                 row_bytes):
     hops = oracle.sample(off, idx, seeds, fanouts, rng_seed)

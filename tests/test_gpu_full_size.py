@@ -1,5 +1,7 @@
 """GPU parity at the full sizes of workloads 2, 3 and 4 (10^8 nodes, 10^9 edges, 57-102 GB of
-features), through helios_prepare_batch exactly as bench.py calls it.  The inputs are generated on
+features): first through helios_prepare_batch on one context, then in the launch configuration
+bench.py times (three contexts on three streams, a recorded batch each, three mini-batches in
+flight).  The inputs are generated on
 the GPU; the CPU oracle runs the whole path on host copies of the same arrays and every output is
 compared bit for bit.  In addition every gathered row is checked against the procedural feature
 generator (out[j] == feat(unique[j]) for all j), a property that needs no table on the host."""
@@ -10,7 +12,7 @@ import pytest
 import torch
 
 from paper_2310_00837_amd import workload as W
-from pathlib_helios import assert_same, gpu_path, oracle_path, to_bytes
+from pathlib_helios import assert_same, gpu_path, lanes_in_flight, oracle_path, to_bytes
 
 pytestmark = pytest.mark.gpu
 SEED = 1234
@@ -32,6 +34,7 @@ def _check_batches(h, helios, oracle, sp, g, host_csr, rank_h, n_hbm, n_host, ta
     off_h, idx_h = host_csr
     h.cache_build(g.order, n_hbm, n_host, sp.row_bytes, *tabs_dev)
     h.sync()
+    wants = {}
     for b in batches:
         seeds = W.seed_batch(sp, g, b)
         rs = W.batch_rng_seed(SEED, b)
@@ -39,6 +42,7 @@ def _check_batches(h, helios, oracle, sp, g, host_csr, rank_h, n_hbm, n_host, ta
         want = oracle_path(oracle, off_h, idx_h, seeds.cpu().numpy(), sp.fanouts, rs, rank_h, n_hbm, n_host,
                            *tabs_host, sp.row_bytes)
         assert_same(got, want)
+        wants[b] = want
         uniq = torch.from_numpy(got["unique"]).cuda()
         for s in range(0, uniq.numel(), 1 << 16):                   # every row equals the generator's row
             rows = W.feature_rows(SEED, uniq[s:s + (1 << 16)], sp.dim, sp.dtype)
@@ -47,6 +51,18 @@ def _check_batches(h, helios, oracle, sp, g, host_csr, rank_h, n_hbm, n_host, ta
         st = want["stats"].tolist()
         say(f"  {sp.name} batch {b}: raw {sum(len(x[2]) for x in want['hops'])} unique {st[0]} "
             f"hbm {st[1]} host {st[2]} miss {st[3]}: bit-exact")
+    # the same batches as bench.py launches them: every batch once on each of the three lanes
+    order_of_jobs = [b for r in range(3) for b in (batches[r % len(batches):] + batches[:r % len(batches)])]
+    while len(order_of_jobs) % 3:
+        order_of_jobs.append(batches[0])
+    jobs = [(W.seed_batch(sp, g, b).cuda(), W.batch_rng_seed(SEED, b)) for b in order_of_jobs]
+    got = lanes_in_flight(helios, g.offsets, g.indices, g.order, n_hbm, n_host, sp.row_bytes, tabs_dev, sp.batch,
+                          sp.fanouts, jobs)
+    for b, res in zip(order_of_jobs, got):
+        want = dict(wants[b])
+        del want["out_before_miss"]
+        assert_same(res, want)
+    say(f"  {sp.name}: {len(jobs)} recorded batches, three in flight: bit-exact")
 
 
 def test_workloads_2_and_4_full_size(helios, oracle):
