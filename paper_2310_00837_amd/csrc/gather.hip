@@ -7,7 +7,8 @@
 // contiguous lines; L is the smallest power of two that covers the row (at most
 // a wave).  Each group takes R list entries per step (R = 1 or 2: measured
 // best; the 32 waves a CU holds supply the requests in flight) and issues all
-// their loads before the first store.  The grid strides over the list and the
+// their loads before the first store.  The groups of the grid share the list
+// evenly (entry k belongs to group k mod groups) and the
 // count is read on the device, so no host round trip sits between the lookup
 // and the copy.  For an HBM source the grid is up to 8192 workgroups, four
 // times what the chip holds at once, so the dispatcher balances the load; a
@@ -96,14 +97,17 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(GatherArgs a) {
     stamp_start(a.clock);
     const int l = threadIdx.x % L;
     const int g = threadIdx.x / L;
-    const int64_t step = static_cast<int64_t>(gridDim.x) * kGroups * R;
+    // Group j of the grid takes the list entries j, j + groups, j + 2 * groups, ..., R of them per step: every
+    // group gets the same number of rows to within one, so all workgroups (for a far source: all the CUs
+    // whose requests fill the link) stay busy until the list ends.
+    const int64_t groups = static_cast<int64_t>(gridDim.x) * kGroups;
     const int64_t n = a.n.get();
-    for (int64_t k0 = (static_cast<int64_t>(blockIdx.x) * kGroups + g) * R; k0 < n; k0 += step) {
+    for (int64_t k0 = static_cast<int64_t>(blockIdx.x) * kGroups + g; k0 < n; k0 += groups * R) {
         chunk16 v[R][CPL];
         int64_t dst[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int64_t k = k0 + r;
+            const int64_t k = k0 + r * groups;
             dst[r] = -1;
             if (k < n) {
                 const int64_t s = a.slot[k];

@@ -164,6 +164,7 @@ __global__ __launch_bounds__(kBlock) void missq_complete_kernel(CompleteArgs a) 
     int remaining = static_cast<int>(wave_sum(static_cast<uint32_t>(my_count)));
     const chunk16* staging = reinterpret_cast<const chunk16*>(a.q.staging);
     unsigned long long last_progress = wall_clock64();
+    int idle_sleeps = 1;            // polls over the link get rarer while nothing arrives
 
     while (remaining > 0) {
         bool progress = false;
@@ -172,6 +173,12 @@ __global__ __launch_bounds__(kBlock) void missq_complete_kernel(CompleteArgs a) 
             const int count = __shfl(my_count, k, kWave), head = __shfl(my_head, k, kWave);
             if (head >= count) continue;                                   // uniform over the wave
             const int64_t base = static_cast<int64_t>(q) * a.q.depth;
+            // the leader polls the entry the queue is waiting for; only when that one is posted does the wave
+            // read the 64 entries from there on (an idle poll costs the host one cache line, not eight)
+            unsigned long long first = 0;
+            if (l == 0) first = __hip_atomic_load(a.q.cq + base + head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            first = __shfl(first, 0, kWave);
+            if (static_cast<uint32_t>(first >> 32) != a.round) continue;
             const int idx = head + l;
             unsigned long long e = 0;
             if (idx < count) e = __hip_atomic_load(a.q.cq + base + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -210,12 +217,14 @@ __global__ __launch_bounds__(kBlock) void missq_complete_kernel(CompleteArgs a) 
         }
         if (progress) {
             last_progress = wall_clock64();
+            idle_sleeps = 1;
         } else {
             if (wall_clock64() - last_progress > a.timeout_ticks) {        // the device has stopped answering
                 if (l == 0) raise(a.err, kErrInternal);
                 return;
             }
-            __builtin_amdgcn_s_sleep(64);
+            for (int z = 0; z < idle_sleeps; ++z) __builtin_amdgcn_s_sleep(127);     // ~3 us each
+            if (idle_sleeps < 4) idle_sleeps += 1;
         }
     }
 }
@@ -238,6 +247,13 @@ void serve_queue(helios_missq* m, int q, uint32_t round, uint32_t count) {
     const int64_t n_staging = static_cast<int64_t>(v.n_queues) * v.depth;
     const bool forward = ((round + static_cast<uint32_t>(q)) & 1u) == 0;
     constexpr uint32_t kAhead = 6;
+    constexpr uint32_t kPostBatch = 8;         // completion entries of one cache line are posted together
+    unsigned long long entry[kPostBatch];
+    uint32_t held = 0;                         // copied, not yet posted; their entries go to cq[p - held, p)
+    auto post = [&](uint32_t p_end) {
+        for (uint32_t b = 0; b < held; ++b) __atomic_store_n(v.cq + base + (p_end - held + b), entry[b], __ATOMIC_RELEASE);
+        held = 0;
+    };
     for (uint32_t p = 0; p < count; ++p) {
         if (p + kAhead < count) {              // the rows are at random places of a large table
             const uint32_t i2 = forward ? p + kAhead : count - 1 - (p + kAhead);
@@ -252,11 +268,14 @@ void serve_queue(helios_missq* m, int q, uint32_t round, uint32_t count) {
         const int64_t slot = static_cast<uint32_t>(cmd), row = static_cast<int64_t>(cmd >> 32);
         if (slot >= m->standin_rows || row >= n_staging) {      // no completion entry: the completion kernel reports it
             m->faulted.store(true);
-            continue;
+            post(p);
+            return;
         }
         memcpy(v.staging + static_cast<size_t>(row) * rb, m->standin + static_cast<size_t>(slot) * rb, rb);
-        __atomic_store_n(v.cq + base + p, (static_cast<unsigned long long>(round) << 32) | i, __ATOMIC_RELEASE);
+        entry[held++] = (static_cast<unsigned long long>(round) << 32) | i;
+        if (held == kPostBatch || ((p + 1) & (kPostBatch - 1)) == 0) post(p + 1);
     }
+    post(count);
     m->commands_served.fetch_add(count, std::memory_order_relaxed);
 }
 
@@ -302,6 +321,26 @@ void service_thread(helios_missq* m, int t) {
         served = round;
         m->rounds_served.fetch_add(1, std::memory_order_relaxed);
     }
+}
+
+// Reads one byte of every page of the stand-in table from the host.  Pinned memory that only the GPU
+// has written so far is resident but not yet in this process's page table; without this pass every
+// first read of a page by a service thread would take a page fault (microseconds, against the tenth
+// of a microsecond the row copy itself takes).
+void touch_pages(const unsigned char* p, size_t bytes) {
+    constexpr size_t kPage = 4096;
+    const unsigned n_threads = 8;
+    const size_t pages = (bytes + kPage - 1) / kPage;
+    std::vector<std::thread> ts;
+    std::atomic<unsigned> sink{0};
+    for (unsigned t = 0; t < n_threads; ++t)
+        ts.emplace_back([=, &sink] {
+            unsigned acc = 0;
+            for (size_t pg = pages * t / n_threads; pg < pages * (t + 1) / n_threads; ++pg)
+                acc += *reinterpret_cast<const volatile unsigned char*>(p + pg * kPage);
+            sink.fetch_add(acc, std::memory_order_relaxed);
+        });
+    for (std::thread& th : ts) th.join();
 }
 
 void stop_threads(helios_missq* m) {
@@ -422,6 +461,7 @@ int helios_missq_create(helios_ctx* c, int32_t n_queues, int32_t queue_depth, in
         delete m;
         return fail(c, HELIOS_EHIP, "helios_missq_create: %s", hipGetErrorString(e));
     }
+    if (n_service_threads > 0 && standin_rows > 0) touch_pages(m->standin, static_cast<size_t>(standin_rows) * c->row_bytes);
     for (int t = 0; t < n_service_threads; ++t) m->threads.emplace_back(service_thread, m, t);
     *out = m;
     return HELIOS_OK;
