@@ -335,6 +335,13 @@ int helios_missq_destroy(helios_missq *q);
 int helios_set_timing(helios_ctx *ctx, int level);
 int helios_gather_times(helios_ctx *ctx, float *hbm_ms, float *host_ms,
                         float *hbm_event_ms, float *host_event_ms);
+/* The same two kernels' first and last tick themselves (level >= 1):
+ * ticks4 = {HBM start, HBM end, host start, host end} of the GPU's
+ * constant-rate clock, which all contexts of a device share, so the copies of
+ * batches in flight on several contexts can be placed on one time axis;
+ * *ticks_per_us (nullable) receives the clock rate.  Zeros for a tier that
+ * launched nothing. */
+int helios_gather_ticks(helios_ctx *ctx, uint64_t *ticks4, double *ticks_per_us);
 
 #ifdef __cplusplus
 }

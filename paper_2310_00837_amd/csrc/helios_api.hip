@@ -749,4 +749,22 @@ int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms, float* hbm
     return HELIOS_OK;
 }
 
+int helios_gather_ticks(helios_ctx* c, uint64_t* ticks4, double* ticks_per_us) {
+    if (!c || !ticks4) return HELIOS_EINVAL;
+    DeviceGuard guard(c->device);
+    for (int i = 0; i < 4; ++i) ticks4[i] = 0;
+    if (ticks_per_us) *ticks_per_us = c->clock_khz / 1000.0;
+    if (!c->timed_hbm && !c->timed_host) return HELIOS_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (int t = 0; t < 2; ++t) {
+        if (!(t == 0 ? c->timed_hbm : c->timed_host)) continue;
+        const volatile uint64_t* k = c->clock_host + 2 * t;
+        if (k[0] != ~0ull && k[1] >= k[0]) {
+            ticks4[2 * t] = k[0];
+            ticks4[2 * t + 1] = k[1];
+        }
+    }
+    return HELIOS_OK;
+}
+
 }  // extern "C"

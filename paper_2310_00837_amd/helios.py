@@ -28,7 +28,7 @@ EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reser
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
            "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
-           "helios_gather_times", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
+           "helios_gather_times", "helios_gather_ticks", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
            "helios_missq_attach", "helios_missq_faulted", "helios_missq_counters", "helios_missq_destroy"]
 
 
@@ -83,6 +83,7 @@ def load_library() -> C.CDLL:
     lib.helios_set_param.argtypes = [vp, C.c_int, i64]
     lib.helios_set_timing.argtypes = [vp, C.c_int]
     lib.helios_gather_times.argtypes = [vp] + [C.POINTER(C.c_float)] * 4
+    lib.helios_gather_ticks.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
     lib.helios_missq_create.argtypes = [vp, i32, i32, i32, C.POINTER(vp)]
     lib.helios_missq_submit.argtypes = [vp, vp, vp, i64, vp]
     lib.helios_missq_complete.argtypes = [vp, vp]
@@ -308,6 +309,12 @@ class Helios:
         v = [C.c_float() for _ in range(4)]
         self._check(_lib.helios_gather_times(self._h, *[C.byref(x) for x in v]))
         return tuple(x.value for x in v)
+
+    def gather_ticks(self):
+        """((hbm_start, hbm_end, host_start, host_end) in ticks of the GPU's clock, ticks per microsecond)"""
+        v, rate = (C.c_uint64 * 4)(), C.c_double()
+        self._check(_lib.helios_gather_ticks(self._h, v, C.byref(rate)))
+        return tuple(v), rate.value
 
     # ---- S0
     def csr_load(self, offsets: torch.Tensor, indices: torch.Tensor) -> None:
