@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time given to the CPU-oracle leg")
     ap.add_argument("--depth", type=int, default=3,
                     help="mini-batches in flight during the timed region (each on its own context and stream)")
+    ap.add_argument("--per-lane", type=int, default=2,
+                    help="mini-batches queued per lane in the timed region (buffer sets per context): one runs, "
+                         "the next waits behind it on the lane's stream")
     ap.add_argument("--threads", type=int, default=0, help="0: one host thread drives all lanes (default, fastest); 1: one host thread per lane")
     ap.add_argument("--graph", type=int, default=1, help="1: replay a recorded batch (HIP graph) per step; 0: launch directly")
     ap.add_argument("--hbm-blocks", type=int, default=0, help="workgroups of the HBM-tier copy (0 = library default)")
@@ -122,14 +125,11 @@ def main() -> int:
     seeds = [W.seed_batch(sp, g, b).to(dev) for b in range(n_batches)]
     rng_seeds = [W.batch_rng_seed(args.seed, b) for b in range(n_batches)]
 
-    class Lane:
-        """One library context on its own stream with its own output buffers: one mini-batch in flight."""
+    class Buffers:
+        """Caller-owned outputs of one mini-batch, and the recordings that write to them."""
 
-        def __init__(self, ctx, stream):
-            self.h, self.stream = ctx, stream
+        def __init__(self, cap):
             self.hops = helios.alloc_hops(B, sp.fanouts, dev)
-            cap = B + sum(hb.flat.numel() for hb in self.hops)
-            self.h.reserve(cap)
             self.unique = torch.empty(cap, dtype=torch.int32, device=dev)
             self.inverse = torch.empty(cap, dtype=torch.int32, device=dev)
             self.out = torch.empty((cap, sp.row_bytes), dtype=torch.uint8, device=dev)
@@ -140,8 +140,24 @@ def main() -> int:
             self.stats = torch.zeros(4, dtype=torch.int64).pin_memory()
             # zero-copy numpy views of the pinned result words: reading them costs the host almost nothing
             self.stats_np, self.sizes_np = self.stats.numpy(), self.sizes.numpy()
-
             self.plans = {}
+
+    class Lane:
+        """One library context on its own stream.  It has two buffer sets: one mini-batch of the lane runs
+        while the next is already queued behind it on the stream."""
+
+        def __init__(self, ctx, stream):
+            self.h, self.stream = ctx, stream
+            cap = width = B                      # seeds + the largest possible sample lists
+            for f in sp.fanouts:
+                width *= f
+                cap += width
+            self.h.reserve(cap)
+            self.sets = [Buffers(cap) for _ in range(max(1, args.per_lane))]
+            first = self.sets[0]                 # the set the one-per-lane regions use
+            for name in ("hops", "unique", "inverse", "out", "mp", "mi", "ms", "sizes", "n_unique", "stats", "stats_np",
+                         "sizes_np", "plans"):
+                setattr(self, name, getattr(first, name))
             self.cap = cap
             self.queue = None
 
@@ -155,12 +171,22 @@ def main() -> int:
                                                      self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
 
         def record(self) -> None:
-            """One recording (HIP graph) of the whole-path call per timing level."""
+            """One recording (HIP graph) of the whole-path call per timing level (and per buffer set for level 0)."""
             for level in (0, 1):
                 self.h.set_timing(level)
-                self.plans[level] = self.h.plan_create(B, sp.fanouts, self.hops, self.sizes, self.unique, self.inverse,
-                                                       self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
+                for bs in (self.sets if level == 0 else self.sets[:1]):
+                    bs.plans[level] = self.h.plan_create(B, sp.fanouts, bs.hops, bs.sizes, bs.unique, bs.inverse,
+                                                         bs.n_unique, bs.out, bs.mp, bs.mi, bs.ms, bs.stats)
             self.h.set_timing(0)
+
+        def launch_set(self, which: int, b: int) -> None:
+            """Batch b into buffer set `which` (timing off)."""
+            bs = self.sets[which]
+            if args.graph:
+                bs.plans[0].launch(seeds[b], rng_seeds[b])
+            else:
+                self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], bs.hops, bs.sizes, bs.unique, bs.inverse,
+                                     bs.n_unique, bs.out, bs.mp, bs.mi, bs.ms, bs.stats)
 
         def launch(self, b: int, serve_misses, timing: int = 0) -> None:
             if serve_misses == "queue":          # the batch submits its misses itself; the completion kernel follows
@@ -200,14 +226,24 @@ def main() -> int:
             ln.record()
         torch.cuda.synchronize()
 
-    def run_region(first: int, count: int, depth: int, timing: int, serve_misses: bool):
-        """`count` whole steps with up to `depth` mini-batches in flight (lane b % depth); a lane's
-        previous batch is waited for (helios_sync) before the lane is reused.  Returns (seconds, sums)."""
+    def run_region(first: int, count: int, depth: int, timing: int, serve_misses, per_lane: int = 1):
+        """`count` whole steps on `depth` lanes.  per_lane == 1: lane b % depth takes batch b and is waited for
+        (helios_sync) before it is reused.  per_lane > 1 (recorded batches, no timing, no miss service): every
+        lane has per_lane buffer sets, a batch is queued behind the lane's running one, and each batch is waited
+        for by itself (helios_plan_wait).  Returns (seconds, sums)."""
         acc = dict(hbm_ms=0.0, host_ms=0.0, hbm_ev_ms=0.0, host_ev_ms=0.0, hbm_rows=0, host_rows=0, miss=0, unique=0,
                    raw=0)
         use = lanes[:depth]
         for ln in use:
             ln.h.set_timing(timing)
+
+        def tally(bs):
+            st = bs.stats_np
+            acc["hbm_rows"] += int(st[1])
+            acc["host_rows"] += int(st[2])
+            acc["miss"] += int(st[3])
+            acc["unique"] += int(st[0])
+            acc["raw"] += int(bs.sizes_np[1::2].sum())
 
         def retire(ln):
             ln.h.sync()
@@ -217,12 +253,7 @@ def main() -> int:
                 acc["host_ms"] += b_ms
                 acc["hbm_ev_ms"] += a_ev
                 acc["host_ev_ms"] += b_ev
-            st = ln.stats_np
-            acc["hbm_rows"] += int(st[1])
-            acc["host_rows"] += int(st[2])
-            acc["miss"] += int(st[3])
-            acc["unique"] += int(st[0])
-            acc["raw"] += int(ln.sizes_np[1::2].sum())
+            tally(ln)
 
         def worker(w: int) -> None:          # lane w takes batches w, w + depth, ... one after the other
             ln = use[w]
@@ -232,7 +263,21 @@ def main() -> int:
 
         torch.cuda.synchronize()
         t_begin = time.perf_counter()
-        if depth == 1 or not args.threads:
+        if per_lane > 1 and args.graph and not timing and not serve_misses:
+            units = [(ln, w) for w in range(per_lane) for ln in use]      # lane 0 set 0, lane 1 set 0, ..., lane 0 set 1, ...
+            for k in range(count):
+                ln, w = units[k % len(units)]
+                if k >= len(units):
+                    ln.sets[w].plans[0].wait()
+                    tally(ln.sets[w])
+                ln.launch_set(w, first + k)
+            for k in range(max(0, count - len(units)), count):
+                ln, w = units[k % len(units)]
+                ln.sets[w].plans[0].wait()
+                tally(ln.sets[w])
+            for ln in use:
+                ln.h.sync()
+        elif depth == 1 or not args.threads:
             for k in range(count):
                 ln = use[k % depth]
                 if k >= depth:
@@ -255,9 +300,13 @@ def main() -> int:
     # ---------------- timed region: W warm-up steps, then K whole steps (S1-S5) with `depth` mini-batches in
     # flight; the row-copy kernels are timed with the device clock inside the same region
     D = len(lanes)
+    P = max(1, args.per_lane) if args.graph else 1
+    run_region(0, Wm, D, 0, False, P)
+    elapsed, acc = run_region(Wm, K, D, 0, False, P)
+    # the same K steps: one batch per lane with the copies timed by the device clock; one batch in flight; with
+    # the miss list served (S6); with HIP events around the copies
     run_region(0, Wm, D, 1, False)
-    elapsed, acc = run_region(Wm, K, D, 1, False)
-    # the same K steps: one batch in flight; with the miss list served (S6); with HIP events around the copies
+    ov_elapsed, ov_acc = run_region(Wm, K, D, 1, False)
     run_region(0, Wm, 1, 1, False)
     one_elapsed, one_acc = run_region(Wm, K, 1, 1, False)
     elapsed_s6, _ = run_region(Wm, K, D, 0, True)
@@ -316,7 +365,7 @@ def main() -> int:
         return hbm, host
 
     hbm_gbs, host_gbs = rates(one_acc)              # kernel quality: nothing else runs beside the copies
-    ov_hbm_gbs, ov_host_gbs = rates(acc)            # the same kernels inside the pipelined region
+    ov_hbm_gbs, ov_host_gbs = rates(ov_acc)         # the same kernels with one batch on each lane
     dominant_host = one_acc["host_ms"] > one_acc["hbm_ms"]
     link_whole_run = 1.0 * acc["host_rows"] * rb / elapsed / 1e9
 
@@ -347,7 +396,7 @@ def main() -> int:
                    "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed,
                    "step": ("helios_plan_launch (recorded helios_prepare_batch" if args.graph else "helios_prepare_batch (") +
                            ": sample, dedup, lookup, HBM+host gather, miss list) + helios_sync, "
-                           "%d mini-batches in flight, each on its own context and stream" % D},
+                           "%d contexts on %d streams, %d mini-batches queued on each" % (D, D, P)},
         "roofline": {"kernel": "gather_rows_kernel (HBM tier)", "bound": "hbm", "achieved": hbm_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_kernel_us": one_acc["hbm_ms"] / K * 1e3,
@@ -358,8 +407,8 @@ def main() -> int:
                      "plain_copy_GBs_on_this_box": copy_gbs,
                      "large_list": big,
                      "while_overlapped": {"achieved": ov_hbm_gbs, "frac": ov_hbm_gbs / HBM_PEAK_GBS,
-                                          "avg_kernel_us": acc["hbm_ms"] / K * 1e3,
-                                          "note": "same kernel inside the %d-in-flight region, beside other batches' host-link copies" % D}},
+                                          "avg_kernel_us": ov_acc["hbm_ms"] / K * 1e3,
+                                          "note": "same kernel with one mini-batch on each of the %d lanes, beside other batches' host-link copies" % D}},
         "roofline_host_link": {"kernel": "gather_rows_kernel (host tier)", "bound": "host_link",
                                "achieved": host_gbs, "peak": link_gbs, "unit": "GB/s",
                                "frac": host_gbs / link_gbs if link_gbs > 0 else None,
@@ -370,7 +419,7 @@ def main() -> int:
                                "while_overlapped": {"link_GBs_over_the_whole_region": link_whole_run,
                                                     "frac": link_whole_run / link_gbs if link_gbs > 0 else None,
                                                     "per_kernel_GBs": ov_host_gbs,
-                                                    "note": "host-tier bytes of all K steps / wall time of the %d-in-flight region" % D}},
+                                                    "note": "host-tier bytes of all K steps / wall time of the timed region (value)"}},
         "dominant_kernel": "host-tier gather" if dominant_host else "HBM-tier gather",
         "with_miss_service": {"value": K / elapsed_s6, "ms_per_step": elapsed_s6 / K * 1e3},
         "with_async_miss_queue": None if elapsed_q is None else {
@@ -378,7 +427,9 @@ def main() -> int:
             "service_threads_per_lane": args.missq_threads,
             "note": "S6 in the shape of the paper's IO stack: submission kernel, host threads serving the stand-in "
                     "into a pinned staging buffer, completion kernel"},
-        "batches_in_flight": D,
+        "batches_in_flight": D * P,
+        "one_batch_per_lane": {"value": K / ov_elapsed, "ms_per_step": ov_elapsed / K * 1e3,
+                               "note": "%d lanes, helios_sync on a lane before it gets its next batch" % D},
         "one_batch_in_flight": {"value": K / one_elapsed, "ms_per_step": one_elapsed / K * 1e3,
                                 "note": "the same K steps with helios_sync after every batch"},
         "per_batch": {"raw_sampled_ids": acc["raw"] / K, "unique_ids": acc["unique"] / K,

@@ -271,6 +271,12 @@ int helios_plan_create(helios_ctx *ctx, int64_t n_seeds, const int32_t *fanouts,
                        void *out, int32_t *miss_pos, int32_t *miss_id, int32_t *miss_slot,
                        int64_t miss_cap, helios_gather_stats *stats, helios_plan **plan_out);
 int helios_plan_launch(helios_plan *plan, const int32_t *seeds, uint64_t rng_seed);
+/* Waits until the plan's last launch has finished (not for launches of other
+ * plans queued behind it on the same context) and reports device-side errors
+ * like helios_sync.  With two plans over two buffer sets on one context the
+ * host can queue a batch behind the one that is running and still take each
+ * batch's results as soon as it is done. */
+int helios_plan_wait(helios_plan *plan);
 int helios_plan_destroy(helios_plan *plan);
 
 /* Asynchronous service of the miss list in the shape of the GPU-initiated IO

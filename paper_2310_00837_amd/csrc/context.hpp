@@ -72,6 +72,7 @@ struct helios_ctx {
     helios::BatchVars* vars = nullptr;                 // device
     helios::BatchVars* vars_ring = nullptr;            // pinned [kVarsRing]
     uint32_t vars_next = 0, vars_unsynced = 0;
+    uint64_t launch_seq = 0;                   // recorded batches launched so far
     bool recording = false;
     uint32_t rec_scans = 0;
     uint64_t scratch_generation = 0;

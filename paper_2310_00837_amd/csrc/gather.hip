@@ -195,7 +195,10 @@ hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32
     // HBM source: 8192 workgroups (four rounds of what the chip holds) balance long lists best; lists that can
     // hold at most a few hundred thousand rows are quicker with the 2048 that are resident at once (measured:
     // 17 k rows 4.4 vs 5.4 us, 35 k rows 8.2 vs 9.1 us; 1 M rows 2 % the other way).
-    unsigned max_blocks = far_source ? (c <= 16 ? 128u : c <= 32 ? 64u : 32u) : (n_max >= 500000 ? kGatherMaxBlocks : 2048u);
+    // (far source, 512 B rows: 64 workgroups copy a list alone 2 % faster than 44, but every kernel launched on
+    // the GPU while the link is saturated starts some microseconds late, the later the more link waves are
+    // in flight; with three mini-batches in flight 44 workgroups gave 4-6 % more mini-batches per second)
+    unsigned max_blocks = far_source ? (c <= 16 ? 128u : c <= 32 ? 44u : 32u) : (n_max >= 500000 ? kGatherMaxBlocks : 2048u);
     if (blocks_limit > 0) max_blocks = blocks_limit < kGatherMaxBlocks ? blocks_limit : kGatherMaxBlocks;
     unsigned nb = 0;
     if (c <= 4) nb = launch_shape<4, 1, 2>(stream, a, n_max, max_blocks);

@@ -316,19 +316,24 @@ int helios_reserve(helios_ctx* c, int64_t max_ids) {
     return ensure_capacity(c, max_ids);
 }
 
+// the device-side error word: reports and clears what kernels have recorded since the last check
+static int check_device_error(helios_ctx* c) {
+    const int code = *reinterpret_cast<volatile int32_t*>(c->err);
+    if (code != 0) {
+        c->err[0] = 0;
+        return fail(c, code, code == HELIOS_ECAPACITY ? "an output did not fit its capacity"
+                             : code == HELIOS_EINTERNAL ? "a workgroup gave up waiting (chained scan, or a miss queue that stopped answering)"
+                             : "a node ID outside [0, n_nodes), or an order that is not a permutation");
+    }
+    return HELIOS_OK;
+}
+
 int helios_sync(helios_ctx* c) {
     if (!c) return HELIOS_EINVAL;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->vars_unsynced = 0;
-    const int code = *reinterpret_cast<volatile int32_t*>(c->err);
-    if (code != 0) {
-        c->err[0] = 0;
-        return fail(c, code, code == HELIOS_ECAPACITY ? "an output did not fit its capacity"
-                             : code == HELIOS_EINTERNAL ? "a workgroup gave up waiting for an earlier one (chained scan)"
-                             : "a node ID outside [0, n_nodes), or an order that is not a permutation");
-    }
-    return HELIOS_OK;
+    return check_device_error(c);
 }
 
 int helios_csr_load(helios_ctx* c, int64_t n_nodes, int64_t n_edges, const int64_t* offsets, const int32_t* indices) {
@@ -513,6 +518,8 @@ struct helios_plan {
     int64_t flat_max[HELIOS_MAX_HOPS] = {0};
     uint32_t slots = 0;
     helios_missq* missq = nullptr;     // the queue attached when the batch was recorded
+    hipEvent_t done = nullptr;         // recorded behind every launch
+    uint64_t launch_seq = 0;           // the context's launch count at this plan's last launch
 };
 
 int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
@@ -546,7 +553,9 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
     c->recording = false;
     pl->n_scans = c->rec_scans;
     if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&pl->exec, pl->graph, nullptr, nullptr, 0);
+    if (e == hipSuccess && rc == HELIOS_OK) e = hipEventCreateWithFlags(&pl->done, hipEventDisableTiming);
     if (e != hipSuccess || rc != HELIOS_OK) {
+        if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
         if (pl->graph) (void)hipGraphDestroy(pl->graph);
         delete pl;
         c->blocks_ready = false;
@@ -599,6 +608,9 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     c->epoch += pl->n_scans;
     HIP_TRY(c, hipMemcpyAsync(c->vars, slot, sizeof(BatchVars), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
+    HIP_TRY(c, hipEventRecord(pl->done, c->stream));
+    c->launch_seq += 1;
+    pl->launch_seq = c->launch_seq;
     c->blocks_ready = true;
     c->last_slots = pl->slots;
     c->last_n_seeds = pl->n_seeds;
@@ -612,6 +624,18 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     return HELIOS_OK;
 }
 
+int helios_plan_wait(helios_plan* pl) {
+    if (!pl || !pl->ctx) return HELIOS_EINVAL;
+    helios_ctx* c = pl->ctx;
+    if (pl->launch_seq == 0) return HELIOS_OK;           // never launched
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipEventSynchronize(pl->done));
+    // everything launched on the context up to this plan's launch has finished
+    const uint64_t later = c->launch_seq - pl->launch_seq;
+    if (later < c->vars_unsynced) c->vars_unsynced = static_cast<uint32_t>(later);
+    return check_device_error(c);
+}
+
 int helios_plan_destroy(helios_plan* pl) {
     if (!pl) return HELIOS_EINVAL;
     if (pl->ctx) {
@@ -620,6 +644,7 @@ int helios_plan_destroy(helios_plan* pl) {
     }
     if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
     if (pl->graph) (void)hipGraphDestroy(pl->graph);
+    if (pl->done) (void)hipEventDestroy(pl->done);
     delete pl;
     return HELIOS_OK;
 }

@@ -27,7 +27,7 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
-           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
+           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_wait", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
            "helios_gather_times", "helios_gather_ticks", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
            "helios_missq_attach", "helios_missq_faulted", "helios_missq_counters", "helios_missq_destroy"]
 
@@ -76,6 +76,7 @@ def load_library() -> C.CDLL:
     lib.helios_plan_create.argtypes = [vp, i64, C.POINTER(i32), i32, C.POINTER(HopOut), vp, vp, i64, vp, vp, vp, vp, vp,
                                        vp, i64, vp, C.POINTER(vp)]
     lib.helios_plan_launch.argtypes = [vp, vp, C.c_uint64]
+    lib.helios_plan_wait.argtypes = [vp]
     lib.helios_plan_destroy.argtypes = [vp]
     lib.helios_host_alloc.argtypes = [i64]
     lib.helios_host_alloc.restype = vp
@@ -190,6 +191,10 @@ class Plan:
         assert seeds.numel() == self.n_seeds
         self._ctx._check(_lib.helios_plan_launch(self._p, _ptr(seeds), C.c_uint64(rng_seed)))
 
+    def wait(self) -> None:
+        """Waits for this plan's last launch only; raises on device-side errors like Helios.sync()."""
+        self._ctx._check(_lib.helios_plan_wait(self._p))
+
     def destroy(self) -> None:
         if self._p is not None and self._p.value:
             _lib.helios_plan_destroy(self._p)
@@ -259,6 +264,7 @@ class Helios:
         self._keep = {}
         self._children = []          # plans and miss queues: destroyed before the context
         s = stream.cuda_stream if stream is not None else torch.cuda.current_stream(device).cuda_stream
+        self._stream_ptr = s
         rc = _lib.helios_create(C.byref(self._h), device, C.c_void_p(s))
         if rc != OK:
             self._h = C.c_void_p()

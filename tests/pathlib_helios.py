@@ -83,39 +83,49 @@ def gpu_path(h, helios, seeds: torch.Tensor, fanouts, rng_seed: int, fused: bool
 
 
 def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, tabs_dev, batch, fanouts, jobs,
-                    n_lanes: int = 3, recorded: bool = True):
-    """bench.py's launch configuration: n_lanes contexts, each on its own stream with its own buffers
-    and (recorded=True) its own recorded batch, sharing the graph and the cache tables; up to n_lanes
-    mini-batches are in flight.  jobs: list of (seeds on the GPU, rng_seed).  Returns one result dict
-    per job, as gpu_path does (misses served)."""
+                    n_lanes: int = 3, recorded: bool = True, per_lane: int = 1):
+    """bench.py's launch configuration: n_lanes contexts, each on its own stream with (recorded=True) a
+    recorded batch per buffer set, sharing the graph and the cache tables.  per_lane == 1: a lane is
+    synchronised before it gets its next batch, and the miss list is served (result key "out").
+    per_lane == 2: every lane has two buffer sets, a batch is queued behind the lane's running one and
+    each is waited for by helios_plan_wait; misses are not served (result key "out_before_miss").
+    jobs: list of (seeds on the GPU, rng_seed).  Returns one result dict per job, as gpu_path does."""
     import torch as T
+    assert per_lane == 1 or recorded
     dev = offsets.device
-    lanes = []
+    lanes, units = [], []
     for _ in range(n_lanes):
         ctx = helios.Helios(dev.index or 0, stream=T.cuda.Stream(device=dev))
         ctx.csr_load(offsets, indices)
         ctx.cache_build(order, n_hbm, n_host, row_bytes, *tabs_dev)
         ctx.sync()
-        hops = helios.alloc_hops(batch, fanouts, dev)
-        cap = batch + sum(hb.flat.numel() for hb in hops)
-        ctx.reserve(cap)
-        bf = dict(ctx=ctx, hops=hops, unique=T.empty(cap, dtype=T.int32, device=dev),
-                  inverse=T.empty(cap, dtype=T.int32, device=dev),
-                  out=T.full((cap, row_bytes), SENTINEL, dtype=T.uint8, device=dev),
-                  mp=T.empty(cap, dtype=T.int32, device=dev), mi=T.empty(cap, dtype=T.int32, device=dev),
-                  ms=T.empty(cap, dtype=T.int32, device=dev), sizes=T.zeros(2 * len(fanouts), dtype=T.int64).pin_memory(),
-                  nu=T.zeros(1, dtype=T.int64).pin_memory(), stats=T.zeros(4, dtype=T.int64).pin_memory(), plan=None)
-        lanes.append(bf)
+        lanes.append(ctx)
+    for w in range(per_lane):
+        for ctx in lanes:
+            hops = helios.alloc_hops(batch, fanouts, dev)
+            cap = batch + sum(hb.flat.numel() for hb in hops)
+            ctx.reserve(cap)
+            units.append(dict(ctx=ctx, hops=hops, unique=T.empty(cap, dtype=T.int32, device=dev),
+                              inverse=T.empty(cap, dtype=T.int32, device=dev),
+                              out=T.full((cap, row_bytes), SENTINEL, dtype=T.uint8, device=dev),
+                              mp=T.empty(cap, dtype=T.int32, device=dev), mi=T.empty(cap, dtype=T.int32, device=dev),
+                              ms=T.empty(cap, dtype=T.int32, device=dev),
+                              sizes=T.zeros(2 * len(fanouts), dtype=T.int64).pin_memory(),
+                              nu=T.zeros(1, dtype=T.int64).pin_memory(), stats=T.zeros(4, dtype=T.int64).pin_memory(),
+                              plan=None))
     T.cuda.synchronize()
     if recorded:
-        for bf in lanes:
+        for bf in units:
             bf["plan"] = bf["ctx"].plan_create(batch, fanouts, bf["hops"], bf["sizes"], bf["unique"], bf["inverse"],
                                                bf["nu"], bf["out"], bf["mp"], bf["mi"], bf["ms"], bf["stats"])
         T.cuda.synchronize()
     K = len(fanouts)
 
     def collect(bf):
-        bf["ctx"].sync()
+        if per_lane > 1:
+            bf["plan"].wait()
+        else:
+            bf["ctx"].sync()
         sizes, U, nm = bf["sizes"], int(bf["nu"][0]), int(bf["stats"][3])
         res = {"hops": []}
         for k in range(K):
@@ -125,28 +135,34 @@ def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, t
         n_cat = batch + sum(int(sizes[2 * k + 1]) for k in range(K))
         res.update(unique=bf["unique"][:U].cpu().numpy(), inverse=bf["inverse"][:n_cat].cpu().numpy(),
                    stats=bf["stats"].numpy().copy(), miss_pos=bf["mp"][:nm].cpu().numpy(),
-                   miss_id=bf["mi"][:nm].cpu().numpy(), miss_slot=bf["ms"][:nm].cpu().numpy(), out=bf["out"][:U].cpu().numpy())
+                   miss_id=bf["mi"][:nm].cpu().numpy(), miss_slot=bf["ms"][:nm].cpu().numpy())
+        res["out" if per_lane == 1 else "out_before_miss"] = bf["out"][:U].cpu().numpy()
         return res
 
     results = [None] * len(jobs)
+    n_units = len(units)
     for j, (seeds, rs) in enumerate(jobs):
-        bf = lanes[j % n_lanes]
-        if j >= n_lanes:
-            results[j - n_lanes] = collect(bf)
-            bf["out"].fill_(SENTINEL)
-            T.cuda.synchronize()
+        bf = units[j % n_units]
+        if j >= n_units:
+            results[j - n_units] = collect(bf)
+            with T.cuda.stream(T.cuda.ExternalStream(bf["ctx"]._stream_ptr, device=dev)):
+                bf["out"].fill_(SENTINEL)                 # in stream order: the lane may be running its other set
         if recorded:
             bf["plan"].launch(seeds, rs)
         else:
             bf["ctx"].prepare_batch(seeds, fanouts, rs, bf["hops"], bf["sizes"], bf["unique"], bf["inverse"], bf["nu"],
                                     bf["out"], bf["mp"], bf["mi"], bf["ms"], bf["stats"])
-        bf["ctx"].gather_miss(bf["mp"], bf["ms"], bf["mp"].numel(), bf["stats"][3:4], bf["out"])
-    for j in range(max(0, len(jobs) - n_lanes), len(jobs)):
-        results[j] = collect(lanes[j % n_lanes])
-    for bf in lanes:
+        if per_lane == 1:
+            bf["ctx"].gather_miss(bf["mp"], bf["ms"], bf["mp"].numel(), bf["stats"][3:4], bf["out"])
+    for j in range(max(0, len(jobs) - n_units), len(jobs)):
+        results[j] = collect(units[j % n_units])
+    for ctx in lanes:
+        ctx.sync()
+    for bf in units:
         if bf["plan"] is not None:
             bf["plan"].destroy()
-        bf["ctx"].close()
+    for ctx in lanes:
+        ctx.close()
     return results
 
 

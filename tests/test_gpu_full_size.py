@@ -62,7 +62,13 @@ def _check_batches(h, helios, oracle, sp, g, host_csr, rank_h, n_hbm, n_host, ta
         want = dict(wants[b])
         del want["out_before_miss"]
         assert_same(res, want)
-    say(f"  {sp.name}: {len(jobs)} recorded batches, three in flight: bit-exact")
+    got = lanes_in_flight(helios, g.offsets, g.indices, g.order, n_hbm, n_host, sp.row_bytes, tabs_dev, sp.batch,
+                          sp.fanouts, jobs + jobs, per_lane=2)
+    for b, res in zip(order_of_jobs + order_of_jobs, got):
+        want = dict(wants[b])
+        del want["out"]
+        assert_same(res, want)
+    say(f"  {sp.name}: {len(jobs)} recorded batches, one per lane, and {2 * len(jobs)}, two per lane: bit-exact")
 
 
 def test_workloads_2_and_4_full_size(helios, oracle):

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2310_00837_amd import workload as W
-from pathlib_helios import GpuCache, SENTINEL, assert_same, gpu_path, oracle_path, to_bytes
+from pathlib_helios import GpuCache, SENTINEL, assert_same, gpu_path, lanes_in_flight, oracle_path, to_bytes
 
 pytestmark = pytest.mark.gpu
 SEED = 1234
@@ -93,6 +93,34 @@ def test_recorded_batch_replays(helios, oracle, cfg):
     assert e.value.code == helios.ESTATE
     plan.destroy()
     h.close()
+
+
+def test_two_batches_queued_per_context(helios, oracle):
+    """The benchmark's timed configuration: three contexts on three streams, two buffer sets and two
+    recordings per context, a batch queued behind the running one, each waited for by helios_plan_wait."""
+    sp = W.spec(1)
+    g = W.make_graph(sp, SEED, "cpu")
+    feats = W.feature_rows(SEED, torch.arange(g.n_nodes), sp.dim, sp.dtype)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    first = helios.Helios(0)
+    off_d, idx_d = g.offsets.cuda(), g.indices.cuda()
+    first.csr_load(off_d, idx_d)
+    cache = GpuCache(first, feats, g.order, n_hbm, n_host)
+    order = g.order.numpy()
+    rank = oracle.rank_build(order)
+    by_rank = to_bytes(feats)[order]
+    tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
+            np.ascontiguousarray(by_rank[n_hbm + n_host:])]
+    n_jobs = 20
+    jobs = [(W.seed_batch(sp, g, b).cuda(), W.batch_rng_seed(SEED, b)) for b in range(n_jobs)]
+    got = lanes_in_flight(helios, off_d, idx_d, cache.order, n_hbm, n_host, sp.row_bytes,
+                          (cache.hbm, cache.host, cache.standin), sp.batch, sp.fanouts, jobs, per_lane=2)
+    for b, res in enumerate(got):
+        want = oracle_path(oracle, g.offsets.numpy(), g.indices.numpy(), jobs[b][0].cpu().numpy(), sp.fanouts, jobs[b][1],
+                           rank, n_hbm, n_host, *tabs, sp.row_bytes)
+        del want["out"]
+        assert_same(res, want)
+    first.close()
 
 
 def test_plan_needs_a_real_stream(helios):
