@@ -10,14 +10,6 @@ namespace helios {
 
 namespace {
 
-__device__ __forceinline__ uint32_t hash_id(uint32_t id, uint32_t mask) {    // the hash of dedup.hip
-    uint32_t h = id * 0x9E3779B1u;
-    h ^= h >> 15;
-    h *= 0x85EBCA77u;
-    h ^= h >> 13;
-    return h & mask;
-}
-
 __global__ __launch_bounds__(kBlock) void local_ids_kernel(const int32_t* __restrict__ ids, Count n_in, DedupScratch s,
                                                            int32_t* out, int32_t* err) {
     const int64_t n = n_in.get();

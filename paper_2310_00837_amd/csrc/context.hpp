@@ -14,6 +14,7 @@ constexpr int kCntFrontier = 0;     // [HELIOS_MAX_HOPS + 1] frontier sizes
 constexpr int kCntFlat = 16;        // [HELIOS_MAX_HOPS] sample-list sizes
 constexpr int kCntCat = 32;         // length of [seeds | flat_0 | ...]
 constexpr int kCntUnique = 33;
+constexpr int kCntHopTotal = 34;    // input length of a de-duplication between two hops (a copy of its flat size)
 constexpr int kCntTier = 40;        // [3] HBM hits, host hits, misses
 constexpr int kNumCounters = 64;
 constexpr uint32_t kVarsRing = 256;   // batch launches that may be queued on a context without a helios_sync
@@ -58,7 +59,9 @@ struct helios_ctx {
     int64_t* cnt = nullptr;                    // device int64[kNumCounters]
 
     int64_t cap_ids = 0;                       // IDs per call the scratch below has room for
-    helios::DedupScratch dd{nullptr, 0, nullptr, nullptr};
+    helios::DedupScratch dd{nullptr, 0, nullptr, nullptr};   // de-duplication of a batch's ID list, and helios_dedup
+    unsigned long long* hop_table[2] = {nullptr, nullptr};   // de-duplication of one hop's samples, hops alternate
+    int32_t* hop_slot_of = nullptr;
     int32_t* list_pos[2] = {nullptr, nullptr};
     int32_t* list_slot[2] = {nullptr, nullptr};
     int32_t* cat = nullptr;

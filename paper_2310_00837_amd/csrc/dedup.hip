@@ -3,10 +3,10 @@
 // unique = the distinct IDs in order of first occurrence.  The order is made
 // independent of thread scheduling by keeping, per distinct ID, the smallest
 // input position that holds it:
-//   1. insert: an open-addressing hash table of 64-bit words {id:32 | pos:32}.
-//      A slot is claimed with one compare-and-swap; later positions of the same
-//      ID fold in with a 64-bit atomic minimum (the ID is in the high half, so
-//      the minimum orders by position).  The slot of every input is remembered.
+//   1. insert: an open-addressing hash table of 64-bit words {id:32 | pos:32}
+//      (hashtable.hpp).  The slot of every input is remembered.  For IDs that
+//      the sampling kernel produces, that kernel does the inserting as it writes
+//      them (sample.hip); the insert kernel here serves helios_dedup.
 //   2. compact: input j is a first occurrence iff its slot's position is j; the
 //      flags are scanned in-workgroup and chained across workgroups, so the
 //      unique list comes out in input order in the same pass.  Between hops
@@ -25,71 +25,25 @@ namespace helios {
 
 namespace {
 
-constexpr unsigned long long kEmpty = ~0ull;
+__global__ __launch_bounds__(kBlock) void dedup_clear_kernel(ClearJob c) { clear_slots(c); }
 
-__device__ __forceinline__ uint32_t hash_id(uint32_t id, uint32_t mask) {
-    uint32_t h = id * 0x9E3779B1u;
-    h ^= h >> 15;
-    h *= 0x85EBCA77u;
-    h ^= h >> 13;
-    return h & mask;
-}
-
-__global__ __launch_bounds__(kBlock) void dedup_clear_kernel(unsigned long long* table, uint32_t n_slots) {
-    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n_slots; i += gridDim.x * kBlock) table[i] = kEmpty;
-}
-
-// The input is the concatenation of up to HELIOS_KERNELS_MAX_SEG segments whose lengths may be known
-// only on the device ([seeds | flat_0 | ...] for the whole-path call, one segment otherwise).  If
-// cat_out is given the concatenation is also written out, for the later passes to index.
-__global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int32_t* cat_out, int64_t* n_total_dev,
-                                                              int64_t n_nodes, DedupScratch s, int32_t* err) {
-    // With one segment the first ID is fetched before the device-side count has arrived (the buffer
-    // holds len.host entries, so the read is in bounds whatever the count turns out to be).
+__global__ __launch_bounds__(kBlock) void dedup_insert_kernel(const int32_t* __restrict__ ids, Count n_in, int64_t n_nodes,
+                                                              DedupScratch s, int32_t* err) {
+    // The first ID is fetched before the device-side count has arrived (the buffer holds n_in.host
+    // entries, so the read is in bounds whatever the count turns out to be).
     const int64_t j0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    const bool one = in.n_seg == 1 && !in.vars;
     int32_t early = 0;
-    if (one && j0 < in.len[0].host) early = in.src[0][j0];
-    int64_t start[HELIOS_KERNELS_MAX_SEG + 1];
-    start[0] = 0;
-#pragma unroll
-    for (int k = 0; k < HELIOS_KERNELS_MAX_SEG; ++k) start[k + 1] = start[k] + (k < in.n_seg ? in.len[k].get() : 0);
-    const int64_t n = start[HELIOS_KERNELS_MAX_SEG];
-    if (blockIdx.x == 0 && threadIdx.x == 0) *n_total_dev = n;
+    if (j0 < n_in.host) early = ids[j0];
+    const int64_t n = n_in.get();
     const uint32_t mask = s.n_slots - 1;
     for (int64_t j = j0; j < n; j += static_cast<int64_t>(gridDim.x) * kBlock) {
-        int32_t id;
-        if (one && j == j0) {
-            id = early;
-        } else {
-            int k = 0;
-#pragma unroll
-            for (int q = 1; q < HELIOS_KERNELS_MAX_SEG; ++q)
-                if (q < in.n_seg && j >= start[q]) k = q;
-            const int32_t* src = (k == 0 && in.vars) ? in.vars->seeds : in.src[k];
-            id = src[j - start[k]];
-        }
-        if (cat_out) cat_out[j] = id;
+        const int32_t id = j == j0 ? early : ids[j];
         if (id < 0 || static_cast<int64_t>(id) >= n_nodes) {
             raise(err, kErrData);
             s.slot_of[j] = -1;
             continue;
         }
-        const unsigned long long mine = (static_cast<unsigned long long>(static_cast<uint32_t>(id)) << 32) |
-                                        static_cast<uint32_t>(j);
-        uint32_t slot = hash_id(static_cast<uint32_t>(id), mask);
-        // the table is at most half full, so an empty slot is always reached
-        while (true) {
-            // try to claim straight away: one round trip when the slot is free (the common case)
-            const unsigned long long cur = atomicCAS(s.table + slot, kEmpty, mine);
-            if (cur == kEmpty) break;                           // claimed
-            if (static_cast<uint32_t>(cur >> 32) == static_cast<uint32_t>(id)) {
-                if (mine < cur) atomicMin(s.table + slot, mine);
-                break;
-            }
-            slot = (slot + 1) & mask;
-        }
-        s.slot_of[j] = static_cast<int32_t>(slot);
+        s.slot_of[j] = static_cast<int32_t>(table_insert(s.table, mask, static_cast<uint32_t>(id), static_cast<uint32_t>(j)));
     }
 }
 
@@ -107,7 +61,8 @@ __global__ __launch_bounds__(kBlock) void dedup_insert_kernel(ConcatArgs in, int
 enum CompactMode { kCompactPlain = 0, kCompactNextHop = 1, kCompactLookup = 2 };
 
 template <int MODE>
-__global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __restrict__ ids, Count n_in, DedupScratch s,
+__global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __restrict__ ids, SegLens lens, int64_t n_max,
+                                                               int64_t* n_total_dev, DedupScratch s,
                                                                int32_t* unique, int64_t unique_cap,
                                                                int64_t* n_unique_dev, int64_t* n_unique_out,
                                                                NextHopCount next, LookupOut look, ScanState scan,
@@ -116,8 +71,13 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
     __shared__ uint32_t s_ticket, s_agg[NC], s_excl[NC];
     __shared__ ScanLookbackLds<NC> s_look;
-    const int64_t n = n_in.get();
+    int64_t n = 0;
+#pragma unroll
+    for (int k = 0; k < HELIOS_KERNELS_MAX_SEG; ++k)
+        if (k < lens.n_seg) n += lens.len[k].get();
+    n = n < n_max ? n : n_max;
     const int64_t n_tiles = (n + kTileItems - 1) / kTileItems;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_total_dev = n;
     if (n == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
         *n_unique_dev = 0;
         if (n_unique_out) *n_unique_out = 0;
@@ -148,6 +108,7 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
     unsigned long long word[kItemsPerThread];
 #pragma unroll
     for (int k = 0; k < kItemsPerThread; ++k) {
+        if (static_cast<uint32_t>(slot[k]) >= s.n_slots) slot[k] = -1;      // never a slot of this table
         word[k] = slot[k] >= 0 ? s.table[slot[k]] : ~0ull;
         cnt[k] = 0;
         r[k] = 0;
@@ -194,6 +155,12 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
     for (int k = 0; k < kItemsPerThread; ++k) {
         if (first[k]) {
             s.index_of_first[j0 + k] = static_cast<int32_t>(at);
+            if (MODE == kCompactNextHop && at == unique_cap) {
+                // the frontier is cut off here: the next hop samples the nodes that fit, and its sample list
+                // ends where this node's samples would have begun
+                next.indptr[unique_cap] = at_cnt;
+                *next.n_flat_dev = at_cnt;
+            }
             if (at < unique_cap) {
                 unique[at] = id[k];
                 if (MODE == kCompactNextHop) next.indptr[at] = at_cnt;
@@ -224,8 +191,10 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
         if (total > unique_cap) raise(err, kErrCapacity);
         if (MODE == kCompactNextHop) {
             const int64_t total_cnt = static_cast<int64_t>(s_excl[NC - 1]) + tile_second;
-            next.indptr[total < unique_cap ? total : unique_cap] = total_cnt;
-            *next.n_flat_dev = total_cnt;
+            if (total <= unique_cap) {           // else the thread at the cut has written both
+                next.indptr[total] = total_cnt;
+                *next.n_flat_dev = total_cnt;
+            }
             if (next.size_out) { next.size_out[0] = total; next.size_out[1] = total_cnt; }
             if (total_cnt > next.flat_cap) raise(err, kErrCapacity);
         }
@@ -243,12 +212,15 @@ __global__ __launch_bounds__(kBlock) void dedup_compact_kernel(const int32_t* __
 }
 
 __global__ __launch_bounds__(kBlock) void dedup_inverse_kernel(Count n_in, DedupScratch s, int32_t* inverse) {
-    const int64_t n = n_in.get();
+    const int64_t n = n_in.get();      // written by the compaction pass
     for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < n;
          j += static_cast<int64_t>(gridDim.x) * kBlock) {
         const int32_t slot = s.slot_of[j];
         int32_t inv = -1;
-        if (slot >= 0) inv = s.index_of_first[static_cast<uint32_t>(s.table[slot])];
+        if (static_cast<uint32_t>(slot) < s.n_slots) {
+            const uint32_t first = static_cast<uint32_t>(s.table[slot]);      // position of the ID's first occurrence
+            if (static_cast<int64_t>(first) < n) inv = s.index_of_first[first];
+        }
         inverse[j] = inv;
     }
 }
@@ -262,31 +234,39 @@ unsigned grid_for(int64_t n_max, unsigned cap_blocks) {
 
 }  // namespace
 
-hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat,
-                        int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
-                        bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
-                        int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next, const LookupOut* look,
-                        const ScanState& scan, int32_t* err) {
+hipError_t launch_dedup_insert(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
+                               const DedupScratch& s, bool table_is_clear, int32_t* err) {
     const dim3 block(kBlock);
     if (!table_is_clear)
-        hipLaunchKernelGGL(dedup_clear_kernel, dim3(grid_for(s.n_slots, 2048)), block, 0, stream, s.table, s.n_slots);
-    hipLaunchKernelGGL(dedup_insert_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, in, cat_out, n_total_dev,
-                       n_nodes, s, err);
-    const Count n{n_total_dev, n_max};
+        hipLaunchKernelGGL(dedup_clear_kernel, dim3(grid_for(s.n_slots, 2048)), block, 0, stream, ClearJob{s.table, s.n_slots});
+    hipLaunchKernelGGL(dedup_insert_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, ids, n, n_nodes, s, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_dedup_compact(hipStream_t stream, const int32_t* ids, const SegLens& lens, int64_t n_max,
+                                int64_t* n_total_dev, const DedupScratch& s, int32_t* unique, int64_t unique_cap,
+                                int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next, const LookupOut* look,
+                                const ScanState& scan, int32_t* err) {
+    const dim3 block(kBlock);
     int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
     if (tiles < 1) tiles = 1;
     const dim3 grid(static_cast<unsigned>(tiles));
     if (next)
-        hipLaunchKernelGGL(dedup_compact_kernel<kCompactNextHop>, grid, block, 0, stream, ids_flat, n, s, unique,
-                           unique_cap, n_unique_dev, n_unique_out, *next, LookupOut{}, scan, err);
+        hipLaunchKernelGGL(dedup_compact_kernel<kCompactNextHop>, grid, block, 0, stream, ids, lens, n_max, n_total_dev, s,
+                           unique, unique_cap, n_unique_dev, n_unique_out, *next, LookupOut{}, scan, err);
     else if (look)
-        hipLaunchKernelGGL(dedup_compact_kernel<kCompactLookup>, grid, block, 0, stream, ids_flat, n, s, unique,
-                           unique_cap, n_unique_dev, n_unique_out, NextHopCount{}, *look, scan, err);
+        hipLaunchKernelGGL(dedup_compact_kernel<kCompactLookup>, grid, block, 0, stream, ids, lens, n_max, n_total_dev, s,
+                           unique, unique_cap, n_unique_dev, n_unique_out, NextHopCount{}, *look, scan, err);
     else
-        hipLaunchKernelGGL(dedup_compact_kernel<kCompactPlain>, grid, block, 0, stream, ids_flat, n, s, unique,
-                           unique_cap, n_unique_dev, n_unique_out, NextHopCount{}, LookupOut{}, scan, err);
-    if (inverse)
-        hipLaunchKernelGGL(dedup_inverse_kernel, dim3(grid_for(n_max, 4096)), block, 0, stream, n, s, inverse);
+        hipLaunchKernelGGL(dedup_compact_kernel<kCompactPlain>, grid, block, 0, stream, ids, lens, n_max, n_total_dev, s,
+                           unique, unique_cap, n_unique_dev, n_unique_out, NextHopCount{}, LookupOut{}, scan, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_dedup_inverse(hipStream_t stream, const int64_t* n_total_dev, int64_t n_max, const DedupScratch& s,
+                                int32_t* inverse) {
+    hipLaunchKernelGGL(dedup_inverse_kernel, dim3(grid_for(n_max, 4096)), dim3(kBlock), 0, stream, Count{n_total_dev, n_max},
+                       s, inverse);
     return hipGetLastError();
 }
 

@@ -25,6 +25,11 @@ void free_scratch(helios_ctx* c) {
     }
     (void)hipFree(c->cat);
     (void)hipFree(c->scan_status);
+    (void)hipFree(c->hop_table[0]);
+    (void)hipFree(c->hop_table[1]);
+    (void)hipFree(c->hop_slot_of);
+    c->hop_table[0] = c->hop_table[1] = nullptr;
+    c->hop_slot_of = nullptr;
     c->dd = DedupScratch{nullptr, 0, nullptr, nullptr};
     c->cat = nullptr;
     c->scan_status = nullptr;
@@ -47,6 +52,9 @@ int ensure_capacity(helios_ctx* c, int64_t n) {
     HIP_TRY(c, hipMalloc(&c->dd.table, sizeof(unsigned long long) * slots));
     HIP_TRY(c, hipMalloc(&c->dd.slot_of, sizeof(int32_t) * cap));
     HIP_TRY(c, hipMalloc(&c->dd.index_of_first, sizeof(int32_t) * cap));
+    HIP_TRY(c, hipMalloc(&c->hop_table[0], sizeof(unsigned long long) * slots));
+    HIP_TRY(c, hipMalloc(&c->hop_table[1], sizeof(unsigned long long) * slots));
+    HIP_TRY(c, hipMalloc(&c->hop_slot_of, sizeof(int32_t) * cap));
     for (int t = 0; t < 2; ++t) {
         HIP_TRY(c, hipMalloc(&c->list_pos[t], sizeof(int32_t) * cap));
         HIP_TRY(c, hipMalloc(&c->list_slot[t], sizeof(int32_t) * cap));
@@ -127,62 +135,61 @@ uint32_t dedup_slots(const helios_ctx* c, int64_t n_max) {
     return want < c->dd.n_slots ? want : c->dd.n_slots;
 }
 
-int dedup_impl(helios_ctx* c, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat, int32_t* cat_out,
-               bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse, int64_t* n_unique_dev,
-               int64_t* n_unique_out, const NextHopCount* next, const LookupOut* look) {
-    ScanState scan;
-    int rc = next_scan(c, &scan);
-    if (rc) return rc;
-    DedupScratch s = c->dd;
-    s.n_slots = dedup_slots(c, n_max);
-    c->blocks_ready = false;
-    c->last_slots = s.n_slots;
-    HIP_TRY(c, launch_dedup(c->stream, in, n_max, ids_flat, cat_out, c->cnt + kCntCat, c->g.n_nodes, s, table_is_clear,
-                            unique, unique_cap, inverse, n_unique_dev, n_unique_out, next, look, scan, c->err));
-    return HELIOS_OK;
+SegLens one_segment(Count n) {
+    SegLens lens{};
+    lens.n_seg = 1;
+    lens.len[0] = n;
+    return lens;
 }
 
-ConcatArgs one_segment(const int32_t* ids, Count n) {
-    ConcatArgs in{};
-    in.n_seg = 1;
-    in.src[0] = ids;
-    in.len[0] = n;
-    return in;
-}
-
-// Hop 0: count pass over the seeds, sampling pass.  Hop h > 0: the de-duplication of flat_{h-1}
-// yields frontier_h together with its indptr, then the sampling pass.  Each sampling pass empties
-// the hash table of the de-duplication that follows it (final_dedup_max > 0: also the last one, for
-// a de-duplication of that many IDs).
+// Hop 0: count pass over the seeds (it also empties the tables that the first sampling pass fills),
+// sampling pass.  Hop h > 0: the de-duplication of flat_{h-1} yields frontier_h together with its
+// indptr, then the sampling pass.  A sampling pass inserts its samples into the table of the
+// de-duplication between this hop and the next, and, with batch_dedup_max > 0 (the whole-path call),
+// into the table of the batch's ID list [seeds | flat_0 | ...], which c->cat receives; so those
+// de-duplications start at their compaction pass.
 int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                 uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p,
-                int64_t final_dedup_max) {
+                int64_t batch_dedup_max) {
     const BatchVars* vars = c->recording ? c->vars : nullptr;
+    const InsertInto batch_table = batch_dedup_max > 0 ? InsertInto{c->dd.table, dedup_slots(c, batch_dedup_max), c->dd.slot_of}
+                                                       : InsertInto{nullptr, 0, nullptr};
+    auto hop_table = [&](int h) {               // hops alternate between two tables
+        return h + 1 < n_hops ? InsertInto{c->hop_table[h % 2], dedup_slots(c, p.flat_max[h]), c->hop_slot_of}
+                              : InsertInto{nullptr, 0, nullptr};
+    };
+    auto clear_of = [](const InsertInto& t) { return ClearJob{t.table, t.table ? t.n_slots : 0u}; };
+    Count prev_flat[HELIOS_MAX_HOPS];
     Count nf{nullptr, n_seeds};
     {
         ScanState scan;
         int rc = next_scan(c, &scan);
         if (rc) return rc;
         HIP_TRY(c, launch_frontier_count(c->stream, c->g, seeds, vars, hops[0].frontier, nf, n_seeds, fanouts[0],
-                                         hops[0].indptr, hops[0].flat_cap, c->cnt + kCntFlat + 0, sizes, scan, c->err));
+                                         hops[0].indptr, hops[0].flat_cap, c->cnt + kCntFlat + 0, sizes,
+                                         clear_of(hop_table(0)), clear_of(batch_table), scan, c->err));
     }
     for (int h = 0; h < n_hops; ++h) {
         const bool last = h + 1 == n_hops;
-        const int64_t next_dedup = last ? final_dedup_max : p.flat_max[h];
-        const uint32_t clear_slots = next_dedup > 0 || !last ? dedup_slots(c, next_dedup) : 0u;
+        const InsertInto mine = hop_table(h);
         HIP_TRY(c, launch_sample_hop(c->stream, c->g, hops[h].frontier, hops[h].indptr, nf, p.frontier_max[h], fanouts[h],
-                                     h, rng_seed, vars, hops[h].flat, hops[h].flat_cap,
-                                     clear_slots ? c->dd.table : nullptr, clear_slots));
+                                     h, rng_seed, vars, hops[h].flat, p.flat_max[h], clear_of(hop_table(h + 1)), mine,
+                                     batch_table, c->cat, n_seeds, prev_flat, c->err));
+        prev_flat[h] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
         if (!last) {
             NextHopCount next{c->g.offsets, c->g.n_nodes, fanouts[h + 1], hops[h + 1].indptr, hops[h + 1].flat_cap,
                               c->cnt + kCntFlat + h + 1, sizes ? sizes + 2 * (h + 1) : nullptr};
-            int rc = dedup_impl(c, one_segment(hops[h].flat, Count{c->cnt + kCntFlat + h, p.flat_max[h]}), p.flat_max[h],
-                                hops[h].flat, nullptr, true, hops[h + 1].frontier, hops[h + 1].frontier_cap, nullptr,
-                                c->cnt + kCntFrontier + h + 1, nullptr, &next, nullptr);
+            ScanState scan;
+            int rc = next_scan(c, &scan);
             if (rc) return rc;
+            const DedupScratch s{mine.table, mine.n_slots, mine.slot_of, c->dd.index_of_first};
+            HIP_TRY(c, launch_dedup_compact(c->stream, hops[h].flat, one_segment(prev_flat[h]), p.flat_max[h],
+                                            c->cnt + kCntHopTotal, s, hops[h + 1].frontier, hops[h + 1].frontier_cap,
+                                            c->cnt + kCntFrontier + h + 1, nullptr, &next, nullptr, scan, c->err));
             nf = Count{c->cnt + kCntFrontier + h + 1, p.frontier_max[h + 1]};
         }
     }
+    c->blocks_ready = false;
     return HELIOS_OK;
 }
 
@@ -416,8 +423,19 @@ int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* uniq
     DeviceGuard guard(c->device);
     int rc = ensure_capacity(c, n_ids);
     if (rc) return rc;
-    return dedup_impl(c, one_segment(ids, Count{nullptr, n_ids}), n_ids, ids, nullptr, false, unique, unique_cap, inverse,
-                      c->cnt + kCntUnique, n_unique, nullptr, nullptr);
+    ScanState scan;
+    rc = next_scan(c, &scan);
+    if (rc) return rc;
+    DedupScratch s = c->dd;
+    s.n_slots = dedup_slots(c, n_ids);
+    c->blocks_ready = false;
+    c->last_slots = s.n_slots;
+    const Count n{nullptr, n_ids};
+    HIP_TRY(c, launch_dedup_insert(c->stream, ids, n, n_ids, c->g.n_nodes, s, false, c->err));
+    HIP_TRY(c, launch_dedup_compact(c->stream, ids, one_segment(n), n_ids, c->cnt + kCntCat, s, unique, unique_cap,
+                                    c->cnt + kCntUnique, n_unique, nullptr, nullptr, scan, c->err));
+    if (inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, c->cnt + kCntCat, n_ids, s, inverse));
+    return HELIOS_OK;
 }
 
 int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, int32_t* miss_pos, int32_t* miss_id,
@@ -463,23 +481,24 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
     if (miss_cap > 0 && (!miss_pos || !miss_id || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL miss list");
     rc = ensure_capacity(c, p.ids_max);
     if (rc) return rc;
-    rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, p.cat_max > 0 ? p.cat_max : 1);
+    const int64_t batch_max = p.cat_max > 0 ? p.cat_max : 1;
+    rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, batch_max);
     if (rc) return rc;
-    ConcatArgs cat{};
-    cat.vars = c->recording ? c->vars : nullptr;
-    cat.n_seg = n_hops + 1;
-    cat.src[0] = seeds;
-    cat.len[0] = Count{nullptr, n_seeds};
-    for (int h = 0; h < n_hops; ++h) {
-        cat.src[h + 1] = hops[h].flat;
-        cat.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
-    }
-    // the final de-duplication classifies the unique IDs by cache tier in the same pass
+    SegLens lens{};
+    lens.n_seg = n_hops + 1;
+    lens.len[0] = Count{nullptr, n_seeds};
+    for (int h = 0; h < n_hops; ++h) lens.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
+    // the sampling passes have filled the table; the compaction classifies the unique IDs by cache tier on the way
     LookupOut look{c->rank, c->n_hbm, c->n_host, tier_lists(c), miss_pos, miss_id, miss_slot, miss_cap,
                    reinterpret_cast<int64_t*>(stats)};
-    rc = dedup_impl(c, cat, p.cat_max, c->cat, c->cat, true, unique, unique_cap, inverse, c->cnt + kCntUnique, n_unique,
-                    nullptr, &look);
+    ScanState scan;
+    rc = next_scan(c, &scan);
     if (rc) return rc;
+    DedupScratch s = c->dd;
+    s.n_slots = dedup_slots(c, batch_max);
+    c->last_slots = s.n_slots;
+    HIP_TRY(c, launch_dedup_compact(c->stream, c->cat, lens, p.cat_max, c->cnt + kCntCat, s, unique, unique_cap,
+                                    c->cnt + kCntUnique, n_unique, nullptr, &look, scan, c->err));
     const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
     if (c->missq) {                 // the misses are on their way while the cached tiers are copied
         const int64_t m_max = miss_cap < u_max ? miss_cap : u_max;
@@ -493,7 +512,11 @@ static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_see
         c->last_frontier_max[h] = p.frontier_max[h];
         c->last_flat_max[h] = p.flat_max[h];
     }
-    return copy_tiers(c, Count{c->cnt + kCntUnique, u_max}, out);
+    rc = copy_tiers(c, Count{c->cnt + kCntUnique, u_max}, out);
+    if (rc) return rc;
+    // last, so that the row copies (and with them the host link) start one launch earlier
+    if (inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, c->cnt + kCntCat, p.cat_max, s, inverse));
+    return HELIOS_OK;
 }
 
 int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,

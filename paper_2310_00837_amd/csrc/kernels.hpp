@@ -2,6 +2,7 @@
 // Every launcher enqueues on `stream` and returns the hipError_t of the launch.
 #pragma once
 #include "common.hpp"
+#include "hashtable.hpp"
 #include "scan.hpp"
 #define HELIOS_KERNELS_MAX_SEG 9
 
@@ -17,18 +18,22 @@ struct CsrView {
 // Count pass of hop 0: indptr[i] = start of frontier[i]'s samples in flat, indptr[n] = total
 // (also to *n_flat_dev); size_out (nullable, device-accessible) gets {n, total}.  frontier_out
 // (nullable, may equal frontier) receives a copy of the frontier; vars (nullable): the frontier
-// is vars->seeds.  The later hops get their indptr from launch_dedup.
+// is vars->seeds.  The later hops get their indptr from launch_dedup_compact.  clear_a / clear_b: tables
+// set to all ones on the way (those the sampling pass of hop 0 inserts into).
 hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchVars* vars,
                                  int32_t* frontier_out, Count n, int64_t n_max, int32_t fanout, int64_t* indptr,
-                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, const ScanState& scan,
-                                 int32_t* err);
+                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, ClearJob clear_a, ClearJob clear_b,
+                                 const ScanState& scan, int32_t* err);
 // Sampling pass: flat[indptr[i] + k] = k-th sample of frontier[i].  vars (nullable) overrides
-// rng_seed.  clear_table (nullable) is set to all ones over clear_slots words on the way (the hash
-// table of the de-duplication that follows the hop).
+// rng_seed.  Every sample is also inserted into hop_table (position = its place in flat) and into
+// batch_table (position = its place in [seeds | flat_0 | ...], which cat_out receives; with hop == 0
+// the frontier itself is inserted as the seeds; prev_flat = sizes of flat_0 .. flat_{hop-1}); either
+// table may be absent.  clear: a table set to all ones on the way (one that a later kernel fills).
 hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, const int64_t* indptr,
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
-                             const BatchVars* vars, int32_t* flat, int64_t flat_cap, unsigned long long* clear_table,
-                             uint32_t clear_slots);
+                             const BatchVars* vars, int32_t* flat, int64_t flat_cap, ClearJob clear, InsertInto hop_table,
+                             InsertInto batch_table, int32_t* cat_out, int64_t n_seeds, const Count* prev_flat,
+                             int32_t* err);
 
 // ---- dedup.hip
 struct DedupScratch {
@@ -37,12 +42,11 @@ struct DedupScratch {
     int32_t* slot_of;            // [n] table slot of every input position
     int32_t* index_of_first;     // [n] index in `unique` of a first occurrence
 };
-// Up to HELIOS_KERNELS_MAX_SEG segments whose lengths may be known only on the device.
-struct ConcatArgs {
-    const int32_t* src[HELIOS_KERNELS_MAX_SEG];
+// The lengths of up to HELIOS_KERNELS_MAX_SEG segments whose concatenation is de-duplicated (each may be
+// known only on the device).
+struct SegLens {
     Count len[HELIOS_KERNELS_MAX_SEG];
     int n_seg;
-    const BatchVars* vars;       // nullable: if set, segment 0 is vars->seeds
 };
 // What the de-duplication between two hops also computes for the hop that follows: the sample
 // counts min(deg, fanout) of the new frontier, scanned into indptr (indptr[n_unique] = total, also
@@ -71,16 +75,22 @@ struct LookupOut {
     int64_t miss_cap;
     int64_t* stats_out;          // device-accessible int64[4], nullable
 };
-// De-duplicates the concatenation of the segments of `in` (n_max bounds its length).  ids_flat is
-// where the concatenation can be indexed: the single segment itself, or cat_out, which the first
-// pass then fills.  *n_total_dev receives the input length.  table_is_clear: an earlier kernel on the
-// stream has already set s.table[0, s.n_slots) to all ones.
-hipError_t launch_dedup(hipStream_t stream, const ConcatArgs& in, int64_t n_max, const int32_t* ids_flat,
-                        int32_t* cat_out, int64_t* n_total_dev, int64_t n_nodes, const DedupScratch& s,
-                        bool table_is_clear, int32_t* unique, int64_t unique_cap, int32_t* inverse,
-                        int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next /* nullable */,
-                        const LookupOut* look /* nullable; not together with next */, const ScanState& scan,
-                        int32_t* err);
+// First pass of a de-duplication as a kernel of its own (for IDs that no kernel of this library
+// produced): clears s.table unless table_is_clear, then inserts ids[0, n).
+hipError_t launch_dedup_insert(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
+                               const DedupScratch& s, bool table_is_clear, int32_t* err);
+// Second pass: the IDs ids[0, n), n = the sum of lens (n_max bounds it; *n_total_dev receives it), have
+// been inserted into s.table with their positions and s.slot_of is filled.  unique = the first
+// occurrences in input order (*n_unique_dev, *n_unique_out (nullable) = their number),
+// s.index_of_first[j] = index in unique of a first occurrence j.
+hipError_t launch_dedup_compact(hipStream_t stream, const int32_t* ids, const SegLens& lens, int64_t n_max,
+                                int64_t* n_total_dev, const DedupScratch& s, int32_t* unique, int64_t unique_cap,
+                                int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next /* nullable */,
+                                const LookupOut* look /* nullable; not together with next */, const ScanState& scan,
+                                int32_t* err);
+// Third pass (optional): inverse[j] = index in unique of ids[j], for j < *n_total_dev.
+hipError_t launch_dedup_inverse(hipStream_t stream, const int64_t* n_total_dev, int64_t n_max, const DedupScratch& s,
+                                int32_t* inverse);
 
 // ---- cache.hip
 hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n_nodes, int32_t* rank, int32_t* err);

@@ -19,6 +19,14 @@
 //           number of workgroups can run, in any order.
 // Fan-outs above 64 use one wave per node, loop over the picks in chunks of 64
 // and keep the chosen positions in LDS.
+//
+// The sampled IDs are de-duplicated right afterwards (into the next hop's
+// frontier, and, in the whole-path call, into the batch's ID list), so the lane
+// that writes a sample also inserts it into the hash tables of those
+// de-duplications: they then start at their second pass, and a mini-batch has
+// two kernel launches fewer per hop.  The tables must be empty before the first
+// insert: each kernel here clears, on the way, the tables that the kernels
+// after it fill.
 #include "kernels.hpp"
 #include "philox.hpp"
 
@@ -40,6 +48,7 @@ struct CountArgs {
     int64_t flat_cap;
     int64_t* n_flat_dev;
     int64_t* size_out;            // nullable: [0] = frontier size, [1] = sample-list size
+    ClearJob clear[2];            // tables that the sampling pass of this hop inserts into
     ScanState scan;
     int32_t* err;
 };
@@ -48,6 +57,8 @@ __global__ __launch_bounds__(kBlock) void frontier_count_kernel(CountArgs a) {
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
     __shared__ uint32_t s_ticket, s_agg[1], s_excl[1];
     __shared__ ScanLookbackLds<1> s_look;
+    clear_slots(a.clear[0]);                     // side job of the whole grid
+    clear_slots(a.clear[1]);
     const int64_t n = a.n.get();
     const int64_t n_tiles = (n + kTileItems - 1) / kTileItems;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -108,37 +119,72 @@ struct HopArgs {
     const BatchVars* vars;        // nullable: rng_seed comes from here (recorded batch)
     int32_t* flat;
     int64_t flat_cap;
-    unsigned long long* clear_table;
-    uint32_t clear_slots;
+    ClearJob clear;               // the table the next hop's sampling pass inserts into
+    InsertInto hop_table;         // de-duplication of this hop's samples; position = place in flat
+    InsertInto batch_table;       // de-duplication of [seeds | flat_0 | ...]; position = place in that list
+    int32_t* cat_out;             // with batch_table: receives [seeds | flat_0 | ...]
+    int64_t n_seeds;
+    Count prev_flat[HELIOS_KERNELS_MAX_SEG - 1];   // sizes of flat_0 .. flat_{hop-1}
+    int32_t* err;
 };
+
+// flat[at] = id has just been written: the same lane inserts id into the tables of the de-duplications
+// that follow.  cat_at is the place of the sample in [seeds | flat_0 | ...].
+__device__ __forceinline__ void insert_sample(const HopArgs& a, int32_t id, int64_t at, int64_t cat_at) {
+    const bool node = id >= 0 && static_cast<int64_t>(id) < a.n_nodes;
+    if (!node) raise(a.err, kErrData);
+    if (a.hop_table.table)
+        a.hop_table.slot_of[at] = node ? static_cast<int32_t>(table_insert(a.hop_table.table, a.hop_table.n_slots - 1,
+                                                                           static_cast<uint32_t>(id), static_cast<uint32_t>(at)))
+                                       : -1;
+    if (a.batch_table.table) {
+        a.cat_out[cat_at] = id;
+        a.batch_table.slot_of[cat_at] =
+            node ? static_cast<int32_t>(table_insert(a.batch_table.table, a.batch_table.n_slots - 1, static_cast<uint32_t>(id),
+                                                     static_cast<uint32_t>(cat_at)))
+                 : -1;
+    }
+}
 
 template <int G>
 __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     constexpr int kGroups = kBlock / G;          // nodes per workgroup and step
     __shared__ int32_t s_chosen[(G == kWave) ? kWavesPerBlock * kMaxFanout : 1];
 
-    // side job: empty the hash table of the de-duplication that follows this hop
-    for (uint32_t w = blockIdx.x * kBlock + threadIdx.x; w < a.clear_slots; w += gridDim.x * kBlock) a.clear_table[w] = ~0ull;
+    clear_slots(a.clear);                        // side job of the whole grid
 
     const int group = threadIdx.x / G;
     const int l = threadIdx.x % G;
     const int f = a.fanout;
-    if (f <= 0) return;
     const int64_t n = a.n_frontier.get();
+    const bool seeds_too = a.batch_table.table && a.hop == 0;   // the frontier of hop 0 is the head of the batch's list
+    int64_t cat_base = a.n_seeds;                // where flat_hop starts in [seeds | flat_0 | ...]
+    for (int h = 0; h < a.hop; ++h) cat_base += a.prev_flat[h].get();
+    if (f <= 0 && !seeds_too) return;
     const uint64_t rng_seed = a.vars ? a.vars->rng_seed : a.rng_seed;
     const int64_t step = static_cast<int64_t>(gridDim.x) * kGroups;
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * kGroups + group; i < n; i += step) {
         // the lanes of a group read the same words
         const int32_t v = a.frontier[i];
         const int64_t out = a.indptr[i];
+        if (seeds_too && l == 0) {               // seed i is element i of the batch's list
+            a.cat_out[i] = v;
+            a.batch_table.slot_of[i] = v >= 0 && static_cast<int64_t>(v) < a.n_nodes
+                                           ? static_cast<int32_t>(table_insert(a.batch_table.table, a.batch_table.n_slots - 1,
+                                                                               static_cast<uint32_t>(v), static_cast<uint32_t>(i)))
+                                           : -1;
+        }
+        if (f <= 0) continue;
         if (v < 0 || static_cast<int64_t>(v) >= a.n_nodes) continue;      // reported by the count pass
         const int64_t base = a.offsets[v];
         const int64_t d64 = a.offsets[v + 1] - base;
         if (d64 <= 0 || d64 > 0x7fffffffLL) continue;
         const int32_t deg = static_cast<int32_t>(d64);
         const int cnt = deg < f ? deg : f;
-        // `out` can only be off if an earlier output overflowed its capacity; never write outside flat
-        const bool out_ok = out >= 0 && out + cnt <= a.flat_cap;
+        // `out` can only be off if an earlier output overflowed its capacity; never write outside flat, but
+        // write every place below the capacity: the de-duplications read all of them
+        const bool out_ok = out >= 0;
+        const int64_t room = a.flat_cap - out;   // samples of this node that fit
 
         if (f <= G) {
             int32_t pos = l;                                  // deg <= f: the whole row, CSR order
@@ -157,13 +203,21 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
                     if (floyd && l > i2 && si == t) s = j;
                 }
             }
-            if (l < cnt && out_ok) a.flat[out + l] = a.indices[base + s];
+            if (l < cnt && out_ok && l < room) {
+                const int32_t id = a.indices[base + s];
+                a.flat[out + l] = id;
+                insert_sample(a, id, out + l, cat_base + out + l);
+            }
             continue;
         }
         if constexpr (G == kWave) {                           // fan-out above 64: one wave per node
             if (deg <= f) {
                 for (int k = l; k < deg; k += kWave)
-                    if (out_ok) a.flat[out + k] = a.indices[base + k];
+                    if (out_ok && k < room) {
+                        const int32_t id = a.indices[base + k];
+                        a.flat[out + k] = id;
+                        insert_sample(a, id, out + k, cat_base + out + k);
+                    }
                 continue;
             }
             int32_t* chosen = s_chosen + wave_id() * kMaxFanout;
@@ -186,7 +240,11 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
                 }
                 if (active) {
                     chosen[k] = s;
-                    if (out_ok) a.flat[out + k] = a.indices[base + s];
+                    if (out_ok && k < room) {
+                        const int32_t id = a.indices[base + s];
+                        a.flat[out + k] = id;
+                        insert_sample(a, id, out + k, cat_base + out + k);
+                    }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -202,22 +260,29 @@ int group_lanes(int32_t fanout) { return fanout <= 8 ? 8 : fanout <= 16 ? 16 : f
 
 hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchVars* vars,
                                  int32_t* frontier_out, Count n, int64_t n_max, int32_t fanout, int64_t* indptr,
-                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, const ScanState& scan,
-                                 int32_t* err) {
+                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, ClearJob clear_a, ClearJob clear_b,
+                                 const ScanState& scan, int32_t* err) {
     CountArgs a{g.offsets, g.n_nodes, frontier, vars, frontier_out, n, fanout, indptr, flat_cap, n_flat_dev, size_out,
-                scan, err};
+                {clear_a, clear_b}, scan, err};
     int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
     if (tiles < 1) tiles = 1;                  // the first workgroup also writes the sizes of an empty hop
-    hipLaunchKernelGGL(frontier_count_kernel, dim3(static_cast<unsigned>(tiles)), dim3(kBlock), 0, stream, a);
+    // enough workgroups for the clearing (16 words a thread), all resident at once
+    const int64_t words = static_cast<int64_t>(clear_a.table ? clear_a.n_slots : 0) + (clear_b.table ? clear_b.n_slots : 0);
+    int64_t blocks = (words + kBlock * 16 - 1) / (kBlock * 16);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < tiles) blocks = tiles;
+    hipLaunchKernelGGL(frontier_count_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream, a);
     return hipGetLastError();
 }
 
 hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, const int64_t* indptr,
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
-                             const BatchVars* vars, int32_t* flat, int64_t flat_cap, unsigned long long* clear_table,
-                             uint32_t clear_slots) {
+                             const BatchVars* vars, int32_t* flat, int64_t flat_cap, ClearJob clear, InsertInto hop_table,
+                             InsertInto batch_table, int32_t* cat_out, int64_t n_seeds, const Count* prev_flat,
+                             int32_t* err) {
     HopArgs a{g.offsets, g.indices, g.n_nodes, frontier, indptr, n_frontier, fanout, hop, rng_seed, vars,
-              flat, flat_cap, clear_table, clear_table ? clear_slots : 0u};
+              flat, flat_cap, clear, hop_table, batch_table, cat_out, n_seeds, {}, err};
+    for (int h = 0; h < hop && h < HELIOS_KERNELS_MAX_SEG - 1; ++h) a.prev_flat[h] = prev_flat[h];
     const int lanes = group_lanes(fanout);
     const int64_t per_block = kBlock / lanes;
     int64_t blocks = (n_frontier_max + per_block - 1) / per_block;
