@@ -193,6 +193,30 @@ def test_whole_path_parity(h, helios, oracle, workloads, cfg):
     assert_same(gpu_path(h, helios, seeds, sp.fanouts, 99, fused=True), want)
 
 
+@pytest.mark.parametrize("fanouts", [[3], [65, 3], [200], [3, 3, 3], [0, 4], [4, 0], [16, 1, 17, 2]])
+def test_whole_path_random_graph(h, helios, oracle, fanouts):
+    """helios_prepare_batch on a graph with empty rows and hubs, with fan-outs on both sides of every
+    group width of the sampling kernel (the lanes that write a sample also feed the de-duplications)."""
+    print("whole path, fanouts", fanouts, flush=True)
+    rng = np.random.default_rng(100 + sum(fanouts))
+    n = 4000
+    off, idx = _random_graph(rng, n, 30, hub_deg=900)
+    feats = torch.from_numpy(rng.integers(0, 256, (n, 48), dtype=np.uint8))
+    order = torch.from_numpy(rng.permutation(n).astype(np.int32))
+    n_hbm, n_host = 700, 1100
+    h.csr_load(torch.from_numpy(off).cuda(), torch.from_numpy(idx).cuda())
+    cache = GpuCache(h, feats, order, n_hbm, n_host)  # noqa: F841
+    by_rank = feats.numpy()[order.numpy()]
+    rank = oracle.rank_build(order.numpy())
+    tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
+            np.ascontiguousarray(by_rank[n_hbm + n_host:])]
+    for n_seeds in (1, 300, 1500):                      # one tile, and a ragged second tile; repeated seeds
+        seeds = torch.from_numpy(rng.integers(0, n, n_seeds).astype(np.int32))
+        want = oracle_path(oracle, off, idx, seeds.numpy(), fanouts, 77, rank, n_hbm, n_host, *tabs, 48)
+        assert_same(gpu_path(h, helios, seeds, fanouts, 77, fused=True), want)
+        assert_same(gpu_path(h, helios, seeds, fanouts, 77, fused=False), want)
+
+
 # ------------------------------------------------------------------ error behaviour
 def test_errors(h, helios):
     HE = helios.HeliosError
