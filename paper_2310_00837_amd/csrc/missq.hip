@@ -376,7 +376,7 @@ int launch_submit(helios_ctx* c, helios_missq* m, const int32_t* miss_pos, const
                   int64_t n_max, uint32_t round, const BatchVars* vars) {
     SubmitArgs a{m->v, miss_pos, miss_slot, n, round, vars, c->err};
     int64_t blocks = (n_max + kBlock * kCommandsPerThread - 1) / (kBlock * kCommandsPerThread);
-    blocks = blocks < 1 ? 1 : blocks > 256 ? 256 : blocks;
+    blocks = blocks < 1 ? 1 : blocks > 16 ? 16 : blocks;     // every workgroup ends with a system-scope fence and a ticket: few of them
     hipLaunchKernelGGL(missq_submit_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, c->stream, a);
     HIP_TRY(c, hipGetLastError());
     return HELIOS_OK;

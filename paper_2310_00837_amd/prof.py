@@ -14,14 +14,18 @@ import sys
 
 
 def _short(name: str) -> str:
-    return name.replace("helios::(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+    return name.replace("helios::(anonymous namespace)::", "").replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+
+
+def _ours(name: str) -> bool:
+    return "helios" in name or "missq_" in name
 
 
 def trace(d: str, prefix: str) -> str:
     rows = list(csv.DictReader(open(os.path.join(d, f"{prefix}_kernel_trace.csv"))))
     agg = collections.OrderedDict()
     for r in rows:
-        if "helios" not in r["Kernel_Name"]:
+        if not _ours(r["Kernel_Name"]):
             continue
         key = (_short(r["Kernel_Name"]), int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1))
         dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
@@ -45,7 +49,7 @@ def pmc(d: str, prefix: str, counter: str) -> str:
         if r.get("Counter_Name") != counter:
             continue
         name = r["Kernel_Name"]
-        if "helios" not in name:
+        if not _ours(name):
             continue
         key = (_short(name), int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1))
         a = agg.setdefault(key, [0, 0.0])
