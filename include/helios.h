@@ -251,7 +251,7 @@ int helios_set_param(helios_ctx *ctx, int param, int64_t value);
 
 /* A recorded batch: the kernel sequence of helios_prepare_batch for one fixed
  * set of buffers, captured once into a HIP graph and replayed with one launch
- * per mini-batch (the per-batch path is a dozen short kernels, so the host's
+ * per mini-batch (the per-batch path is eight short kernels, so the host's
  * launch cost matters).  helios_plan_create takes the arguments of
  * helios_prepare_batch except seeds and rng_seed; all buffers, capacities,
  * n_seeds and fan-outs are fixed by it.  helios_plan_launch(plan, seeds,
