@@ -58,7 +58,8 @@ typedef enum {
 
 /* Context on `device`, working on `hip_stream` (a hipStream_t, borrowed;
  * NULL = the default stream).  helios_destroy waits for the stream and frees
- * the library's own memory only. */
+ * the library's own memory only; while plans or miss queues of the context
+ * are alive it returns HELIOS_ESTATE and destroys nothing. */
 int helios_create(helios_ctx **out, int device, void *hip_stream);
 int helios_destroy(helios_ctx *ctx);
 const char *helios_last_error(const helios_ctx *ctx);

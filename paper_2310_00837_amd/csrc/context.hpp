@@ -51,6 +51,7 @@ struct helios_ctx {
     bool has_cache = false;
     uint64_t cache_generation = 0;             // bumped by every helios_cache_build
 
+    int n_children = 0;                        // live plans and miss queues: they point back to the context
     helios_missq* missq = nullptr;             // attached miss queue: batches submit their misses by themselves
     int64_t missq_timeout_us = 2000000;        // how long the completion kernel waits without progress
     unsigned missq_waves = 0;                  // 0 = default

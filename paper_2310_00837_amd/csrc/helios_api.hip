@@ -296,6 +296,8 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
 
 int helios_destroy(helios_ctx* c) {
     if (!c) return HELIOS_EINVAL;
+    if (c->n_children > 0)
+        return fail(c, HELIOS_ESTATE, "%d plan(s) / miss queue(s) of this context are still alive; destroy them first", c->n_children);
     DeviceGuard guard(c->device);
     (void)hipStreamSynchronize(c->stream);
     if (c->aux) (void)hipStreamSynchronize(c->aux);
@@ -595,6 +597,7 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
     pl->slots = c->last_slots;
     pl->missq = c->missq;
     c->blocks_ready = false;                     // nothing has run yet
+    c->n_children += 1;
     *plan_out = pl;
     return HELIOS_OK;
 }
@@ -664,6 +667,7 @@ int helios_plan_destroy(helios_plan* pl) {
     if (pl->ctx) {
         DeviceGuard guard(pl->ctx->device);
         (void)hipStreamSynchronize(pl->ctx->stream);
+        pl->ctx->n_children -= 1;
     }
     if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
     if (pl->graph) (void)hipGraphDestroy(pl->graph);

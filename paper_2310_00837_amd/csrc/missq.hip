@@ -463,6 +463,7 @@ int helios_missq_create(helios_ctx* c, int32_t n_queues, int32_t queue_depth, in
     }
     if (n_service_threads > 0 && standin_rows > 0) touch_pages(m->standin, static_cast<size_t>(standin_rows) * c->row_bytes);
     for (int t = 0; t < n_service_threads; ++t) m->threads.emplace_back(service_thread, m, t);
+    c->n_children += 1;
     *out = m;
     return HELIOS_OK;
 }
@@ -473,6 +474,7 @@ int helios_missq_destroy(helios_missq* m) {
     DeviceGuard guard(c->device);
     (void)hipStreamSynchronize(c->stream);
     if (c->missq == m) c->missq = nullptr;
+    c->n_children -= 1;
     stop_threads(m);
     free_buffers(m);
     delete m;

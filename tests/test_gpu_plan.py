@@ -86,6 +86,8 @@ def test_recorded_batch_replays(helios, oracle, cfg):
     want = oracle_path(oracle, off, idx, W.seed_batch(sp, g, 9).numpy(), sp.fanouts, W.batch_rng_seed(SEED, 9), rank,
                        n_hbm, n_host, *tabs, sp.row_bytes)
     assert np.array_equal(unique[:int(nu[0])].cpu().numpy(), want["unique"]) and stats.tolist() == want["stats"].tolist()
+    # a context with a live plan is not destroyed
+    assert helios._lib.helios_destroy(h._h) == helios.ESTATE
     # growing the scratch invalidates the plan
     h.reserve(4 * cap)
     with pytest.raises(helios.HeliosError) as e:
