@@ -46,7 +46,7 @@ def measure_host_link(torch, gib: float = 1.0) -> float:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="workload index in BASELINE.json configs (0-based)")
     ap.add_argument("--hbm-frac", type=float, default=None, help="config 4 only: HBM-tier fraction of the sweep")
