@@ -24,7 +24,7 @@
 // frontier, and, in the whole-path call, into the batch's ID list), so the lane
 // that writes a sample also inserts it into the hash tables of those
 // de-duplications: they then start at their second pass, and a mini-batch has
-// two kernel launches fewer per hop.  The tables must be empty before the first
+// one kernel launch fewer per hop.  The tables must be empty before the first
 // insert: each kernel here clears, on the way, the tables that the kernels
 // after it fill.
 #include "kernels.hpp"
