@@ -113,7 +113,7 @@ def test_two_batches_queued_per_context(helios, oracle):
     by_rank = to_bytes(feats)[order]
     tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
             np.ascontiguousarray(by_rank[n_hbm + n_host:])]
-    n_jobs = 20
+    n_jobs = 48
     jobs = [(W.seed_batch(sp, g, b).cuda(), W.batch_rng_seed(SEED, b)) for b in range(n_jobs)]
     got = lanes_in_flight(helios, off_d, idx_d, cache.order, n_hbm, n_host, sp.row_bytes,
                           (cache.hbm, cache.host, cache.standin), sp.batch, sp.fanouts, jobs, per_lane=2)
