@@ -83,7 +83,7 @@ def gpu_path(h, helios, seeds: torch.Tensor, fanouts, rng_seed: int, fused: bool
 
 
 def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, tabs_dev, batch, fanouts, jobs,
-                    n_lanes: int = 3, recorded: bool = True, per_lane: int = 1):
+                    n_lanes: int = 3, recorded: bool = True, per_lane: int = 1, tune=None):
     """bench.py's launch configuration: n_lanes contexts, each on its own stream with (recorded=True) a
     recorded batch per buffer set, sharing the graph and the cache tables.  per_lane == 1: a lane is
     synchronised before it gets its next batch, and the miss list is served (result key "out").
@@ -99,6 +99,8 @@ def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, t
         ctx.csr_load(offsets, indices)
         ctx.cache_build(order, n_hbm, n_host, row_bytes, *tabs_dev)
         ctx.sync()
+        if tune is not None:
+            tune(ctx)                             # launch parameters, set before anything is recorded
         lanes.append(ctx)
     for w in range(per_lane):
         for ctx in lanes:

@@ -125,6 +125,43 @@ def test_two_batches_queued_per_context(helios, oracle):
     first.close()
 
 
+@pytest.mark.parametrize("params", [dict(serial=0), dict(serial=0, hbm_blocks=7, host_blocks=3), dict(serial=1, hbm_blocks=8192, host_blocks=1)])
+def test_launch_parameters_do_not_change_results(helios, oracle, params):
+    """The tuning parameters (tier copies side by side on two streams, grid sizes of the row copies) only
+    change launch shapes: directly launched and recorded batches still match the oracle."""
+    sp = W.spec(0)
+    g = W.make_graph(sp, SEED, "cpu")
+    feats = W.feature_rows(SEED, torch.arange(g.n_nodes), sp.dim, sp.dtype)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    first = helios.Helios(0)
+    off_d, idx_d = g.offsets.cuda(), g.indices.cuda()
+    first.csr_load(off_d, idx_d)
+    cache = GpuCache(first, feats, g.order, n_hbm, n_host)
+    order = g.order.numpy()
+    rank = oracle.rank_build(order)
+    by_rank = to_bytes(feats)[order]
+    tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
+            np.ascontiguousarray(by_rank[n_hbm + n_host:])]
+
+    def tune(ctx):
+        ctx.set_param(helios.PARAM_SERIAL_TIERS, params["serial"])
+        ctx.set_param(helios.PARAM_HBM_GATHER_BLOCKS, params.get("hbm_blocks", 0))
+        ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, params.get("host_blocks", 0))
+
+    jobs = [(W.seed_batch(sp, g, b).cuda(), W.batch_rng_seed(SEED, b)) for b in range(6)]
+    wants = [oracle_path(oracle, g.offsets.numpy(), g.indices.numpy(), sd.cpu().numpy(), sp.fanouts, rs, rank, n_hbm, n_host,
+                         *tabs, sp.row_bytes) for sd, rs in jobs]
+    for recorded in (False, True):
+        got = lanes_in_flight(helios, off_d, idx_d, cache.order, n_hbm, n_host, sp.row_bytes,
+                              (cache.hbm, cache.host, cache.standin), sp.batch, sp.fanouts, jobs, n_lanes=2,
+                              recorded=recorded, tune=tune)
+        for res, want in zip(got, wants):
+            want = dict(want)
+            del want["out_before_miss"]
+            assert_same(res, want)
+    first.close()
+
+
 def test_plan_needs_a_real_stream(helios):
     h = helios.Helios(0)                                  # torch's default stream is the NULL stream
     off = torch.tensor([0, 1, 2], dtype=torch.int64, device="cuda")
