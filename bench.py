@@ -43,6 +43,68 @@ def measure_host_link(torch, gib: float = 1.0) -> float:
     return best
 
 
+def probe_launch_delay(torch, helios, dev, args) -> int:
+    """What a kernel launch costs while the host link is saturated: stream B runs a chain of `chain` one-workgroup
+    copies (64 B each) with and without a long row copy from pinned host memory running on stream A (512 B rows,
+    --host-blocks workgroups, library default if 0).  The difference is what every launch of a mini-batch's
+    front pays while another mini-batch's host-tier copy is running."""
+    rb, table_rows, n_rows, chain = 512, 600_000, 1 << 19, 200
+    table = helios.pinned_empty((table_rows, rb), torch.uint8)
+    table.tensor.fill_(1)
+    out = torch.empty((n_rows, rb), dtype=torch.uint8, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    slot = torch.randint(0, table_rows, (n_rows,), device=dev, dtype=torch.int32, generator=gen)
+    pos = torch.arange(n_rows, device=dev, dtype=torch.int32)
+    small_src = torch.zeros(64, dtype=torch.uint8, device=dev)
+    small_dst = torch.zeros(64, dtype=torch.uint8, device=dev)
+    sa, sb = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    a, b = helios.Helios(0, stream=sa), helios.Helios(0, stream=sb)
+    n1 = torch.tensor([0, 1], dtype=torch.int64, device=dev)
+    order = torch.tensor([0], dtype=torch.int32, device=dev)
+    for ctx in (a, b):                       # a one-node graph whose only row lives in the stand-in: the long copy is S6
+        ctx.csr_load(n1, order)
+    a.cache_build(order, 0, 0, rb, None, None, table.tensor)
+    if args.host_blocks:
+        a.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
+    a.sync()
+    res = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(sa)
+    a._check(helios._lib.helios_gather_miss(a._h, pos.data_ptr(), slot.data_ptr(), n_rows, None, out.data_ptr()))
+    e1.record(sa)
+    e1.synchronize()
+    res["link_copy_alone_GBs"] = n_rows * rb / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    # the chain as one recorded graph, so that the host's launch rate does not hide what the GPU does
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=sb):
+        for _ in range(chain):
+            b.calibration_copy(small_src, small_dst)
+    torch.cuda.synchronize()
+    for with_link in (0, 1):
+        best = 1e30
+        for _ in range(5):
+            torch.cuda.synchronize()
+            if with_link:
+                a._check(helios._lib.helios_gather_miss(a._h, pos.data_ptr(), slot.data_ptr(), n_rows, None, out.data_ptr()))
+            t0 = time.perf_counter()
+            with torch.cuda.stream(sb):
+                graph.replay()
+            sb.synchronize()
+            best = min(best, (time.perf_counter() - t0) / chain * 1e6)
+            torch.cuda.synchronize()
+        res["us_per_launch_link_busy" if with_link else "us_per_launch_link_idle"] = best
+    res["chain"] = chain
+    res["what"] = ("a recorded chain of one-workgroup kernels on one stream; the other stream copies 2^19 rows of 512 B "
+                   "from pinned host memory")
+    a.close()
+    b.close()
+    table.free()
+    print(json.dumps(res))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,6 +128,12 @@ def main() -> int:
     ap.add_argument("--missq-threads", type=int, default=4, help="service threads per miss queue (one queue per lane)")
     ap.add_argument("--large-list-gb", type=float, default=20.0,
                     help="table size of the bandwidth-bound run of the HBM-tier copy (1 M random rows; 0 skips it)")
+    ap.add_argument("--serial-tiers", type=int, default=1,
+                    help="1: the host-tier copy follows the HBM-tier copy on the lane's stream (library default); "
+                         "0: the two run side by side on two streams")
+    ap.add_argument("--probe-launch-delay", action="store_true",
+                    help="instead of the benchmark: time a chain of small kernels on one stream while another "
+                         "stream's row copy saturates the host link, and print that as one JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
                     help="skip the host-link probe and use this rate (for runs under a counter profiler)")
@@ -84,6 +152,8 @@ def main() -> int:
         return 2
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
+    if args.probe_launch_delay:
+        return probe_launch_delay(torch, helios, dev, args)
     sp = W.spec(args.config, args.hbm_frac)
     K, Wm = args.steps, args.warmup
 
@@ -219,6 +289,8 @@ def main() -> int:
             ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
         if args.hbm_blocks:
             ctx.set_param(helios.PARAM_HBM_GATHER_BLOCKS, args.hbm_blocks)
+        if not args.serial_tiers:
+            ctx.set_param(helios.PARAM_SERIAL_TIERS, 0)
         lanes.append(Lane(ctx, st))
     torch.cuda.synchronize()
     if args.graph:

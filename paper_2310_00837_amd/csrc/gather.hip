@@ -173,7 +173,9 @@ unsigned launch_shape(hipStream_t stream, const GatherArgs& a, int64_t n_max, un
 }  // namespace
 
 hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* dst, int64_t bytes) {
-    hipLaunchKernelGGL(calibration_copy_kernel, dim3(kGatherMaxBlocks), dim3(kBlock), 0, stream,
+    int64_t blocks = (bytes / 16 + kBlock - 1) / kBlock;
+    blocks = blocks < 1 ? 1 : blocks > kGatherMaxBlocks ? kGatherMaxBlocks : blocks;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream,
                        static_cast<const chunk16*>(src), static_cast<chunk16*>(dst), bytes / 16);
     return hipGetLastError();
 }
