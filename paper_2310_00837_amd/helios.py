@@ -6,8 +6,10 @@ importing this module raises.
 """
 from __future__ import annotations
 
+import atexit
 import ctypes as C
 import os
+import weakref
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -256,6 +258,20 @@ class MissQueue:
             pass
 
 
+_live_contexts = weakref.WeakSet()
+
+
+@atexit.register
+def _close_all() -> None:
+    """Miss queues own host threads: stop them (and free every context) before the interpreter and the
+    HIP runtime shut down."""
+    for ctx in list(_live_contexts):
+        try:
+            ctx.close()
+        except Exception:
+            pass
+
+
 class Helios:
     """One library context on one device and stream."""
 
@@ -271,6 +287,7 @@ class Helios:
             raise HeliosError(rc, "helios_create failed")
         self.device = torch.device("cuda", device)
         self.row_bytes = 0
+        _live_contexts.add(self)
 
     def close(self) -> None:
         if getattr(self, "_h", None) is not None and self._h.value:
