@@ -37,6 +37,17 @@ struct BatchVars {
     uint32_t io_round;       // round number of the miss queue the batch submits to (0 if none)
 };
 
+// How a recorded batch gets its BatchVars without a copy being part of the recording: the host writes
+// them to the next slot of a ring in pinned memory before every launch; the batch's first kernel reads
+// the slot that the number of recorded batches run so far on the context selects (a device counter,
+// advanced by the batch's second kernel) and leaves a copy in device memory for the kernels after it.
+struct BatchFeed {
+    const BatchVars* ring;        // pinned host memory, nullable (a directly launched batch)
+    uint32_t ring_slots;
+    const uint32_t* batches_run;  // device
+    BatchVars* vars_out;          // device
+};
+
 // First error wins is not needed: any recorded error makes the call fail.
 // err points to pinned, GPU-mapped host memory (int32[2]: code, detail).
 __device__ __forceinline__ void raise(int32_t* err, int code) {

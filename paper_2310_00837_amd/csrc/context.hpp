@@ -75,6 +75,7 @@ struct helios_ctx {
     // of pinned slots; while recording, scans get epoch offsets 1, 2, ... instead of fresh epochs
     helios::BatchVars* vars = nullptr;                 // device
     helios::BatchVars* vars_ring = nullptr;            // pinned [kVarsRing]
+    uint32_t* batches_run = nullptr;           // device: recorded batches run so far (selects the ring slot)
     uint32_t vars_next = 0, vars_unsynced = 0;
     uint64_t launch_seq = 0;                   // recorded batches launched so far
     bool recording = false;

@@ -152,6 +152,8 @@ int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int3
                 uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p,
                 int64_t batch_dedup_max) {
     const BatchVars* vars = c->recording ? c->vars : nullptr;
+    const BatchFeed feed = c->recording ? BatchFeed{c->vars_ring, kVarsRing, c->batches_run, c->vars}
+                                        : BatchFeed{nullptr, 0, nullptr, nullptr};
     const InsertInto batch_table = batch_dedup_max > 0 ? InsertInto{c->dd.table, dedup_slots(c, batch_dedup_max), c->dd.slot_of}
                                                        : InsertInto{nullptr, 0, nullptr};
     auto hop_table = [&](int h) {               // hops alternate between two tables
@@ -165,7 +167,7 @@ int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int3
         ScanState scan;
         int rc = next_scan(c, &scan);
         if (rc) return rc;
-        HIP_TRY(c, launch_frontier_count(c->stream, c->g, seeds, vars, hops[0].frontier, nf, n_seeds, fanouts[0],
+        HIP_TRY(c, launch_frontier_count(c->stream, c->g, seeds, feed, hops[0].frontier, nf, n_seeds, fanouts[0],
                                          hops[0].indptr, hops[0].flat_cap, c->cnt + kCntFlat + 0, sizes,
                                          clear_of(hop_table(0)), clear_of(batch_table), scan, c->err));
     }
@@ -174,7 +176,7 @@ int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int3
         const InsertInto mine = hop_table(h);
         HIP_TRY(c, launch_sample_hop(c->stream, c->g, hops[h].frontier, hops[h].indptr, nf, p.frontier_max[h], fanouts[h],
                                      h, rng_seed, vars, hops[h].flat, p.flat_max[h], clear_of(hop_table(h + 1)), mine,
-                                     batch_table, c->cat, n_seeds, prev_flat, c->err));
+                                     batch_table, c->cat, n_seeds, prev_flat, c->recording ? c->batches_run : nullptr, c->err));
         prev_flat[h] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
         if (!last) {
             NextHopCount next{c->g.offsets, c->g.n_nodes, fanouts[h + 1], hops[h + 1].indptr, hops[h + 1].flat_cap,
@@ -274,7 +276,9 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
               hipMalloc(&c->vars, sizeof(BatchVars)) == hipSuccess &&
               hipMalloc(&c->scan_ticket, 64) == hipSuccess &&
-              hipHostMalloc(reinterpret_cast<void**>(&c->vars_ring), sizeof(BatchVars) * kVarsRing, hipHostMallocDefault) == hipSuccess &&
+              hipMalloc(&c->batches_run, 64) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&c->vars_ring), sizeof(BatchVars) * kVarsRing,
+                            hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
@@ -284,6 +288,7 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
         c->err[0] = c->err[1] = 0;
         ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
              hipMemsetAsync(c->scan_ticket, 0, 64, c->stream) == hipSuccess &&
+             hipMemsetAsync(c->batches_run, 0, 64, c->stream) == hipSuccess &&
              hipStreamSynchronize(c->stream) == hipSuccess;
     }
     if (!ok) {
@@ -306,6 +311,7 @@ int helios_destroy(helios_ctx* c) {
     (void)hipFree(c->cnt);
     (void)hipFree(c->vars);
     (void)hipFree(c->scan_ticket);
+    (void)hipFree(c->batches_run);
     if (c->vars_ring) (void)hipHostFree(c->vars_ring);
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
@@ -632,7 +638,7 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     slot->epoch_base = c->epoch;
     slot->io_round = io_round;
     c->epoch += pl->n_scans;
-    HIP_TRY(c, hipMemcpyAsync(c->vars, slot, sizeof(BatchVars), hipMemcpyHostToDevice, c->stream));
+    __atomic_thread_fence(__ATOMIC_RELEASE);     // the slot is written before the launch is rung in
     HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
     HIP_TRY(c, hipEventRecord(pl->done, c->stream));
     c->launch_seq += 1;

@@ -17,10 +17,10 @@ struct CsrView {
 // ---- sample.hip
 // Count pass of hop 0: indptr[i] = start of frontier[i]'s samples in flat, indptr[n] = total
 // (also to *n_flat_dev); size_out (nullable, device-accessible) gets {n, total}.  frontier_out
-// (nullable, may equal frontier) receives a copy of the frontier; vars (nullable): the frontier
-// is vars->seeds.  The later hops get their indptr from launch_dedup_compact.  clear_a / clear_b: tables
+// (nullable, may equal frontier) receives a copy of the frontier; feed.ring (nullable): a recorded
+// batch, whose variables this kernel takes from the host's ring (the frontier is their seeds).  The later hops get their indptr from launch_dedup_compact.  clear_a / clear_b: tables
 // set to all ones on the way (those the sampling pass of hop 0 inserts into).
-hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchVars* vars,
+hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchFeed& feed,
                                  int32_t* frontier_out, Count n, int64_t n_max, int32_t fanout, int64_t* indptr,
                                  int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, ClearJob clear_a, ClearJob clear_b,
                                  const ScanState& scan, int32_t* err);
@@ -33,7 +33,7 @@ hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
                              const BatchVars* vars, int32_t* flat, int64_t flat_cap, ClearJob clear, InsertInto hop_table,
                              InsertInto batch_table, int32_t* cat_out, int64_t n_seeds, const Count* prev_flat,
-                             int32_t* err);
+                             uint32_t* batches_run /* nullable: hop 0 of a recorded batch advances it */, int32_t* err);
 
 // ---- dedup.hip
 struct DedupScratch {

@@ -40,7 +40,7 @@ struct CountArgs {
     const int64_t* offsets;
     int64_t n_nodes;
     const int32_t* frontier;
-    const BatchVars* vars;        // nullable: the frontier is vars->seeds (recorded batch)
+    BatchFeed feed;               // recorded batch: the batch's variables come from the host's ring, and the frontier is their seeds
     int32_t* frontier_out;        // nullable: receives a copy of the frontier
     Count n;
     int32_t fanout;
@@ -57,8 +57,19 @@ __global__ __launch_bounds__(kBlock) void frontier_count_kernel(CountArgs a) {
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
     __shared__ uint32_t s_ticket, s_agg[1], s_excl[1];
     __shared__ ScanLookbackLds<1> s_look;
+    // A recorded batch starts here: every workgroup reads the batch's variables from the slot of the host's
+    // ring that the count of batches run so far selects (the read travels while the tables are cleared), and
+    // the first workgroup leaves them in device memory for the kernels that follow.
+    BatchVars bv{};
+    if (a.feed.ring) bv = a.feed.ring[*a.feed.batches_run % a.feed.ring_slots];
     clear_slots(a.clear[0]);                     // side job of the whole grid
     clear_slots(a.clear[1]);
+    ScanState scan = a.scan;
+    if (a.feed.ring) {
+        scan.vars = nullptr;
+        scan.epoch += bv.epoch_base;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *a.feed.vars_out = bv;
+    }
     const int64_t n = a.n.get();
     const int64_t n_tiles = (n + kTileItems - 1) / kTileItems;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -70,8 +81,8 @@ __global__ __launch_bounds__(kBlock) void frontier_count_kernel(CountArgs a) {
         }
     }
     if (static_cast<int64_t>(blockIdx.x) >= n_tiles) return;
-    const uint32_t tile = scan_take_ticket(a.scan, static_cast<uint32_t>(n_tiles), &s_ticket);
-    const int32_t* frontier = a.vars ? a.vars->seeds : a.frontier;
+    const uint32_t tile = scan_take_ticket(scan, static_cast<uint32_t>(n_tiles), &s_ticket);
+    const int32_t* frontier = a.feed.ring ? bv.seeds : a.frontier;
     const int64_t j0 = static_cast<int64_t>(tile) * kTileItems + static_cast<int64_t>(threadIdx.x) * kItemsPerThread;
     int32_t v[kItemsPerThread];
     uint32_t cnt[kItemsPerThread];
@@ -90,7 +101,7 @@ __global__ __launch_bounds__(kBlock) void frontier_count_kernel(CountArgs a) {
     uint32_t tile_total;
     const uint32_t local = block_exclusive_scan(sum, s_wave, tile_total);
     if (threadIdx.x == 0) s_agg[0] = tile_total;
-    scan_chained_prefix<1>(a.scan, tile, s_agg, s_excl, &s_look, a.err);
+    scan_chained_prefix<1>(scan, tile, s_agg, s_excl, &s_look, a.err);
     int64_t at = static_cast<int64_t>(s_excl[0]) + local;
 #pragma unroll
     for (int k = 0; k < kItemsPerThread; ++k) {
@@ -125,6 +136,7 @@ struct HopArgs {
     int32_t* cat_out;             // with batch_table: receives [seeds | flat_0 | ...]
     int64_t n_seeds;
     Count prev_flat[HELIOS_KERNELS_MAX_SEG - 1];   // sizes of flat_0 .. flat_{hop-1}
+    uint32_t* batches_run;        // nullable: hop 0 of a recorded batch counts the batch (see frontier_count_kernel)
     int32_t* err;
 };
 
@@ -152,6 +164,8 @@ __global__ __launch_bounds__(kBlock) void sample_hop_kernel(HopArgs a) {
     __shared__ int32_t s_chosen[(G == kWave) ? kWavesPerBlock * kMaxFanout : 1];
 
     clear_slots(a.clear);                        // side job of the whole grid
+    // the count pass has taken this batch's slot of the ring: the next batch takes the next one
+    if (a.batches_run && blockIdx.x == 0 && threadIdx.x == 0) *a.batches_run += 1;
 
     const int group = threadIdx.x / G;
     const int l = threadIdx.x % G;
@@ -258,11 +272,11 @@ int group_lanes(int32_t fanout) { return fanout <= 8 ? 8 : fanout <= 16 ? 16 : f
 
 }  // namespace
 
-hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchVars* vars,
+hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchFeed& feed,
                                  int32_t* frontier_out, Count n, int64_t n_max, int32_t fanout, int64_t* indptr,
                                  int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, ClearJob clear_a, ClearJob clear_b,
                                  const ScanState& scan, int32_t* err) {
-    CountArgs a{g.offsets, g.n_nodes, frontier, vars, frontier_out, n, fanout, indptr, flat_cap, n_flat_dev, size_out,
+    CountArgs a{g.offsets, g.n_nodes, frontier, feed, frontier_out, n, fanout, indptr, flat_cap, n_flat_dev, size_out,
                 {clear_a, clear_b}, scan, err};
     int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
     if (tiles < 1) tiles = 1;                  // the first workgroup also writes the sizes of an empty hop
@@ -279,9 +293,9 @@ hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t
                              Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
                              const BatchVars* vars, int32_t* flat, int64_t flat_cap, ClearJob clear, InsertInto hop_table,
                              InsertInto batch_table, int32_t* cat_out, int64_t n_seeds, const Count* prev_flat,
-                             int32_t* err) {
+                             uint32_t* batches_run, int32_t* err) {
     HopArgs a{g.offsets, g.indices, g.n_nodes, frontier, indptr, n_frontier, fanout, hop, rng_seed, vars,
-              flat, flat_cap, clear, hop_table, batch_table, cat_out, n_seeds, {}, err};
+              flat, flat_cap, clear, hop_table, batch_table, cat_out, n_seeds, {}, hop == 0 ? batches_run : nullptr, err};
     for (int h = 0; h < hop && h < HELIOS_KERNELS_MAX_SEG - 1; ++h) a.prev_flat[h] = prev_flat[h];
     const int lanes = group_lanes(fanout);
     const int64_t per_block = kBlock / lanes;
