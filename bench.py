@@ -165,7 +165,13 @@ def main() -> int:
     offsets, indices, order = g.offsets.to(dev), g.indices.to(dev), g.order.to(dev)
     g.offsets, g.indices, g.order, g.perm_seed = offsets, indices, order, g.perm_seed.to(dev)
     t1 = time.time()
-    tiers = W.make_tiers(sp, g, dev, progress=log if sp.n_nodes > 5_000_000 else None)
+    pinned_bufs = []
+
+    def pinned_exact(shape, dtype):          # torch's pinned allocator rounds 28 GB up to 32 GB and keeps it; this one does not
+        pinned_bufs.append(helios.pinned_empty(shape, dtype))
+        return pinned_bufs[-1].tensor
+
+    tiers = W.make_tiers(sp, g, dev, progress=log if sp.n_nodes > 5_000_000 else None, pinned_empty=pinned_exact)
     log(f"tiers: hbm {tiers.n_hbm} host {tiers.n_host} stand-in {tiers.n_rest} rows x {sp.row_bytes} B "
         f"filled in {time.time() - t1:.1f}s")
     link_gbs = args.link_gbs if args.link_gbs else measure_host_link(torch)

@@ -282,6 +282,7 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
+    ok = ok && c->err && c->cnt && c->vars && c->scan_ticket && c->batches_run && c->vars_ring && c->clock && c->clock_host;
     if (ok) {
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;
