@@ -134,6 +134,9 @@ def main() -> int:
     ap.add_argument("--probe-launch-delay", action="store_true",
                     help="instead of the benchmark: time a chain of small kernels on one stream while another "
                          "stream's row copy saturates the host link, and print that as one JSON line")
+    ap.add_argument("--presample-batches", type=int, default=0,
+                    help="0: tiers in the in-degree order BASELINE.json names; N > 0: in the order of hotness counted over "
+                         "N pre-sampling batches (the paper's policy); -1: over one epoch of the train split")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
                     help="skip the host-link probe and use this rate (for runs under a counter profiler)")
@@ -164,6 +167,36 @@ def main() -> int:
     log(f"{sp.name}: N={g.n_nodes} E={g.n_edges} generated on {gen_dev} in {time.time() - t0:.1f}s")
     offsets, indices, order = g.offsets.to(dev), g.indices.to(dev), g.order.to(dev)
     g.offsets, g.indices, g.order, g.perm_seed = offsets, indices, order, g.perm_seed.to(dev)
+    cache_order = "in-degree, ties by ID (BASELINE.json)"
+    if args.presample_batches:
+        # Sec. 3.2.2 "Cache Initialization": an epoch of pre-sampling on the GPU counts every vertex's hotness, the
+        # GPU sorts the vertices by it, the hottest fill the GPU tier and the next the CPU tier
+        Bp = min(sp.batch, g.n_nodes)
+        per_epoch = -(-max(Bp, int(sp.train_frac * g.n_nodes)) // Bp)
+        nb = per_epoch if args.presample_batches < 0 else args.presample_batches
+        hp = helios.Helios(0)
+        hp.csr_load(offsets, indices)
+        hops_p = helios.alloc_hops(Bp, sp.fanouts, dev)
+        cap_p = Bp + sum(hb.flat.numel() for hb in hops_p)
+        uniq_p = torch.empty(cap_p, dtype=torch.int32, device=dev)
+        sizes_p = torch.zeros(2 * len(sp.fanouts), dtype=torch.int64).pin_memory()
+        nu_p = torch.zeros(1, dtype=torch.int64).pin_memory()
+        counts = torch.zeros(g.n_nodes, dtype=torch.int32, device=dev)
+        for b in range(nb):
+            sd = W.seed_batch(sp, g, b, epoch=1).to(dev)         # another shuffle of the train split than the timed batches
+            hp.sample(sd, sp.fanouts, W.batch_rng_seed(args.seed + 1, b), hops_p, sizes_p)
+            hp.sync()
+            cat = torch.cat([sd] + [hops_p[k].flat[:int(sizes_p[2 * k + 1])] for k in range(len(sp.fanouts))])
+            hp.dedup(cat, uniq_p, None, nu_p)
+            hp.hotness_add(uniq_p, uniq_p.numel(), nu_p, counts)
+        order = torch.empty(g.n_nodes, dtype=torch.int32, device=dev)
+        hp.hotness_order(counts, order)
+        hp.sync()
+        hp.close()
+        g.order = order
+        cache_order = f"pre-sampling hotness over {nb} batches (helios_hotness_add / helios_hotness_order)"
+        log(f"cache order: {cache_order}; {int((counts > 0).sum())} nodes seen")
+        del counts, uniq_p, hops_p
     t1 = time.time()
     pinned_bufs = []
 
@@ -471,7 +504,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"BASELINE.json configs[{args.config}] {sp.name}", "n_nodes": g.n_nodes,
                    "n_edges": g.n_edges, "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
-                   "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed,
+                   "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed, "cache_order": cache_order,
                    "step": ("helios_plan_launch (recorded helios_prepare_batch" if args.graph else "helios_prepare_batch (") +
                            ": sample, dedup, lookup, HBM+host gather, miss list) + helios_sync, "
                            "%d contexts on %d streams, %d mini-batches queued on each" % (D, D, P)},
