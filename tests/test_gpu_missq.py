@@ -48,6 +48,7 @@ def test_missq_rounds_match_the_oracle(h, helios, oracle, row_bytes, shape):
     rank = oracle.rank_build(order.numpy())
     q = helios.MissQueue(h, n_queues, depth, threads)
     h.set_param(helios.PARAM_MISSQ_TIMEOUT_US, 20_000_000)
+    rounds = misses = 0
     for n_ids in (4000, 0, 1, 333, 4000):                       # the queues are reused round after round
         ids = rng.integers(0, n, n_ids).astype(np.int32)
         if n_ids == 1:
@@ -69,6 +70,9 @@ def test_missq_rounds_match_the_oracle(h, helios, oracle, row_bytes, shape):
         assert np.array_equal(out[:n_ids].cpu().numpy(), wout)
         assert np.array_equal(wout, feats.numpy()[ids])
         assert not q.faulted()
+        rounds, misses = rounds + 1, misses + int(wstats[3])
+    opened, served, commands = q.counters()
+    assert opened == rounds and commands == misses and served in (rounds - 1, rounds)   # the last round may still be closing
     q.destroy()
 
 
