@@ -278,6 +278,36 @@ def test_errors(h, helios):
     assert m.cpu().tolist() == [0, 1]
 
 
+def test_graph_with_a_neighbour_that_is_no_node(h, helios):
+    """An entry of `indices` outside [0, n): the lane that samples it reports it when it feeds the
+    de-duplications (HELIOS_EDATA at the next sync); nothing is indexed with it, and the context works on."""
+    off = torch.tensor([0, 2, 3, 3], dtype=torch.int64, device="cuda")
+    idx = torch.tensor([1, 9, 0], dtype=torch.int32, device="cuda")
+    h.csr_load(off, idx)
+    seeds = torch.tensor([0], dtype=torch.int32, device="cuda")
+    hops = helios.alloc_hops(1, [2, 2], h.device)
+    sizes = torch.zeros(4, dtype=torch.int64).pin_memory()
+    h.sample(seeds, [2, 2], 5, hops, sizes)
+    with pytest.raises(helios.HeliosError) as e:
+        h.sync()
+    assert e.value.code == helios.EDATA
+    assert sizes.tolist() == [1, 2, 1, 1]                       # frontier_1 = [1]: the bad value is no frontier node
+    assert hops[1].frontier[:1].cpu().tolist() == [1] and hops[1].flat[:1].cpu().tolist() == [0]
+    # whole path: same report
+    h.cache_build(torch.tensor([2, 0, 1], dtype=torch.int32, device="cuda"), 1, 1, 16,
+                  torch.zeros(16, dtype=torch.uint8, device="cuda"), torch.zeros(16, dtype=torch.uint8).pin_memory(),
+                  torch.zeros(16, dtype=torch.uint8).pin_memory())
+    h.sync()
+    with pytest.raises(helios.HeliosError) as e:
+        gpu_path(h, helios, seeds.cpu(), [2, 2], 5, fused=True)
+    assert e.value.code == helios.EDATA
+    # a sound graph afterwards
+    h.csr_load(off, torch.tensor([1, 2, 0], dtype=torch.int32, device="cuda"))
+    h.sample(seeds, [2, 2], 5, hops, sizes)
+    h.sync()
+    assert sizes.tolist() == [1, 2, 2, 1]
+
+
 # ------------------------------------------------------------------ limits and capacities
 def test_maximum_fanout_and_hops(h, helios, oracle):
     rng = np.random.default_rng(11)
