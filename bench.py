@@ -506,7 +506,7 @@ def main() -> int:
                    "n_edges": g.n_edges, "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
                    "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed, "cache_order": cache_order,
                    "step": ("helios_plan_launch (recorded helios_prepare_batch" if args.graph else "helios_prepare_batch (") +
-                           ": sample, dedup, lookup, HBM+host gather, miss list) + helios_sync, "
+                           ": sample, dedup, lookup, HBM+host gather, miss list) + one wait per batch (helios_plan_wait / helios_sync), "
                            "%d contexts on %d streams, %d mini-batches queued on each" % (D, D, P)},
         "roofline": {"kernel": "gather_rows_kernel (HBM tier)", "bound": "hbm", "achieved": hbm_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": traffic,
