@@ -632,15 +632,17 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
         c->vars_unsynced = 0;
     }
     BatchVars* slot = c->vars_ring + (c->vars_next % kVarsRing);
-    c->vars_next += 1;
-    c->vars_unsynced += 1;
     slot->rng_seed = rng_seed;
     slot->seeds = seeds;
     slot->epoch_base = c->epoch;
     slot->io_round = io_round;
-    c->epoch += pl->n_scans;
     __atomic_thread_fence(__ATOMIC_RELEASE);     // the slot is written before the launch is rung in
     HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
+    // only a batch that was launched takes its slot: the device counts the batches it runs, and the two
+    // counts select the slot
+    c->vars_next += 1;
+    c->vars_unsynced += 1;
+    c->epoch += pl->n_scans;
     HIP_TRY(c, hipEventRecord(pl->done, c->stream));
     c->launch_seq += 1;
     pl->launch_seq = c->launch_seq;
