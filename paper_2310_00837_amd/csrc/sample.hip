@@ -57,11 +57,12 @@ __global__ __launch_bounds__(kBlock) void frontier_count_kernel(CountArgs a) {
     __shared__ uint32_t s_wave[kWavesPerBlock + 1];
     __shared__ uint32_t s_ticket, s_agg[1], s_excl[1];
     __shared__ ScanLookbackLds<1> s_look;
-    // A recorded batch starts here: every workgroup reads the batch's variables from the slot of the host's
+    // A recorded batch starts here: every workgroup that counts reads the batch's variables from the slot of the host's
     // ring that the count of batches run so far selects (the read travels while the tables are cleared), and
     // the first workgroup leaves them in device memory for the kernels that follow.
     BatchVars bv{};
-    if (a.feed.ring) bv = a.feed.ring[*a.feed.batches_run % a.feed.ring_slots];
+    const bool counts = static_cast<int64_t>(blockIdx.x) * kTileItems < a.n.host || blockIdx.x == 0;   // else: clears only
+    if (a.feed.ring && counts) bv = a.feed.ring[*a.feed.batches_run % a.feed.ring_slots];
     clear_slots(a.clear[0]);                     // side job of the whole grid
     clear_slots(a.clear[1]);
     ScanState scan = a.scan;
