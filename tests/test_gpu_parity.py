@@ -210,7 +210,7 @@ def test_whole_path_random_graph(h, helios, oracle, fanouts):
     rank = oracle.rank_build(order.numpy())
     tabs = [np.ascontiguousarray(by_rank[:n_hbm]), np.ascontiguousarray(by_rank[n_hbm:n_hbm + n_host]),
             np.ascontiguousarray(by_rank[n_hbm + n_host:])]
-    for n_seeds in (1, 300, 1500):                      # one tile, and a ragged second tile; repeated seeds
+    for n_seeds in (0, 1, 300, 1500):                   # none; one tile; a ragged second tile; repeated seeds
         seeds = torch.from_numpy(rng.integers(0, n, n_seeds).astype(np.int32))
         want = oracle_path(oracle, off, idx, seeds.numpy(), fanouts, 77, rank, n_hbm, n_host, *tabs, 48)
         assert_same(gpu_path(h, helios, seeds, fanouts, 77, fused=True), want)
