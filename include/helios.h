@@ -139,6 +139,21 @@ int helios_sample(helios_ctx *ctx, const int32_t *seeds, int64_t n_seeds,
 int helios_dedup(helios_ctx *ctx, const int32_t *ids, int64_t n_ids,
                  int32_t *unique, int64_t unique_cap, int32_t *inverse, int64_t *n_unique);
 
+/* helios_dedup for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * results and same errors as helios_dedup, but the call allocates and frees
+ * nothing: all its scratch (hash table, per-input slots, scan state, counters)
+ * is a fixed array of about 6 MiB in the library's device image, which every
+ * GPU the library runs on holds until the process ends.  At most
+ * HELIOS_DEDUP_NOALLOC_MAX_IDS IDs per call, more is HELIOS_EINVAL.  All
+ * contexts of a GPU share that array and each call starts by resetting it, so
+ * calls that overlap on one GPU (different streams or host threads) race: the
+ * caller serialises them.  It does not touch the scratch of helios_dedup or of
+ * the batch calls. */
+#define HELIOS_DEDUP_NOALLOC_MAX_IDS 262144
+int helios_dedup_noalloc(helios_ctx *ctx, const int32_t *ids, int64_t n_ids,
+                         int32_t *unique, int64_t unique_cap, int32_t *inverse, int64_t *n_unique);
+
 /* Cache lookup + feature gather + miss list (Sec. 3.2.2 "Cache Lookup": GPU
  * threads read cached rows directly from GPU memory or, through the mapped
  * address, from CPU memory; Sec. 3.1.1: the IDs found in neither cache are

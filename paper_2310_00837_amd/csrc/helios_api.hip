@@ -3,6 +3,7 @@
 // for the contract of every entry point.
 #include "context.hpp"
 #include "missq.hpp"
+#include "noalloc.hpp"
 
 using namespace helios;
 
@@ -283,6 +284,7 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
     ok = ok && c->err && c->cnt && c->vars && c->scan_ticket && c->batches_run && c->vars_ring && c->clock && c->clock_host;
+    ok = ok && noalloc_init(device) == HELIOS_OK;      // address of this device's static scratch (helios_dedup_noalloc)
     if (ok) {
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libhelios.so")
 
 OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 MAX_HOPS, MAX_FANOUT = 8, 1024
+DEDUP_NOALLOC_MAX_IDS = 262144
 PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SERIAL_TIERS = 1, 2, 3
 PARAM_MISSQ_TIMEOUT_US, PARAM_MISSQ_WAVES = 4, 5
 _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
@@ -27,7 +28,7 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 
 # every symbol include/helios.h declares
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
-           "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup",
+           "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup", "helios_dedup_noalloc",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
            "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_wait", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
            "helios_gather_times", "helios_gather_ticks", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
@@ -67,6 +68,7 @@ def load_library() -> C.CDLL:
     lib.helios_cache_fill.argtypes = [vp, vp, vp, i64, i64, i32, vp]
     lib.helios_sample.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp]
     lib.helios_dedup.argtypes = [vp, vp, i64, vp, i64, vp, vp]
+    lib.helios_dedup_noalloc.argtypes = [vp, vp, i64, vp, i64, vp, vp]
     lib.helios_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, i64, vp]
     lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
@@ -399,6 +401,18 @@ class Helios:
             assert inverse.numel() >= n
         self._check(_lib.helios_dedup(self._h, _ptr(ids), n, _ptr(unique), unique.numel(), _ptr(inverse),
                                       _ptr(n_unique)))
+
+    def dedup_noalloc(self, ids: torch.Tensor, unique: torch.Tensor, inverse: Optional[torch.Tensor],
+                      n_unique: torch.Tensor, n_ids: Optional[int] = None) -> None:
+        """helios_dedup on the library's fixed scratch array: allocates nothing (at most DEDUP_NOALLOC_MAX_IDS IDs)."""
+        _dev(ids, torch.int32, "ids"), _dev(unique, torch.int32, "unique")
+        _dev_accessible(n_unique, torch.int64, "n_unique")
+        n = ids.numel() if n_ids is None else n_ids
+        if inverse is not None:
+            _dev(inverse, torch.int32, "inverse")
+            assert inverse.numel() >= n
+        self._check(_lib.helios_dedup_noalloc(self._h, _ptr(ids), n, _ptr(unique), unique.numel(), _ptr(inverse),
+                                              _ptr(n_unique)))
 
     # ---- S3 + S4 + S5
     def gather(self, ids: torch.Tensor, out: torch.Tensor, miss_pos: torch.Tensor, miss_id: torch.Tensor,
