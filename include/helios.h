@@ -24,9 +24,10 @@
  *  - Node IDs, positions and slots are int32; edge offsets and counts int64.
  *    A single call handles fewer than 2^31 IDs; a CSR row holds fewer than
  *    2^31 entries.
- *  - The library allocates its own scratch (hash table, scan state, position
+ *  - The library allocates its own scratch (hash tables, scan state, position
  *    lists) and grows it when a call needs more than any call before;
- *    helios_reserve() does that ahead of time.
+ *    helios_reserve() does that ahead of time, after which calls of that size
+ *    allocate nothing.
  *  - One context serves one stream; calls on one context must not overlap
  *    from several host threads.
  */
@@ -180,9 +181,12 @@ int helios_gather(helios_ctx *ctx, const int32_t *ids, int64_t n_ids, void *out,
  * stack of Sec. 3.1): out[miss_pos[k],:] = standin_table[miss_slot[k],:].
  * n_miss_max bounds the list; if n_miss_dev (device-accessible int64, e.g.
  * &stats->n_miss) is not NULL the count is read from it on the device,
- * otherwise exactly n_miss_max entries are served. */
+ * otherwise exactly n_miss_max entries are served.  out has out_rows rows.
+ * The list is the caller's, so every entry is checked on the device: one whose
+ * slot is no row of the stand-in, or whose position is no row of out, is
+ * skipped and reported as HELIOS_EDATA by the next helios_sync. */
 int helios_gather_miss(helios_ctx *ctx, const int32_t *miss_pos, const int32_t *miss_slot,
-                       int64_t n_miss_max, const int64_t *n_miss_dev, void *out);
+                       int64_t n_miss_max, const int64_t *n_miss_dev, void *out, int64_t out_rows);
 
 /* The whole path for one mini-batch with no host round trip between the
  * steps: helios_sample, then helios_dedup of [seeds | flat_0 | ... |
@@ -213,8 +217,11 @@ int helios_host_free(void *ptr);
  * with indptr_h this is the hop's block in CSR form over the rows of `out`.
  * hops: the descriptors given to helios_prepare_batch; blocks: host array of
  * n_hops descriptors of device buffers, row_local[frontier_cap(h)],
- * col_local[flat_cap(h)].  Must directly follow helios_prepare_batch (it
- * reuses that call's hash table); otherwise HELIOS_ESTATE. */
+ * col_local[flat_cap(h)].  It reuses the hash table of that batch's
+ * de-duplication, which the context keeps until the second batch after it is
+ * launched; helios_make_blocks serves the context's last batch (HELIOS_ESTATE
+ * if there is none), helios_plan_make_blocks (below) the last batch of a
+ * recorded plan, also when one more batch has been queued behind it. */
 typedef struct {
     int32_t *row_local;
     int32_t *col_local;
@@ -244,14 +251,17 @@ int helios_hotness_order(helios_ctx *ctx, const int32_t *counts, int32_t *order)
  * copy bandwidth the part reaches. */
 int helios_calibration_copy(helios_ctx *ctx, const void *src, void *dst, int64_t bytes);
 
-/* Launch-shape parameters of the row-copy kernels (tuning; results do not
- * depend on them).  *_GATHER_BLOCKS: workgroups of the persistent grid that
- * copies the HBM tier / the host tier and stand-in (0 = built-in default; the
- * host-link kernels need few workgroups to fill the link, and fewer of them
- * leave more of the memory system to the HBM-tier copy that runs beside them,
- * cf. Sec. 3.3 "Operator Resources Allocation").  SERIAL_TIERS: non-zero (the
- * default) runs the host-tier copy after the HBM-tier copy on the context's
- * stream; zero runs the two side by side on two streams.
+/* Launch-shape parameters (tuning; results do not depend on them).
+ * *_GATHER_BLOCKS: workgroups that copy the HBM tier / the host tier and
+ * stand-in (0 = built-in default; the host-link copies need few workgroups to
+ * fill the link, and fewer of them leave more of the GPU to the work that runs
+ * beside them, cf. Sec. 3.3 "Operator Resources Allocation").  SPLIT_COPIES:
+ * zero (the default): helios_prepare_batch overlaps its steps inside its
+ * launches (Sec. 3.3, intra-mini-batch pipeline): the host-tier rows that one
+ * hop has brought in are copied while the next hop is sampled, and the last
+ * ones beside the HBM-tier copy.  Non-zero: the two tier copies run after the
+ * last hop as kernels of their own, one after the other (for measuring each
+ * copy by itself).
  * MISSQ_TIMEOUT_US: how long a wave of helios_missq_complete's kernel waits
  * without seeing a new completion before it gives up (default 2 000 000);
  * MISSQ_WAVES: waves of that kernel (0 = default 256; at least one per 64
@@ -259,7 +269,7 @@ int helios_calibration_copy(helios_ctx *ctx, const void *src, void *dst, int64_t
 typedef enum {
     HELIOS_PARAM_HBM_GATHER_BLOCKS = 1,
     HELIOS_PARAM_HOST_GATHER_BLOCKS = 2,
-    HELIOS_PARAM_SERIAL_TIERS = 3,
+    HELIOS_PARAM_SPLIT_COPIES = 3,
     HELIOS_PARAM_MISSQ_TIMEOUT_US = 4,
     HELIOS_PARAM_MISSQ_WAVES = 5
 } helios_param;
@@ -267,8 +277,8 @@ int helios_set_param(helios_ctx *ctx, int param, int64_t value);
 
 /* A recorded batch: the kernel sequence of helios_prepare_batch for one fixed
  * set of buffers, captured once into a HIP graph and replayed with one launch
- * per mini-batch (the per-batch path is eight short kernels, so the host's
- * launch cost matters).  helios_plan_create takes the arguments of
+ * per mini-batch (the per-batch path is a handful of short kernels, so the
+ * host's launch cost matters).  helios_plan_create takes the arguments of
  * helios_prepare_batch except seeds and rng_seed; all buffers, capacities,
  * n_seeds and fan-outs are fixed by it.  helios_plan_launch(plan, seeds,
  * rng_seed) enqueues one batch on the context's stream: seeds (device
@@ -288,11 +298,19 @@ int helios_plan_create(helios_ctx *ctx, int64_t n_seeds, const int32_t *fanouts,
                        int64_t miss_cap, helios_gather_stats *stats, helios_plan **plan_out);
 int helios_plan_launch(helios_plan *plan, const int32_t *seeds, uint64_t rng_seed);
 /* Waits until the plan's last launch has finished (not for launches of other
- * plans queued behind it on the same context) and reports device-side errors
- * like helios_sync.  With two plans over two buffer sets on one context the
+ * plans queued behind it on the same context) and reports the device-side
+ * errors of this plan's batches (every plan has an error word of its own;
+ * helios_sync reports and clears those of all plans of the context).  With two plans over two buffer sets on one context the
  * host can queue a batch behind the one that is running and still take each
  * batch's results as soon as it is done. */
 int helios_plan_wait(helios_plan *plan);
+/* helios_make_blocks for the plan's last launch, from the plan's own buffers
+ * (the hops and sizes given to helios_plan_create; without a sizes array only
+ * right after the launch).  Valid while at most one more batch has been
+ * launched on the context since (e.g. two plans over two buffer sets used in
+ * turn: launch A, launch B, wait A, blocks of A, launch A, ...); else
+ * HELIOS_ESTATE.  Its device-side errors are reported by the plan's wait. */
+int helios_plan_make_blocks(helios_plan *plan, const helios_block_out *blocks);
 int helios_plan_destroy(helios_plan *plan);
 
 /* Asynchronous service of the miss list in the shape of the GPU-initiated IO
@@ -315,8 +333,10 @@ int helios_plan_destroy(helios_plan *plan);
  * time limit).  The queue is bound to the context and to that cache: after
  * another helios_cache_build its calls return HELIOS_ESTATE.
  * helios_missq_submit enqueues the submission kernel on the context's stream
- * (arguments as helios_gather_miss); helios_missq_complete enqueues the
- * completion kernel.  The two alternate (else HELIOS_ESTATE): one round at a
+ * (arguments as helios_gather_miss: out_rows = rows of the buffer that
+ * helios_missq_complete will be given; an entry outside the stand-in or
+ * outside out is reported as HELIOS_EDATA and its data is dropped);
+ * helios_missq_complete enqueues the completion kernel.  The two alternate (else HELIOS_ESTATE): one round at a
  * time per queue; to keep several batches in flight give each context a queue.
  * A round with more misses than the queues hold reports HELIOS_ECAPACITY at
  * helios_sync and serves the first n_queues * queue_depth.  If the service
@@ -335,7 +355,7 @@ typedef struct helios_missq helios_missq;
 int helios_missq_create(helios_ctx *ctx, int32_t n_queues, int32_t queue_depth,
                         int32_t n_service_threads, helios_missq **out);
 int helios_missq_submit(helios_missq *q, const int32_t *miss_pos, const int32_t *miss_slot,
-                        int64_t n_miss_max, const int64_t *n_miss_dev);
+                        int64_t n_miss_max, const int64_t *n_miss_dev, int64_t out_rows);
 int helios_missq_complete(helios_missq *q, void *out);
 int helios_missq_attach(helios_ctx *ctx, helios_missq *q);
 int helios_missq_faulted(const helios_missq *q);
@@ -344,26 +364,40 @@ int helios_missq_faulted(const helios_missq *q);
 int helios_missq_counters(const helios_missq *q, int64_t *out3);
 int helios_missq_destroy(helios_missq *q);
 
-/* Timing of the two row-copy kernels (HBM tier, host tier) of the last
- * helios_gather / helios_prepare_batch on this context.  Level 1: every
- * workgroup of those kernels stores its first and last tick of the GPU's
- * constant-rate clock; helios_gather_times waits for the stream and returns,
- * per kernel, latest end minus earliest start in milliseconds (hbm_ms,
- * host_ms: the kernel's own duration, as a kernel trace reports it).  Level 2
- * also records HIP events around the launch on the kernel's stream and
- * returns the time between them (hbm_event_ms, host_event_ms, nullable; 0 at
- * level 1): these also contain launch gaps.  Level 0 turns timing off.  A
- * tier that launched nothing reports 0. */
+/* Timing.  Level 1: every workgroup of every step ("role": a launch of the
+ * whole-path call carries several, see SPLIT_COPIES) of the next
+ * helios_prepare_batch / helios_gather / recorded batch stores its first and
+ * last tick of the GPU's constant-rate clock; helios_batch_ticks waits for the
+ * stream and returns, per role of the last batch, earliest start and latest
+ * end (ticks of a clock that all contexts of a device share, so batches in
+ * flight on several contexts can be placed on one time axis; *ticks_per_us,
+ * nullable, receives its rate).  kind is a helios_role, stage the hop (for
+ * copies: the stage of the batch's ID list, i.e. the hop that completed it).
+ * helios_gather_times returns the HBM-tier copy's span and the sum of the
+ * host-tier copies' spans in milliseconds.  Level 2 (directly launched calls
+ * with split copies, and helios_gather): the two copy kernels are launched
+ * with HIP events that take each kernel's own begin and end, as a kernel
+ * trace reports them; helios_gather_times returns them in hbm_event_ms /
+ * host_event_ms (nullable; 0 at level 1).  Level 0 turns timing off.  The
+ * level in force when a batch is recorded (0 or 1) is part of the recording. */
+typedef enum {
+    HELIOS_ROLE_SAMPLE = 1,          /* sampling pass of a hop                       */
+    HELIOS_ROLE_COMPACT_HOP = 2,     /* a hop's samples -> next frontier             */
+    HELIOS_ROLE_COMPACT_LOOKUP = 3,  /* a stage of the batch's ID list, cache lookup */
+    HELIOS_ROLE_COPY_HOST = 4,       /* host-tier rows of a stage                    */
+    HELIOS_ROLE_COPY_HBM = 5,        /* HBM-tier rows                                */
+    HELIOS_ROLE_INVERSE = 6
+} helios_role;
+typedef struct {
+    int32_t kind, stage;
+    int64_t workgroups;
+    uint64_t start, end;             /* 0, 0 if the role did not run */
+} helios_role_ticks;
 int helios_set_timing(helios_ctx *ctx, int level);
+int helios_batch_ticks(helios_ctx *ctx, helios_role_ticks *out, int32_t cap, int32_t *n_out,
+                       double *ticks_per_us);
 int helios_gather_times(helios_ctx *ctx, float *hbm_ms, float *host_ms,
                         float *hbm_event_ms, float *host_event_ms);
-/* The same two kernels' first and last tick themselves (level >= 1):
- * ticks4 = {HBM start, HBM end, host start, host end} of the GPU's
- * constant-rate clock, which all contexts of a device share, so the copies of
- * batches in flight on several contexts can be placed on one time axis;
- * *ticks_per_us (nullable) receives the clock rate.  Zeros for a tier that
- * launched nothing. */
-int helios_gather_ticks(helios_ctx *ctx, uint64_t *ticks4, double *ticks_per_us);
 
 #ifdef __cplusplus
 }

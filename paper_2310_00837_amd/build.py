@@ -11,7 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(CSRC, "libhelios.so")
-SOURCES = ["sample.hip", "dedup.hip", "cache.hip", "gather.hip", "blocks.hip", "hotness.hip", "missq.hip",
+SOURCES = ["pipeline.hip", "sample.hip", "dedup.hip", "cache.hip", "gather.hip", "blocks.hip", "hotness.hip", "missq.hip",
            "noalloc.hip", "helios_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

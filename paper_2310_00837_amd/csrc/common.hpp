@@ -35,12 +35,15 @@ struct BatchVars {
     const int32_t* seeds;
     uint32_t epoch_base;     // added to the per-launch epoch of the chained scans
     uint32_t io_round;       // round number of the miss queue the batch submits to (0 if none)
+    uint32_t table;          // which of the rotating batch tables this batch uses
+    uint32_t reserved;
 };
 
 // How a recorded batch gets its BatchVars without a copy being part of the recording: the host writes
-// them to the next slot of a ring in pinned memory before every launch; the batch's first kernel reads
-// the slot that the number of recorded batches run so far on the context selects (a device counter,
-// advanced by the batch's second kernel) and leaves a copy in device memory for the kernels after it.
+// them to the next slot of a ring in pinned memory before every launch; the workgroups of the batch's
+// first kernel read the slot that the number of recorded batches run so far on the context selects (a
+// device counter, advanced by the batch's second kernel) and the first of them leaves a copy in device
+// memory for the kernels after it.
 struct BatchFeed {
     const BatchVars* ring;        // pinned host memory, nullable (a directly launched batch)
     uint32_t ring_slots;
@@ -52,6 +55,33 @@ struct BatchFeed {
 // err points to pinned, GPU-mapped host memory (int32[2]: code, detail).
 __device__ __forceinline__ void raise(int32_t* err, int code) {
     *reinterpret_cast<volatile int32_t*>(err) = code;
+}
+
+// A role is a range of the workgroups of a launch that does one job; several roles share a launch
+// when their jobs are independent and bound by different things (the host link, HBM, latency).
+// Workgroup blockIdx.x belongs to the role with first <= blockIdx.x < first + blocks and is its
+// workgroup number blockIdx.x - first.
+struct Role {
+    uint32_t first, blocks;
+    __device__ __forceinline__ bool mine() const { return blockIdx.x - first < blocks; }   // unsigned wrap-around
+    __device__ __forceinline__ uint32_t rb() const { return blockIdx.x - first; }
+};
+constexpr unsigned kMaxRoleBlocks = 8192;
+
+// Optional timing of a role: workgroup rb of nrb stores its first and last tick of the constant-rate
+// device clock at clock[rb] and clock[nrb + rb] (plain stores, no contention); a publish kernel
+// reduces them to {earliest start, latest end} in pinned host memory.
+struct Stamps {
+    unsigned long long* clock;     // nullable
+};
+__device__ __forceinline__ void stamp_start(const Stamps& s, uint32_t rb) {
+    if (s.clock && threadIdx.x == 0) s.clock[rb] = wall_clock64();
+}
+__device__ __forceinline__ void stamp_end(const Stamps& s, uint32_t rb, uint32_t nrb) {
+    if (s.clock) {
+        __syncthreads();
+        if (threadIdx.x == 0) s.clock[nrb + rb] = wall_clock64();
+    }
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }

@@ -5,7 +5,34 @@
 #include "missq.hpp"
 #include "noalloc.hpp"
 
+#include <algorithm>
+
 using namespace helios;
+
+struct helios_plan {
+    helios_ctx* ctx = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    uint32_t n_scans = 0;
+    uint64_t scratch_generation = 0;
+    uint64_t cache_generation = 0, graph_generation = 0;   // the recording holds the graph's and the cache's pointers and sizes
+    int64_t n_seeds = 0;
+    int32_t n_hops = 0;
+    int64_t frontier_max[HELIOS_MAX_HOPS] = {0};
+    int64_t flat_max[HELIOS_MAX_HOPS] = {0};
+    helios_hop_out hops[HELIOS_MAX_HOPS] = {};
+    const int64_t* sizes = nullptr;    // the caller's size array (device-accessible, nullable)
+    uint32_t slots = 0;                // slots of the batch table the recording uses
+    uint32_t clear_slots = 0;          // slots of the next batch's table it empties on the way
+    helios_missq* missq = nullptr;     // the queue attached when the batch was recorded
+    hipEvent_t done = nullptr;         // recorded behind every launch
+    uint64_t launch_seq = 0;           // the context's launch count at this plan's last launch
+    uint64_t batch_seq = 0;            // the context's batch count right after this plan's last launch
+    int32_t* err = nullptr;            // pinned int32[2]: the device-side error word of this plan's batches
+    StampRole stamp_roles[kMaxStampRoles];
+    StampTable stamp_table{};
+    int n_stamps = 0;
+};
 
 namespace {
 
@@ -16,30 +43,32 @@ uint32_t pow2_at_least(int64_t n) {
 }
 
 void free_scratch(helios_ctx* c) {
-    (void)hipFree(c->dd.table);
-    (void)hipFree(c->dd.slot_of);
-    (void)hipFree(c->dd.index_of_first);
+    (void)hipFree(c->batch_tables);
+    (void)hipFree(c->batch_iof);
+    (void)hipFree(c->batch_slot_of);
     for (int t = 0; t < 2; ++t) {
         (void)hipFree(c->list_pos[t]);
         (void)hipFree(c->list_slot[t]);
+        (void)hipFree(c->hop_table[t]);
         c->list_pos[t] = c->list_slot[t] = nullptr;
+        c->hop_table[t] = nullptr;
     }
     (void)hipFree(c->cat);
     (void)hipFree(c->scan_status);
-    (void)hipFree(c->hop_table[0]);
-    (void)hipFree(c->hop_table[1]);
     (void)hipFree(c->hop_slot_of);
-    c->hop_table[0] = c->hop_table[1] = nullptr;
-    c->hop_slot_of = nullptr;
-    c->dd = DedupScratch{nullptr, 0, nullptr, nullptr};
-    c->cat = nullptr;
+    c->batch_tables = nullptr;
+    c->batch_iof = c->batch_slot_of = c->hop_slot_of = c->cat = nullptr;
     c->scan_status = nullptr;
     c->cap_ids = 0;
+    c->table_slots = 0;
     c->scan_stride = 0;
 }
 
+unsigned long long* batch_table(const helios_ctx* c, uint32_t t) { return c->batch_tables + static_cast<size_t>(t) * c->table_slots; }
+int32_t* batch_iof(const helios_ctx* c, uint32_t t) { return c->batch_iof + static_cast<size_t>(t) * c->cap_ids; }
+
 // Scratch for calls with up to n IDs.  Growing waits for the stream first: the
-// old buffers may still be in use.
+// old buffers may still be in use.  Every hash table starts out empty.
 int ensure_capacity(helios_ctx* c, int64_t n) {
     if (n <= c->cap_ids) return HELIOS_OK;
     if (c->recording) return fail(c, HELIOS_ESTATE, "scratch must be reserved before a batch is recorded");
@@ -47,12 +76,13 @@ int ensure_capacity(helios_ctx* c, int64_t n) {
     if (n >= (1ll << 31) - 1024) return fail(c, HELIOS_EINVAL, "a call handles fewer than 2^31 IDs (got %lld)", (long long)n);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     free_scratch(c);
+    c->blocks_ready = false;
     const int64_t cap = (n + 4095) / 4096 * 4096;
     const uint32_t slots = pow2_at_least(2 * cap);
     const uint32_t stride = static_cast<uint32_t>(cap / kTileItems + 2);
-    HIP_TRY(c, hipMalloc(&c->dd.table, sizeof(unsigned long long) * slots));
-    HIP_TRY(c, hipMalloc(&c->dd.slot_of, sizeof(int32_t) * cap));
-    HIP_TRY(c, hipMalloc(&c->dd.index_of_first, sizeof(int32_t) * cap));
+    HIP_TRY(c, hipMalloc(&c->batch_tables, sizeof(unsigned long long) * slots * kBatchTables));
+    HIP_TRY(c, hipMalloc(&c->batch_iof, sizeof(int32_t) * cap * kBatchTables));
+    HIP_TRY(c, hipMalloc(&c->batch_slot_of, sizeof(int32_t) * cap));
     HIP_TRY(c, hipMalloc(&c->hop_table[0], sizeof(unsigned long long) * slots));
     HIP_TRY(c, hipMalloc(&c->hop_table[1], sizeof(unsigned long long) * slots));
     HIP_TRY(c, hipMalloc(&c->hop_slot_of, sizeof(int32_t) * cap));
@@ -61,29 +91,45 @@ int ensure_capacity(helios_ctx* c, int64_t n) {
         HIP_TRY(c, hipMalloc(&c->list_slot[t], sizeof(int32_t) * cap));
     }
     HIP_TRY(c, hipMalloc(&c->cat, sizeof(int32_t) * cap));
-    HIP_TRY(c, hipMalloc(&c->scan_status, sizeof(unsigned long long) * 3 * stride));
-    HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * stride, c->stream));
-    c->dd.n_slots = slots;
+    HIP_TRY(c, hipMalloc(&c->scan_status, sizeof(unsigned long long) * kScanRows * stride));
+    HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * kScanRows * stride, c->stream));
+    c->table_slots = slots;
     c->scan_stride = stride;
     c->epoch = 0;
     c->cap_ids = cap;
+    for (uint32_t t = 0; t < kBatchTables; ++t) {
+        HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, t), slots}));
+        c->batch_dirty[t] = 0;
+    }
+    for (int t = 0; t < 2; ++t) {
+        HIP_TRY(c, launch_clear(c->stream, ClearJob{c->hop_table[t], slots}));
+        c->hop_dirty[t] = 0;
+    }
     return HELIOS_OK;
 }
 
-// scan state with a fresh epoch; stale status words of earlier launches read as unpublished
-int next_scan(helios_ctx* c, ScanState* out) {
-    if (!c->recording && c->epoch >= (1u << 30) - 64) {
-        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * c->scan_stride, c->stream));
-        c->epoch = 0;
-    }
-    if (c->recording) {                       // the batch's base epoch is added on the device
+// A fresh epoch for the scans of one launch; stale status words of earlier launches read as
+// unpublished.  In a recording the batch's base epoch is added on the device.
+int next_epoch(helios_ctx* c, uint32_t* out) {
+    if (c->recording) {
         c->rec_scans += 1;
-        *out = ScanState{c->scan_status, c->scan_ticket, c->scan_stride, c->rec_scans, c->vars};
+        *out = c->rec_scans;
         return HELIOS_OK;
     }
+    if (c->epoch >= (1u << 30) - 64) {
+        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * kScanRows * c->scan_stride, c->stream));
+        c->epoch = 0;
+    }
     c->epoch += 1;
-    *out = ScanState{c->scan_status, c->scan_ticket, c->scan_stride, c->epoch, nullptr};
+    *out = c->epoch;
     return HELIOS_OK;
+}
+
+// scan state over the status rows from `first_row` on; the two row groups have a ticket counter each
+ScanState scan_state(const helios_ctx* c, uint32_t epoch, int first_row) {
+    return ScanState{c->scan_status + static_cast<size_t>(first_row) * c->scan_stride,
+                     c->scan_ticket + (first_row == kScanRowsHop ? 0 : 16), c->scan_stride, epoch,
+                     c->recording ? c->vars : nullptr};
 }
 
 int64_t sat_mul(int64_t a, int64_t b) {
@@ -130,126 +176,347 @@ int plan_hops(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_
 }
 
 // slots of the hash table a de-duplication of up to n_max IDs uses (no more than it needs: a smaller
-// table is cheaper to clear and stays in cache)
+// table is cheaper to empty and stays in cache)
 uint32_t dedup_slots(const helios_ctx* c, int64_t n_max) {
     const uint32_t want = pow2_at_least(2 * n_max);
-    return want < c->dd.n_slots ? want : c->dd.n_slots;
+    return want < c->table_slots ? want : c->table_slots;
 }
 
-SegLens one_segment(Count n) {
-    SegLens lens{};
-    lens.n_seg = 1;
-    lens.len[0] = n;
-    return lens;
+unsigned tiles_for(int64_t n_max) {
+    int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
+    return static_cast<unsigned>(tiles < 1 ? 1 : tiles);
 }
 
-// Hop 0: count pass over the seeds (it also empties the tables that the first sampling pass fills),
-// sampling pass.  Hop h > 0: the de-duplication of flat_{h-1} yields frontier_h together with its
-// indptr, then the sampling pass.  A sampling pass inserts its samples into the table of the
-// de-duplication between this hop and the next, and, with batch_dedup_max > 0 (the whole-path call),
-// into the table of the batch's ID list [seeds | flat_0 | ...], which c->cat receives; so those
-// de-duplications start at their compaction pass.
-int sample_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
-                uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p,
-                int64_t batch_dedup_max) {
-    const BatchVars* vars = c->recording ? c->vars : nullptr;
-    const BatchFeed feed = c->recording ? BatchFeed{c->vars_ring, kVarsRing, c->batches_run, c->vars}
-                                        : BatchFeed{nullptr, 0, nullptr, nullptr};
-    const InsertInto batch_table = batch_dedup_max > 0 ? InsertInto{c->dd.table, dedup_slots(c, batch_dedup_max), c->dd.slot_of}
-                                                       : InsertInto{nullptr, 0, nullptr};
-    auto hop_table = [&](int h) {               // hops alternate between two tables
-        return h + 1 < n_hops ? InsertInto{c->hop_table[h % 2], dedup_slots(c, p.flat_max[h]), c->hop_slot_of}
-                              : InsertInto{nullptr, 0, nullptr};
-    };
-    auto clear_of = [](const InsertInto& t) { return ClearJob{t.table, t.table ? t.n_slots : 0u}; };
-    Count prev_flat[HELIOS_MAX_HOPS];
-    Count nf{nullptr, n_seeds};
-    {
-        ScanState scan;
-        int rc = next_scan(c, &scan);
-        if (rc) return rc;
-        HIP_TRY(c, launch_frontier_count(c->stream, c->g, seeds, feed, hops[0].frontier, nf, n_seeds, fanouts[0],
-                                         hops[0].indptr, hops[0].flat_cap, c->cnt + kCntFlat + 0, sizes,
-                                         clear_of(hop_table(0)), clear_of(batch_table), scan, c->err));
-    }
-    for (int h = 0; h < n_hops; ++h) {
-        const bool last = h + 1 == n_hops;
-        const InsertInto mine = hop_table(h);
-        HIP_TRY(c, launch_sample_hop(c->stream, c->g, hops[h].frontier, hops[h].indptr, nf, p.frontier_max[h], fanouts[h],
-                                     h, rng_seed, vars, hops[h].flat, p.flat_max[h], clear_of(hop_table(h + 1)), mine,
-                                     batch_table, c->cat, n_seeds, prev_flat, c->recording ? c->batches_run : nullptr, c->err));
-        prev_flat[h] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
-        if (!last) {
-            NextHopCount next{c->g.offsets, c->g.n_nodes, fanouts[h + 1], hops[h + 1].indptr, hops[h + 1].flat_cap,
-                              c->cnt + kCntFlat + h + 1, sizes ? sizes + 2 * (h + 1) : nullptr};
-            ScanState scan;
-            int rc = next_scan(c, &scan);
-            if (rc) return rc;
-            const DedupScratch s{mine.table, mine.n_slots, mine.slot_of, c->dd.index_of_first};
-            HIP_TRY(c, launch_dedup_compact(c->stream, hops[h].flat, one_segment(prev_flat[h]), p.flat_max[h],
-                                            c->cnt + kCntHopTotal, s, hops[h + 1].frontier, hops[h + 1].frontier_cap,
-                                            c->cnt + kCntFrontier + h + 1, nullptr, &next, nullptr, scan, c->err));
-            nf = Count{c->cnt + kCntFrontier + h + 1, p.frontier_max[h + 1]};
-        }
-    }
-    c->blocks_ready = false;
+// ---- timing of roles
+void reset_stamps(helios_ctx* c) {
+    c->n_stamps = 0;
+    c->stamp_words = 0;
+    c->timed_events = false;
+}
+
+// Room in the clock buffer for a role of `workgroups` workgroups, if roles are being timed.
+Stamps take_stamps(helios_ctx* c, int kind, int stage, unsigned workgroups) {
+    if (c->timing != 1 || c->n_stamps >= kMaxStampRoles || workgroups == 0 || workgroups > kMaxRoleBlocks) return Stamps{nullptr};
+    const int q = c->n_stamps++;
+    c->stamp_roles[q] = StampRole{kind, stage, workgroups};
+    c->stamp_table.offset[q] = c->stamp_words;
+    c->stamp_table.workgroups[q] = workgroups;
+    Stamps s{reinterpret_cast<unsigned long long*>(c->clock) + c->stamp_words};
+    c->stamp_words += 2 * workgroups;
+    return s;
+}
+
+int publish_stamps(helios_ctx* c) {
+    if (c->n_stamps > 0) HIP_TRY(c, launch_clock_publish(c->stream, c->clock, c->stamp_table, c->n_stamps, c->clock_host));
     return HELIOS_OK;
 }
 
-TierLists tier_lists(helios_ctx* c) {
-    return TierLists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier};
+// ---- emptiness of the hash tables
+// Every table is empty between calls, except the batch tables of the last two batches (kept for
+// helios_make_blocks; `batch_dirty` says how much of each may be in use).  A call that failed half way
+// leaves its tables marked as in use: the next call empties them first.
+int clean_for_call(helios_ctx* c, int batch_table_needed /* -1: none */) {
+    for (int t = 0; t < 2; ++t)
+        if (c->hop_dirty[t]) {
+            HIP_TRY(c, launch_clear(c->stream, ClearJob{c->hop_table[t], c->hop_dirty[t]}));
+            c->hop_dirty[t] = 0;
+        }
+    if (batch_table_needed >= 0 && c->batch_dirty[batch_table_needed]) {
+        HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, batch_table_needed), c->batch_dirty[batch_table_needed]}));
+        c->batch_dirty[batch_table_needed] = 0;
+    }
+    return HELIOS_OK;
 }
 
-int copy_tiers(helios_ctx* c, Count n, void* out);
+struct BatchOut {                // the outputs of the whole-path call beyond those of the sampling
+    int32_t* unique;
+    int64_t unique_cap;
+    int32_t* inverse;
+    int64_t* n_unique;
+    void* out;
+    int32_t *miss_pos, *miss_id, *miss_slot;
+    int64_t miss_cap;
+    helios_gather_stats* stats;
+};
 
-int gather_impl(helios_ctx* c, const int32_t* ids, Count n, void* out, int32_t* miss_pos, int32_t* miss_id,
-                int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
-    ScanState scan;
-    int rc = next_scan(c, &scan);
+int64_t* stage_words(const helios_ctx* c, int stage) { return c->cnt + kCntStage + stage * kStageWords; }
+
+GatherArgs tier_copy_args(helios_ctx* c, int tier, const int64_t* begin, Count end, void* out, Stamps stamps) {
+    return GatherArgs{static_cast<const chunk16*>(tier == 0 ? c->hbm_table : c->host_table), c->list_pos[tier], c->list_slot[tier],
+                      begin, end, c->row_bytes / 16, static_cast<chunk16*>(out), -1, -1, c->err_now, stamps};
+}
+
+// The two row copies as kernels of their own over the per-tier lists that a lookup has left behind
+// (helios_gather, and the whole-path call with split copies); n_max bounds the lists.
+int copy_tiers_split(helios_ctx* c, int64_t n_max, void* out) {
+    const bool events = c->timing > 1 && !c->recording;
+    if (c->n_hbm > 0 && n_max > 0) {
+        const unsigned nb = copy_role_blocks(c->row_bytes / 16, false, n_max, c->hbm_blocks);
+        const GatherArgs a = tier_copy_args(c, 0, nullptr, Count{c->cnt + kCntTier + 0, n_max}, out, take_stamps(c, HELIOS_ROLE_COPY_HBM, 0, nb));
+        HIP_TRY(c, launch_gather_rows(c->stream, a, n_max, false, false, c->hbm_blocks, events ? c->t_hbm[0] : nullptr,
+                                      events ? c->t_hbm[1] : nullptr, nullptr));
+    }
+    if (c->n_host > 0 && n_max > 0) {
+        const unsigned nb = copy_role_blocks(c->row_bytes / 16, true, n_max, c->host_blocks);
+        const GatherArgs a = tier_copy_args(c, 1, nullptr, Count{c->cnt + kCntTier + 1, n_max}, out, take_stamps(c, HELIOS_ROLE_COPY_HOST, 0, nb));
+        HIP_TRY(c, launch_gather_rows(c->stream, a, n_max, true, false, c->host_blocks, events ? c->t_host[0] : nullptr,
+                                      events ? c->t_host[1] : nullptr, nullptr));
+    }
+    c->timed_events = events;
+    return HELIOS_OK;
+}
+
+// The sampling pipeline, and with `b` the whole path: see pipeline.hip for the launches and their roles.
+int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                 uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p, const BatchOut* b) {
+    const bool rec = c->recording;
+    const BatchVars* vars = rec ? c->vars : nullptr;
+    const BatchFeed feed = rec ? BatchFeed{c->vars_ring, kVarsRing, c->batches_run, c->vars} : BatchFeed{nullptr, 0, nullptr, nullptr};
+    int32_t* err = c->err_now;
+    const int32_t chunks = c->row_bytes / 16;
+    reset_stamps(c);
+    c->blocks_ready = false;
+
+    const int64_t batch_max = p.cat_max > 0 ? p.cat_max : 1;
+    const uint32_t which = static_cast<uint32_t>(c->batch_seq % kBatchTables), next = (which + 1) % kBatchTables;
+    BatchTables bt{nullptr, 0, nullptr, 0, 0, nullptr, 0};
+    uint32_t slots_b = 0;
+    if (b) {
+        slots_b = dedup_slots(c, batch_max);
+        bt = BatchTables{c->batch_tables, c->table_slots, c->batch_iof, static_cast<uint64_t>(c->cap_ids), slots_b, c->batch_slot_of, which};
+    }
+    uint32_t hop_slots[HELIOS_MAX_HOPS];
+    for (int h = 0; h < n_hops; ++h) hop_slots[h] = dedup_slots(c, p.flat_max[h]);
+    if (!rec) {
+        int rc = clean_for_call(c, b ? static_cast<int>(which) : -1);
+        if (rc) return rc;
+        // until the call has been enqueued completely, its tables count as in use
+        for (int h = 0; h + 1 < n_hops; ++h) c->hop_dirty[h % 2] = std::max(c->hop_dirty[h % 2], hop_slots[h]);
+        if (b) c->batch_dirty[which] = slots_b;
+    }
+    const int64_t u_max = b ? std::min(p.cat_max, b->unique_cap) : 0;
+
+    const bool fold = n_seeds <= kFoldMaxSeeds;
+    if (!fold) {
+        uint32_t epoch;
+        int rc = next_epoch(c, &epoch);
+        if (rc) return rc;
+        HIP_TRY(c, launch_frontier_count(c->stream, c->g, seeds, feed, hops[0].frontier, Count{nullptr, n_seeds}, n_seeds,
+                                         fanouts[0], hops[0].indptr, hops[0].flat_cap, c->cnt + kCntFlat + 0, sizes,
+                                         scan_state(c, epoch, kScanRowsHop), err));
+    }
+    Count prev_flat[HELIOS_MAX_HOPS];
+    Count nf{nullptr, n_seeds};
+    for (int h = 0; h < n_hops; ++h) {
+        const bool last = h + 1 == n_hops;
+        // ---- sampling pass of hop h; beside it the host-tier copy of the stage that the compaction before it listed
+        HopArgs ha{};
+        ha.offsets = c->g.offsets;
+        ha.indices = c->g.indices;
+        ha.n_nodes = c->g.n_nodes;
+        ha.fold = h == 0 && fold;
+        ha.frontier = ha.fold ? seeds : hops[h].frontier;
+        ha.indptr = hops[h].indptr;
+        ha.n_frontier = nf;
+        ha.fanout = fanouts[h];
+        ha.hop = h;
+        ha.rng_seed = rng_seed;
+        ha.vars = ha.fold ? nullptr : vars;          // the folded hop 0 of a recorded batch reads the ring itself
+        ha.flat = hops[h].flat;
+        ha.flat_cap = p.flat_max[h];
+        ha.clear = h > 0 ? ClearJob{c->hop_table[(h - 1) % 2], hop_slots[h - 1]} : ClearJob{nullptr, 0};
+        ha.hop_table = !last ? InsertInto{c->hop_table[h % 2], hop_slots[h], c->hop_slot_of} : InsertInto{nullptr, 0, nullptr};
+        ha.batch = bt;
+        ha.cat_out = c->cat;
+        ha.n_seeds = n_seeds;
+        for (int k = 0; k < h; ++k) ha.prev_flat[k] = prev_flat[k];
+        ha.err = err;
+        if (ha.fold) {
+            ha.feed = feed;
+            ha.frontier_out = hops[0].frontier;
+            ha.indptr_out = hops[0].indptr;
+            ha.n_flat_dev = c->cnt + kCntFlat + 0;
+            ha.size_out = sizes;
+        }
+        const unsigned hop_blocks = sample_role_blocks(fanouts[h], p.frontier_max[h]);
+        ha.stamps = take_stamps(c, HELIOS_ROLE_SAMPLE, h, hop_blocks);
+        GatherArgs link{};
+        unsigned link_blocks = 0;
+        if (b && h > 0 && !c->split_copies && c->n_host > 0 && u_max > 0) {
+            const int stage = h - 1;
+            const int64_t stage_max = std::min(u_max, stage == 0 ? n_seeds + p.flat_max[0] : p.flat_max[stage]);
+            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks);
+            link = tier_copy_args(c, 1, stage > 0 ? stage_words(c, stage - 1) + kStageHostCopy : nullptr,
+                                  Count{stage_words(c, stage) + kStageHostCopy, u_max}, b->out,
+                                  take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
+        }
+        HIP_TRY(c, launch_sample(c->stream, ha, hop_blocks, link, link_blocks));
+        prev_flat[h] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
+
+        // ---- compaction: this hop's samples into the next frontier, and stage h of the batch's ID list
+        if (last && !b) break;
+        uint32_t epoch;
+        int rc = next_epoch(c, &epoch);
+        if (rc) return rc;
+        CompactArgs hopc{}, look{};
+        unsigned hopc_blocks = 0, look_blocks = 0;
+        if (!last) {
+            hopc.ids = hops[h].flat;
+            hopc.lens.n_seg = 1;
+            hopc.lens.first_here = 0;
+            hopc.lens.len[0] = prev_flat[h];
+            hopc.n_max = p.flat_max[h];
+            hopc.n_total_dev = c->cnt + kCntHopTotal;
+            hopc.s = DedupScratch{c->hop_table[h % 2], hop_slots[h], c->hop_slot_of, nullptr};
+            hopc.unique = hops[h + 1].frontier;
+            hopc.unique_cap = hops[h + 1].frontier_cap;
+            hopc.last = true;
+            hopc.n_unique_dev = c->cnt + kCntFrontier + h + 1;
+            hopc.next = NextHopCount{c->g.offsets, c->g.n_nodes, fanouts[h + 1], hops[h + 1].indptr, hops[h + 1].flat_cap,
+                                     c->cnt + kCntFlat + h + 1, sizes ? sizes + 2 * (h + 1) : nullptr};
+            hopc.scan = scan_state(c, epoch, kScanRowsHop);
+            hopc.err = err;
+            hopc_blocks = tiles_for(p.flat_max[h]);
+            hopc.stamps = take_stamps(c, HELIOS_ROLE_COMPACT_HOP, h, hopc_blocks);
+        }
+        if (b) {
+            look.ids = c->cat;
+            look.lens.n_seg = h + 2;
+            look.lens.first_here = h == 0 ? 0 : h + 1;
+            look.lens.len[0] = Count{nullptr, n_seeds};
+            for (int k = 0; k <= h; ++k) look.lens.len[k + 1] = prev_flat[k];
+            look.n_max = h == 0 ? n_seeds + p.flat_max[0] : p.flat_max[h];
+            look.n_total_dev = c->cnt + kCntCat;
+            look.batch = bt;
+            look.vars = vars;
+            look.unique = b->unique;
+            look.unique_cap = b->unique_cap;
+            look.prev = h > 0 ? stage_words(c, h - 1) : nullptr;
+            look.mine = stage_words(c, h);
+            look.last = last;
+            look.n_unique_dev = c->cnt + kCntUnique;
+            look.n_unique_out = b->n_unique;
+            look.look = LookupOut{c->rank, c->n_hbm, c->n_host,
+                                  TierLists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier},
+                                  b->miss_pos, b->miss_id, b->miss_slot, b->miss_cap, reinterpret_cast<int64_t*>(b->stats)};
+            look.batches_run = rec && h == 0 ? c->batches_run : nullptr;
+            look.scan = scan_state(c, epoch, kScanRowsLook);
+            look.err = err;
+            look_blocks = tiles_for(look.n_max);
+            look.stamps = take_stamps(c, HELIOS_ROLE_COMPACT_LOOKUP, h, look_blocks);
+        }
+        HIP_TRY(c, launch_compact(c->stream, hopc, hopc_blocks, look, look_blocks));
+        nf = Count{c->cnt + kCntFrontier + h + 1, !last ? p.frontier_max[h + 1] : 0};
+    }
+    if (!b) {
+        if (!rec) for (int t = 0; t < 2; ++t) c->hop_dirty[t] = 0;         // every hop table was emptied on the way
+        return publish_stamps(c);
+    }
+
+    // ---- the end of the batch: the rest of the row copies, the inverse map, the next batch's table
+    if (c->missq) {                 // the misses are on their way while the cached tiers are copied
+        const int64_t m_max = std::min(b->miss_cap, u_max);
+        int rc = missq_submit_from_batch(c, b->miss_pos, b->miss_slot, Count{c->cnt + kCntTier + 2, m_max}, m_max, b->unique_cap);
+        if (rc) return rc;
+    }
+    const uint32_t clear_slots = rec ? slots_b : c->batch_dirty[next];
+    InverseArgs inv{Count{c->cnt + kCntCat, p.cat_max}, DedupScratch{nullptr, 0, nullptr, nullptr}, bt, vars, b->inverse, Stamps{nullptr}};
+    if (c->split_copies) {
+        int rc = copy_tiers_split(c, u_max, b->out);
+        if (rc) return rc;
+        if (b->inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, inv, p.cat_max));
+        // (a recording with split copies leaves the emptying of the next table to helios_plan_launch)
+        if (!rec && clear_slots) HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, next), clear_slots}));
+    } else {
+        const int stage = n_hops - 1;
+        GatherArgs hbm{}, link{};
+        unsigned hbm_blocks = 0, link_blocks = 0, inv_blocks = 0, clear_blocks = 0;
+        if (c->n_hbm > 0 && u_max > 0) {
+            hbm_blocks = copy_role_blocks(chunks, false, u_max, c->hbm_blocks);
+            hbm = tier_copy_args(c, 0, nullptr, Count{c->cnt + kCntTier + 0, u_max}, b->out, take_stamps(c, HELIOS_ROLE_COPY_HBM, stage, hbm_blocks));
+        }
+        if (c->n_host > 0 && u_max > 0) {
+            const int64_t stage_max = std::min(u_max, stage == 0 ? n_seeds + p.flat_max[0] : p.flat_max[stage]);
+            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks);
+            link = tier_copy_args(c, 1, stage > 0 ? stage_words(c, stage - 1) + kStageHostCopy : nullptr,
+                                  Count{c->cnt + kCntTier + 1, u_max}, b->out, take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
+        }
+        if (b->inverse) {
+            inv_blocks = static_cast<unsigned>(std::min<int64_t>(1024, (p.cat_max + kBlock - 1) / kBlock));
+            inv_blocks = inv_blocks < 1 ? 1 : inv_blocks;
+            inv.stamps = take_stamps(c, HELIOS_ROLE_INVERSE, stage, inv_blocks);
+        }
+        ClearJob clear{nullptr, 0};
+        if (clear_slots) {
+            clear = ClearJob{batch_table(c, next), clear_slots};      // a recording picks the table on the device
+            clear_blocks = std::min(256u, (clear_slots + kBlock * 16 - 1) / (kBlock * 16));
+        }
+        HIP_TRY(c, launch_finish(c->stream, hbm, hbm_blocks, link, link_blocks, inv, inv_blocks, clear, clear_blocks, bt, vars));
+    }
+    int rc = publish_stamps(c);
     if (rc) return rc;
-    HIP_TRY(c, launch_lookup_partition(c->stream, ids, n, n.host, c->rank, c->g.n_nodes, c->n_hbm, c->n_host,
-                                       tier_lists(c), miss_pos, miss_id, miss_slot, miss_cap,
-                                       reinterpret_cast<int64_t*>(stats), scan, c->err));
-    return copy_tiers(c, n, out);
+    if (!rec) {
+        for (int t = 0; t < 2; ++t) c->hop_dirty[t] = 0;
+        c->batch_dirty[next] = 0;
+        c->batch_seq += 1;
+        c->blocks_ready = true;
+        c->last_table = which;
+    }
+    c->rec_clear_slots = c->split_copies ? 0 : clear_slots;
+    c->last_slots = slots_b;
+    c->last_n_seeds = n_seeds;
+    c->last_n_hops = n_hops;
+    for (int h = 0; h < n_hops; ++h) {
+        c->last_frontier_max[h] = p.frontier_max[h];
+        c->last_flat_max[h] = p.flat_max[h];
+    }
+    return HELIOS_OK;
 }
 
-// The two row copies over the per-tier lists that a lookup has left behind; n bounds the lists.
-int copy_tiers(helios_ctx* c, Count n, void* out) {
-    const TierLists lists = tier_lists(c);
-    c->timed_hbm = c->timed_host = false;
-    const bool do_hbm = c->n_hbm > 0 && n.host > 0, do_host = c->n_host > 0 && n.host > 0;
-    const bool fork = do_host && !c->serial_tiers;
-    hipStream_t host_stream = fork ? c->aux : c->stream;
-    if (fork) {                                 // the host-tier copy runs beside the HBM-tier copy
-        HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));
-        HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_fork, 0));
+int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                       uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, int32_t* unique,
+                       int64_t unique_cap, int32_t* inverse, int64_t* n_unique, void* out, int32_t* miss_pos,
+                       int32_t* miss_id, int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
+    if (!c->has_graph || !c->has_cache) return fail(c, HELIOS_ESTATE, "helios_prepare_batch needs the graph and the cache");
+    HopPlan p;
+    int rc = plan_hops(c, n_seeds, fanouts, n_hops, hops, &p);
+    if (rc) return rc;
+    if (n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
+    if (unique_cap < 0 || miss_cap < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (unique_cap > 0 && (!unique || !out)) return fail(c, HELIOS_EINVAL, "NULL pointer");
+    if (miss_cap > 0 && (!miss_pos || !miss_id || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL miss list");
+    rc = ensure_capacity(c, p.ids_max);
+    if (rc) return rc;
+    const BatchOut b{unique, unique_cap, inverse, n_unique, out, miss_pos, miss_id, miss_slot, miss_cap, stats};
+    return run_pipeline(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, &b);
+}
+
+// a device-side error word: reports and clears what kernels have recorded since the last check
+int check_error_word(helios_ctx* c, int32_t* word) {
+    const int code = *reinterpret_cast<volatile int32_t*>(word);
+    if (code != 0) {
+        word[0] = 0;
+        return fail(c, code, code == HELIOS_ECAPACITY ? "an output did not fit its capacity"
+                             : code == HELIOS_EINTERNAL ? "a workgroup gave up waiting (chained scan, or a miss queue that stopped answering)"
+                             : "a node ID outside [0, n_nodes), an order that is not a permutation, or a list entry outside its table");
     }
-    if (do_hbm) {
-        if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_hbm[0], c->stream));
-        HIP_TRY(c, launch_gather_rows(c->stream, c->hbm_table, lists.pos[0], lists.slot[0],
-                                      Count{c->cnt + kCntTier + 0, n.host}, n.host, c->row_bytes, out, false,
-                                      c->timing ? c->clock : nullptr, &c->clock_blocks[0], c->hbm_blocks));
-        if (c->timing) {
-            if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_hbm[1], c->stream));
-            HIP_TRY(c, launch_clock_publish(c->stream, c->clock, c->clock_blocks[0], c->clock_host));
-            c->timed_hbm = true;
-        }
-    }
-    if (do_host) {
-        if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_host[0], host_stream));
-        HIP_TRY(c, launch_gather_rows(host_stream, c->host_table, lists.pos[1], lists.slot[1],
-                                      Count{c->cnt + kCntTier + 1, n.host}, n.host, c->row_bytes, out, true,
-                                      c->timing ? c->clock + 2 * kGatherMaxBlocks : nullptr, &c->clock_blocks[1], c->host_blocks));
-        if (c->timing) {
-            if (c->timing > 1) HIP_TRY(c, hipEventRecord(c->t_host[1], host_stream));
-            HIP_TRY(c, launch_clock_publish(host_stream, c->clock + 2 * kGatherMaxBlocks, c->clock_blocks[1],
-                                            c->clock_host + 2));
-            c->timed_host = true;
-        }
-        if (fork) {
-            HIP_TRY(c, hipEventRecord(c->ev_join, c->aux));
-            HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
-        }
+    return HELIOS_OK;
+}
+
+int make_blocks_impl(helios_ctx* c, uint32_t table, uint32_t slots, int64_t n_seeds, int32_t n_hops, const int64_t* frontier_max,
+                     const int64_t* flat_max, const int64_t* sizes, const helios_hop_out* hops, const helios_block_out* blocks,
+                     int32_t* err) {
+    const DedupScratch s{batch_table(c, table), slots, nullptr, batch_iof(c, table)};
+    for (int h = 0; h < n_hops; ++h)
+        if (!blocks[h].row_local || !blocks[h].col_local) return fail(c, HELIOS_EINVAL, "hop %d: NULL block buffer", h);
+    for (int h = 0; h < n_hops; ++h) {
+        // the sizes of the batch: the caller's size array if there is one (it belongs to the batch's buffers), else
+        // the context's counters, which hold those of the context's last batch
+        const Count nf = h == 0 ? Count{nullptr, n_seeds}
+                                : Count{sizes ? sizes + 2 * h : c->cnt + kCntFrontier + h, frontier_max[h]};
+        const Count nfl{sizes ? sizes + 2 * h + 1 : c->cnt + kCntFlat + h, flat_max[h]};
+        HIP_TRY(c, launch_local_ids(c->stream, hops[h].frontier, nf, frontier_max[h], s, blocks[h].row_local, err));
+        HIP_TRY(c, launch_local_ids(c->stream, hops[h].flat, nfl, flat_max[h], s, blocks[h].col_local, err));
     }
     return HELIOS_OK;
 }
@@ -268,20 +535,17 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
     helios_ctx* c = new helios_ctx();
     c->device = device;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    bool ok = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) == hipSuccess &&
-              hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess &&
-              hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess &&
-              hipEventCreate(&c->t_hbm[0]) == hipSuccess && hipEventCreate(&c->t_hbm[1]) == hipSuccess &&
+    bool ok = hipEventCreate(&c->t_hbm[0]) == hipSuccess && hipEventCreate(&c->t_hbm[1]) == hipSuccess &&
               hipEventCreate(&c->t_host[0]) == hipSuccess && hipEventCreate(&c->t_host[1]) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->err), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipMalloc(&c->cnt, sizeof(int64_t) * kNumCounters) == hipSuccess &&
               hipMalloc(&c->vars, sizeof(BatchVars)) == hipSuccess &&
-              hipMalloc(&c->scan_ticket, 64) == hipSuccess &&
+              hipMalloc(&c->scan_ticket, 128) == hipSuccess &&
               hipMalloc(&c->batches_run, 64) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->vars_ring), sizeof(BatchVars) * kVarsRing,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
-              hipMalloc(&c->clock, sizeof(uint64_t) * 4 * kGatherMaxBlocks) == hipSuccess &&
-              hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 4,
+              hipMalloc(&c->clock, sizeof(uint64_t) * 2 * kMaxRoleBlocks * kMaxStampRoles) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 2 * kMaxStampRoles,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
     ok = ok && c->err && c->cnt && c->vars && c->scan_ticket && c->batches_run && c->vars_ring && c->clock && c->clock_host;
     ok = ok && noalloc_init(device) == HELIOS_OK;      // address of this device's static scratch (helios_dedup_noalloc)
@@ -289,8 +553,9 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;
         c->err[0] = c->err[1] = 0;
+        c->err_now = c->err;
         ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
-             hipMemsetAsync(c->scan_ticket, 0, 64, c->stream) == hipSuccess &&
+             hipMemsetAsync(c->scan_ticket, 0, 128, c->stream) == hipSuccess &&
              hipMemsetAsync(c->batches_run, 0, 64, c->stream) == hipSuccess &&
              hipStreamSynchronize(c->stream) == hipSuccess;
     }
@@ -308,20 +573,21 @@ int helios_destroy(helios_ctx* c) {
         return fail(c, HELIOS_ESTATE, "%d plan(s) / miss queue(s) of this context are still alive; destroy them first", c->n_children);
     DeviceGuard guard(c->device);
     (void)hipStreamSynchronize(c->stream);
-    if (c->aux) (void)hipStreamSynchronize(c->aux);
     free_scratch(c);
     (void)hipFree(c->rank);
     (void)hipFree(c->cnt);
     (void)hipFree(c->vars);
     (void)hipFree(c->scan_ticket);
     (void)hipFree(c->batches_run);
+    (void)hipFree(c->hot_temp);
+    (void)hipFree(c->hot_ids);
+    (void)hipFree(c->hot_counts);
     if (c->vars_ring) (void)hipHostFree(c->vars_ring);
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
     if (c->err) (void)hipHostFree(c->err);
-    for (hipEvent_t e : {c->ev_fork, c->ev_join, c->t_hbm[0], c->t_hbm[1], c->t_host[0], c->t_host[1]})
+    for (hipEvent_t e : {c->t_hbm[0], c->t_hbm[1], c->t_host[0], c->t_host[1]})
         if (e) (void)hipEventDestroy(e);
-    if (c->aux) (void)hipStreamDestroy(c->aux);
     delete c;
     return HELIOS_OK;
 }
@@ -334,24 +600,17 @@ int helios_reserve(helios_ctx* c, int64_t max_ids) {
     return ensure_capacity(c, max_ids);
 }
 
-// the device-side error word: reports and clears what kernels have recorded since the last check
-static int check_device_error(helios_ctx* c) {
-    const int code = *reinterpret_cast<volatile int32_t*>(c->err);
-    if (code != 0) {
-        c->err[0] = 0;
-        return fail(c, code, code == HELIOS_ECAPACITY ? "an output did not fit its capacity"
-                             : code == HELIOS_EINTERNAL ? "a workgroup gave up waiting (chained scan, or a miss queue that stopped answering)"
-                             : "a node ID outside [0, n_nodes), or an order that is not a permutation");
-    }
-    return HELIOS_OK;
-}
-
 int helios_sync(helios_ctx* c) {
     if (!c) return HELIOS_EINVAL;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->vars_unsynced = 0;
-    return check_device_error(c);
+    int rc = check_error_word(c, c->err);
+    for (helios_plan* pl : c->plans) {           // every batch launched on the context has finished: its errors count
+        const int rp = check_error_word(c, pl->err);
+        if (rc == HELIOS_OK) rc = rp;
+    }
+    return rc;
 }
 
 int helios_csr_load(helios_ctx* c, int64_t n_nodes, int64_t n_edges, const int64_t* offsets, const int32_t* indices) {
@@ -361,7 +620,9 @@ int helios_csr_load(helios_ctx* c, int64_t n_nodes, int64_t n_edges, const int64
     c->g = CsrView{offsets, indices, n_nodes};
     c->n_edges = n_edges;
     c->has_graph = true;
+    c->graph_generation += 1;
     c->has_cache = false;              // the cache map belongs to the graph it was built for
+    c->blocks_ready = false;
     return HELIOS_OK;
 }
 
@@ -406,8 +667,9 @@ int helios_cache_fill(helios_ctx* c, const void* src_table, const int32_t* order
     if (n_rows == 0) return HELIOS_OK;
     if (!src_table || !order || !dst) return fail(c, HELIOS_EINVAL, "NULL pointer");
     DeviceGuard guard(c->device);
-    HIP_TRY(c, launch_gather_rows(c->stream, src_table, nullptr, order + first_rank, Count{nullptr, n_rows}, n_rows,
-                                  row_bytes, dst, false, nullptr, nullptr, 0));
+    const GatherArgs a{static_cast<const chunk16*>(src_table), nullptr, order + first_rank, nullptr, Count{nullptr, n_rows},
+                       row_bytes / 16, static_cast<chunk16*>(dst), -1, -1, c->err, Stamps{nullptr}};
+    HIP_TRY(c, launch_gather_rows(c->stream, a, n_rows, false, false, 0, nullptr, nullptr, nullptr));
     return HELIOS_OK;
 }
 
@@ -422,7 +684,7 @@ int helios_sample(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const in
     DeviceGuard guard(c->device);
     rc = ensure_capacity(c, p.ids_max);
     if (rc) return rc;
-    return sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, 0);
+    return run_pipeline(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, nullptr);
 }
 
 int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* unique, int64_t unique_cap,
@@ -434,18 +696,38 @@ int helios_dedup(helios_ctx* c, const int32_t* ids, int64_t n_ids, int32_t* uniq
     DeviceGuard guard(c->device);
     int rc = ensure_capacity(c, n_ids);
     if (rc) return rc;
-    ScanState scan;
-    rc = next_scan(c, &scan);
+    // the table that the context's next batch would use: not one that helios_make_blocks may still need
+    const uint32_t which = static_cast<uint32_t>(c->batch_seq % kBatchTables);
+    rc = clean_for_call(c, static_cast<int>(which));
     if (rc) return rc;
-    DedupScratch s = c->dd;
-    s.n_slots = dedup_slots(c, n_ids);
-    c->blocks_ready = false;
-    c->last_slots = s.n_slots;
+    uint32_t epoch;
+    rc = next_epoch(c, &epoch);
+    if (rc) return rc;
+    const DedupScratch s{batch_table(c, which), dedup_slots(c, n_ids), c->batch_slot_of, batch_iof(c, which)};
+    c->batch_dirty[which] = s.n_slots;
     const Count n{nullptr, n_ids};
-    HIP_TRY(c, launch_dedup_insert(c->stream, ids, n, n_ids, c->g.n_nodes, s, false, c->err));
-    HIP_TRY(c, launch_dedup_compact(c->stream, ids, one_segment(n), n_ids, c->cnt + kCntCat, s, unique, unique_cap,
-                                    c->cnt + kCntUnique, n_unique, nullptr, nullptr, scan, c->err));
-    if (inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, c->cnt + kCntCat, n_ids, s, inverse));
+    HIP_TRY(c, launch_dedup_insert(c->stream, ids, n, n_ids, c->g.n_nodes, s, c->err));
+    CompactArgs a{};
+    a.ids = ids;
+    a.lens.n_seg = 1;
+    a.lens.first_here = 0;
+    a.lens.len[0] = n;
+    a.n_max = n_ids;
+    a.n_total_dev = c->cnt + kCntCat;
+    a.s = s;
+    a.unique = unique;
+    a.unique_cap = unique_cap;
+    a.last = true;
+    a.n_unique_dev = c->cnt + kCntUnique;
+    a.n_unique_out = n_unique;
+    a.scan = scan_state(c, epoch, kScanRowsLook);
+    a.err = c->err;
+    HIP_TRY(c, launch_dedup_compact_plain(c->stream, a, n_ids));
+    if (inverse) {
+        const InverseArgs inv{Count{c->cnt + kCntCat, n_ids}, s, BatchTables{nullptr, 0, nullptr, 0, 0, nullptr, 0}, nullptr, inverse,
+                              Stamps{nullptr}};
+        HIP_TRY(c, launch_dedup_inverse(c->stream, inv, n_ids));
+    }
     return HELIOS_OK;
 }
 
@@ -459,74 +741,33 @@ int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, i
     DeviceGuard guard(c->device);
     int rc = ensure_capacity(c, n_ids);
     if (rc) return rc;
-    return gather_impl(c, ids, Count{nullptr, n_ids}, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
+    reset_stamps(c);
+    uint32_t epoch;
+    rc = next_epoch(c, &epoch);
+    if (rc) return rc;
+    const TierLists lists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier};
+    HIP_TRY(c, launch_lookup_partition(c->stream, ids, Count{nullptr, n_ids}, n_ids, c->rank, c->g.n_nodes, c->n_hbm, c->n_host,
+                                       lists, miss_pos, miss_id, miss_slot, miss_cap, reinterpret_cast<int64_t*>(stats),
+                                       scan_state(c, epoch, kScanRowsLook), c->err));
+    rc = copy_tiers_split(c, n_ids, out);
+    if (rc) return rc;
+    return publish_stamps(c);
 }
 
 int helios_gather_miss(helios_ctx* c, const int32_t* miss_pos, const int32_t* miss_slot, int64_t n_miss_max,
-                       const int64_t* n_miss_dev, void* out) {
+                       const int64_t* n_miss_dev, void* out, int64_t out_rows) {
     if (!c) return HELIOS_EINVAL;
     if (!c->has_cache) return fail(c, HELIOS_ESTATE, "helios_gather_miss before helios_cache_build");
-    if (n_miss_max < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (n_miss_max < 0 || out_rows < 0) return fail(c, HELIOS_EINVAL, "negative size");
     if (n_miss_max == 0) return HELIOS_OK;
     if (!miss_pos || !miss_slot || !out) return fail(c, HELIOS_EINVAL, "NULL pointer");
-    if (c->n_hbm + c->n_host >= c->g.n_nodes) return HELIOS_OK;      // every node is cached: nothing can miss
-    if (!c->standin_table) return fail(c, HELIOS_ESTATE, "no stand-in table was given to helios_cache_build");
+    const int64_t standin_rows = c->g.n_nodes - c->n_hbm - c->n_host;
+    if (standin_rows > 0 && !c->standin_table) return fail(c, HELIOS_ESTATE, "no stand-in table was given to helios_cache_build");
     DeviceGuard guard(c->device);
-    HIP_TRY(c, launch_gather_rows(c->stream, c->standin_table, miss_pos, miss_slot, Count{n_miss_dev, n_miss_max},
-                                  n_miss_max, c->row_bytes, out, true, nullptr, nullptr, c->host_blocks));
-    return HELIOS_OK;
-}
-
-static int prepare_batch_impl(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
-                         uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, int32_t* unique,
-                         int64_t unique_cap, int32_t* inverse, int64_t* n_unique, void* out, int32_t* miss_pos,
-                         int32_t* miss_id, int32_t* miss_slot, int64_t miss_cap, helios_gather_stats* stats) {
-    if (!c) return HELIOS_EINVAL;
-    if (!c->has_graph || !c->has_cache) return fail(c, HELIOS_ESTATE, "helios_prepare_batch needs the graph and the cache");
-    HopPlan p;
-    int rc = plan_hops(c, n_seeds, fanouts, n_hops, hops, &p);
-    if (rc) return rc;
-    if (n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
-    if (unique_cap < 0 || miss_cap < 0) return fail(c, HELIOS_EINVAL, "negative size");
-    if (unique_cap > 0 && (!unique || !out)) return fail(c, HELIOS_EINVAL, "NULL pointer");
-    if (miss_cap > 0 && (!miss_pos || !miss_id || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL miss list");
-    rc = ensure_capacity(c, p.ids_max);
-    if (rc) return rc;
-    const int64_t batch_max = p.cat_max > 0 ? p.cat_max : 1;
-    rc = sample_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, p, batch_max);
-    if (rc) return rc;
-    SegLens lens{};
-    lens.n_seg = n_hops + 1;
-    lens.len[0] = Count{nullptr, n_seeds};
-    for (int h = 0; h < n_hops; ++h) lens.len[h + 1] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
-    // the sampling passes have filled the table; the compaction classifies the unique IDs by cache tier on the way
-    LookupOut look{c->rank, c->n_hbm, c->n_host, tier_lists(c), miss_pos, miss_id, miss_slot, miss_cap,
-                   reinterpret_cast<int64_t*>(stats)};
-    ScanState scan;
-    rc = next_scan(c, &scan);
-    if (rc) return rc;
-    DedupScratch s = c->dd;
-    s.n_slots = dedup_slots(c, batch_max);
-    c->last_slots = s.n_slots;
-    HIP_TRY(c, launch_dedup_compact(c->stream, c->cat, lens, p.cat_max, c->cnt + kCntCat, s, unique, unique_cap,
-                                    c->cnt + kCntUnique, n_unique, nullptr, &look, scan, c->err));
-    const int64_t u_max = p.cat_max < unique_cap ? p.cat_max : unique_cap;
-    if (c->missq) {                 // the misses are on their way while the cached tiers are copied
-        const int64_t m_max = miss_cap < u_max ? miss_cap : u_max;
-        rc = missq_submit_from_batch(c, miss_pos, miss_slot, Count{c->cnt + kCntTier + 2, m_max}, m_max);
-        if (rc) return rc;
-    }
-    c->blocks_ready = true;
-    c->last_n_seeds = n_seeds;
-    c->last_n_hops = n_hops;
-    for (int h = 0; h < n_hops; ++h) {
-        c->last_frontier_max[h] = p.frontier_max[h];
-        c->last_flat_max[h] = p.flat_max[h];
-    }
-    rc = copy_tiers(c, Count{c->cnt + kCntUnique, u_max}, out);
-    if (rc) return rc;
-    // last, so that the row copies (and with them the host link) start one launch earlier
-    if (inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, c->cnt + kCntCat, p.cat_max, s, inverse));
+    // (with every node cached nothing can miss: any entry is then reported by the kernel as outside its table)
+    const GatherArgs a{static_cast<const chunk16*>(c->standin_table), miss_pos, miss_slot, nullptr, Count{n_miss_dev, n_miss_max},
+                       c->row_bytes / 16, static_cast<chunk16*>(out), standin_rows, out_rows, c->err, Stamps{nullptr}};
+    HIP_TRY(c, launch_gather_rows(c->stream, a, n_miss_max, true, true, c->host_blocks, nullptr, nullptr, nullptr));
     return HELIOS_OK;
 }
 
@@ -539,22 +780,6 @@ int helios_prepare_batch(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, c
     return prepare_batch_impl(c, seeds, n_seeds, fanouts, n_hops, rng_seed, hops, sizes, unique, unique_cap, inverse,
                               n_unique, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
 }
-
-struct helios_plan {
-    helios_ctx* ctx = nullptr;
-    hipGraph_t graph = nullptr;
-    hipGraphExec_t exec = nullptr;
-    uint32_t n_scans = 0;
-    uint64_t scratch_generation = 0;
-    int64_t n_seeds = 0;
-    int32_t n_hops = 0;
-    int64_t frontier_max[HELIOS_MAX_HOPS] = {0};
-    int64_t flat_max[HELIOS_MAX_HOPS] = {0};
-    uint32_t slots = 0;
-    helios_missq* missq = nullptr;     // the queue attached when the batch was recorded
-    hipEvent_t done = nullptr;         // recorded behind every launch
-    uint64_t launch_seq = 0;           // the context's launch count at this plan's last launch
-};
 
 int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                        const helios_hop_out* hops, int64_t* sizes, int32_t* unique, int64_t unique_cap,
@@ -574,39 +799,58 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     helios_plan* pl = new helios_plan();
     pl->ctx = c;
+    if (hipHostMalloc(reinterpret_cast<void**>(&pl->err), 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess || !pl->err) {
+        (void)hipGetLastError();
+        delete pl;
+        return fail(c, HELIOS_EHIP, "helios_plan_create: no pinned memory for the plan's error word");
+    }
+    pl->err[0] = pl->err[1] = 0;
     c->recording = true;
     c->rec_scans = 0;
+    c->err_now = pl->err;
+    const bool was_ready = c->blocks_ready;
     hipError_t e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal);
     if (e == hipSuccess) {
-        // the seeds pointer and rng_seed passed here are placeholders: recorded kernels read both from c->vars
+        // the seeds pointer and rng_seed passed here are placeholders: recorded kernels read both from the batch's variables
         rc = prepare_batch_impl(c, reinterpret_cast<const int32_t*>(c->vars), n_seeds, fanouts, n_hops, 0, hops, sizes,
                                 unique, unique_cap, inverse, n_unique, out, miss_pos, miss_id, miss_slot, miss_cap, stats);
         hipError_t e2 = hipStreamEndCapture(c->stream, &pl->graph);
         if (rc == HELIOS_OK && e2 != hipSuccess) e = e2;
     }
     c->recording = false;
+    c->err_now = c->err;
+    c->blocks_ready = was_ready;                 // nothing has run
     pl->n_scans = c->rec_scans;
     if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&pl->exec, pl->graph, nullptr, nullptr, 0);
     if (e == hipSuccess && rc == HELIOS_OK) e = hipEventCreateWithFlags(&pl->done, hipEventDisableTiming);
     if (e != hipSuccess || rc != HELIOS_OK) {
         if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
         if (pl->graph) (void)hipGraphDestroy(pl->graph);
+        (void)hipHostFree(pl->err);
         delete pl;
-        c->blocks_ready = false;
         if (rc != HELIOS_OK) return rc;
         return fail(c, HELIOS_EHIP, "recording the batch failed: %s", hipGetErrorString(e));
     }
     pl->scratch_generation = c->scratch_generation;
+    pl->cache_generation = c->cache_generation;
+    pl->graph_generation = c->graph_generation;
     pl->n_seeds = n_seeds;
     pl->n_hops = n_hops;
     for (int h = 0; h < n_hops; ++h) {
         pl->frontier_max[h] = p.frontier_max[h];
         pl->flat_max[h] = p.flat_max[h];
+        pl->hops[h] = hops[h];
     }
+    pl->sizes = sizes;
     pl->slots = c->last_slots;
+    pl->clear_slots = c->rec_clear_slots;
     pl->missq = c->missq;
-    c->blocks_ready = false;                     // nothing has run yet
+    pl->n_stamps = c->n_stamps;
+    pl->stamp_table = c->stamp_table;
+    for (int q = 0; q < c->n_stamps; ++q) pl->stamp_roles[q] = c->stamp_roles[q];
+    reset_stamps(c);
     c->n_children += 1;
+    c->plans.push_back(pl);
     *plan_out = pl;
     return HELIOS_OK;
 }
@@ -617,27 +861,41 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     if (pl->n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
     if (pl->scratch_generation != c->scratch_generation)
         return fail(c, HELIOS_ESTATE, "the context's scratch was regrown after the batch was recorded; record it again");
+    if (pl->graph_generation != c->graph_generation || pl->cache_generation != c->cache_generation || !c->has_cache)
+        return fail(c, HELIOS_ESTATE, "helios_csr_load / helios_cache_build was called after the batch was recorded; record it again");
     if (pl->missq != c->missq)
         return fail(c, HELIOS_ESTATE, "the miss queue attached to the context is not the one the batch was recorded with");
     DeviceGuard guard(c->device);
     uint32_t io_round = 0;
     if (pl->missq) {
-        int rc = missq_open_round(c, pl->missq, &io_round);
+        int rc = missq_next_round(c, pl->missq, &io_round);      // opened below, once the launch has succeeded
         if (rc) return rc;
     }
     if (c->epoch + pl->n_scans >= (1u << 30) - 64) {
-        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * 3 * c->scan_stride, c->stream));
+        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * kScanRows * c->scan_stride, c->stream));
         c->epoch = 0;
     }
     if (c->vars_unsynced + 1 >= kVarsRing) {     // the ring slot about to be reused may still be in flight
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         c->vars_unsynced = 0;
     }
+    // The recording assumes that its own batch table and both hop tables are empty, and it empties clear_slots slots
+    // of the next batch's table.  What that leaves out is emptied here, by launches of their own (rare: only when
+    // batches of different sizes, or direct and recorded calls, alternate on a context).
+    const uint32_t which = static_cast<uint32_t>(c->batch_seq % kBatchTables), next = (which + 1) % kBatchTables;
+    int rc = clean_for_call(c, static_cast<int>(which));
+    if (rc) return rc;
+    if (c->batch_dirty[next] > pl->clear_slots) {
+        HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, next), c->batch_dirty[next]}));
+        c->batch_dirty[next] = 0;
+    }
     BatchVars* slot = c->vars_ring + (c->vars_next % kVarsRing);
     slot->rng_seed = rng_seed;
     slot->seeds = seeds;
     slot->epoch_base = c->epoch;
     slot->io_round = io_round;
+    slot->table = which;
+    slot->reserved = 0;
     __atomic_thread_fence(__ATOMIC_RELEASE);     // the slot is written before the launch is rung in
     HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
     // only a batch that was launched takes its slot: the device counts the batches it runs, and the two
@@ -645,10 +903,16 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
     c->vars_next += 1;
     c->vars_unsynced += 1;
     c->epoch += pl->n_scans;
+    if (pl->missq) missq_commit_round(pl->missq, io_round);
+    c->batch_dirty[which] = pl->slots;
+    c->batch_dirty[next] = 0;
+    c->batch_seq += 1;
+    pl->batch_seq = c->batch_seq;
     HIP_TRY(c, hipEventRecord(pl->done, c->stream));
     c->launch_seq += 1;
     pl->launch_seq = c->launch_seq;
     c->blocks_ready = true;
+    c->last_table = which;
     c->last_slots = pl->slots;
     c->last_n_seeds = pl->n_seeds;
     c->last_n_hops = pl->n_hops;
@@ -656,8 +920,10 @@ int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed)
         c->last_frontier_max[h] = pl->frontier_max[h];
         c->last_flat_max[h] = pl->flat_max[h];
     }
-    c->timed_hbm = c->timing != 0 && c->n_hbm > 0 && pl->n_seeds > 0;
-    c->timed_host = c->timing != 0 && c->n_host > 0 && pl->n_seeds > 0;
+    c->n_stamps = pl->n_stamps;
+    c->stamp_table = pl->stamp_table;
+    for (int q = 0; q < pl->n_stamps; ++q) c->stamp_roles[q] = pl->stamp_roles[q];
+    c->timed_events = false;
     return HELIOS_OK;
 }
 
@@ -670,19 +936,22 @@ int helios_plan_wait(helios_plan* pl) {
     // everything launched on the context up to this plan's launch has finished
     const uint64_t later = c->launch_seq - pl->launch_seq;
     if (later < c->vars_unsynced) c->vars_unsynced = static_cast<uint32_t>(later);
-    return check_device_error(c);
+    return check_error_word(c, pl->err);                 // the errors of this plan's batches, not of others queued behind them
 }
 
 int helios_plan_destroy(helios_plan* pl) {
     if (!pl) return HELIOS_EINVAL;
     if (pl->ctx) {
-        DeviceGuard guard(pl->ctx->device);
-        (void)hipStreamSynchronize(pl->ctx->stream);
-        pl->ctx->n_children -= 1;
+        helios_ctx* c = pl->ctx;
+        DeviceGuard guard(c->device);
+        (void)hipStreamSynchronize(c->stream);
+        c->n_children -= 1;
+        c->plans.erase(std::remove(c->plans.begin(), c->plans.end(), pl), c->plans.end());
     }
     if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
     if (pl->graph) (void)hipGraphDestroy(pl->graph);
     if (pl->done) (void)hipEventDestroy(pl->done);
+    if (pl->err) (void)hipHostFree(pl->err);
     delete pl;
     return HELIOS_OK;
 }
@@ -692,16 +961,26 @@ int helios_make_blocks(helios_ctx* c, const helios_hop_out* hops, int32_t n_hops
     if (!c->blocks_ready) return fail(c, HELIOS_ESTATE, "helios_make_blocks must follow helios_prepare_batch on this context");
     if (!hops || !blocks || n_hops != c->last_n_hops) return fail(c, HELIOS_EINVAL, "hops / blocks do not match the last batch");
     DeviceGuard guard(c->device);
-    DedupScratch s = c->dd;
-    s.n_slots = c->last_slots;
-    for (int h = 0; h < n_hops; ++h) {
-        if (!blocks[h].row_local || !blocks[h].col_local) return fail(c, HELIOS_EINVAL, "hop %d: NULL block buffer", h);
-        const Count nf = h == 0 ? Count{nullptr, c->last_n_seeds} : Count{c->cnt + kCntFrontier + h, c->last_frontier_max[h]};
-        HIP_TRY(c, launch_local_ids(c->stream, hops[h].frontier, nf, c->last_frontier_max[h], s, blocks[h].row_local, c->err));
-        HIP_TRY(c, launch_local_ids(c->stream, hops[h].flat, Count{c->cnt + kCntFlat + h, c->last_flat_max[h]},
-                                    c->last_flat_max[h], s, blocks[h].col_local, c->err));
-    }
-    return HELIOS_OK;
+    return make_blocks_impl(c, c->last_table, c->last_slots, c->last_n_seeds, n_hops, c->last_frontier_max, c->last_flat_max,
+                            nullptr, hops, blocks, c->err);
+}
+
+int helios_plan_make_blocks(helios_plan* pl, const helios_block_out* blocks) {
+    if (!pl || !pl->ctx) return HELIOS_EINVAL;
+    helios_ctx* c = pl->ctx;
+    if (!blocks) return fail(c, HELIOS_EINVAL, "blocks is NULL");
+    if (pl->launch_seq == 0) return fail(c, HELIOS_ESTATE, "the plan has not been launched");
+    if (pl->scratch_generation != c->scratch_generation) return fail(c, HELIOS_ESTATE, "the context's scratch was regrown since");
+    // the plan's batch was number batch_seq - 1 of the context; its table is kept until the second batch after it
+    // is launched (that one empties it for the third)
+    const uint32_t table = static_cast<uint32_t>((pl->batch_seq - 1) % kBatchTables);
+    if (c->batch_seq - pl->batch_seq > 1 || c->batch_dirty[table] < pl->slots)
+        return fail(c, HELIOS_ESTATE, "two or more batches were launched on the context since this plan's: its table is gone");
+    if (!pl->sizes && c->batch_seq != pl->batch_seq)
+        return fail(c, HELIOS_ESTATE, "a plan recorded without a size array can only make blocks right after its launch");
+    DeviceGuard guard(c->device);
+    return make_blocks_impl(c, table, pl->slots, pl->n_seeds, pl->n_hops, pl->frontier_max, pl->flat_max, pl->sizes, pl->hops,
+                            blocks, pl->err);
 }
 
 int helios_hotness_add(helios_ctx* c, const int32_t* ids, int64_t n_max, const int64_t* n_dev, int32_t* counts) {
@@ -722,18 +1001,24 @@ int helios_hotness_order(helios_ctx* c, const int32_t* counts, int32_t* order) {
     if (n == 0) return HELIOS_OK;
     if (!counts || !order) return fail(c, HELIOS_EINVAL, "NULL pointer");
     DeviceGuard guard(c->device);
+    // scratch of the sort: allocated on the first call for a graph of this size, kept until the context is destroyed
     const size_t temp_bytes = hotness_order_temp_bytes(n);
-    void* temp = nullptr;
-    int32_t *ids_in = nullptr, *counts_sorted = nullptr;
-    HIP_TRY(c, hipMalloc(&temp, temp_bytes ? temp_bytes : 16));
-    hipError_t e = hipMalloc(&ids_in, sizeof(int32_t) * n);
-    if (e == hipSuccess) e = hipMalloc(&counts_sorted, sizeof(int32_t) * n);
-    if (e == hipSuccess) e = launch_hotness_order(c->stream, counts, n, ids_in, counts_sorted, order, temp, temp_bytes);
-    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);     // the scratch is freed below
-    (void)hipFree(temp);
-    (void)hipFree(ids_in);
-    (void)hipFree(counts_sorted);
-    if (e != hipSuccess) return fail(c, HELIOS_EHIP, "helios_hotness_order: %s", hipGetErrorString(e));
+    if (n > c->hot_cap || temp_bytes > c->hot_temp_bytes) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        (void)hipFree(c->hot_temp);
+        (void)hipFree(c->hot_ids);
+        (void)hipFree(c->hot_counts);
+        c->hot_temp = nullptr;
+        c->hot_ids = c->hot_counts = nullptr;
+        c->hot_cap = 0;
+        c->hot_temp_bytes = 0;
+        HIP_TRY(c, hipMalloc(&c->hot_temp, temp_bytes ? temp_bytes : 16));
+        HIP_TRY(c, hipMalloc(&c->hot_ids, sizeof(int32_t) * n));
+        HIP_TRY(c, hipMalloc(&c->hot_counts, sizeof(int32_t) * n));
+        c->hot_cap = n;
+        c->hot_temp_bytes = temp_bytes;
+    }
+    HIP_TRY(c, launch_hotness_order(c->stream, counts, n, c->hot_ids, c->hot_counts, order, c->hot_temp, c->hot_temp_bytes));
     return HELIOS_OK;
 }
 
@@ -764,13 +1049,13 @@ int helios_set_param(helios_ctx* c, int param, int64_t value) {
     if (value < 0) return fail(c, HELIOS_EINVAL, "helios_set_param: negative value");
     switch (param) {
         case HELIOS_PARAM_HBM_GATHER_BLOCKS:
-            c->hbm_blocks = static_cast<unsigned>(value > kGatherMaxBlocks ? kGatherMaxBlocks : value);
+            c->hbm_blocks = static_cast<unsigned>(value > kMaxRoleBlocks ? kMaxRoleBlocks : value);
             return HELIOS_OK;
         case HELIOS_PARAM_HOST_GATHER_BLOCKS:
-            c->host_blocks = static_cast<unsigned>(value > kGatherMaxBlocks ? kGatherMaxBlocks : value);
+            c->host_blocks = static_cast<unsigned>(value > kMaxRoleBlocks ? kMaxRoleBlocks : value);
             return HELIOS_OK;
-        case HELIOS_PARAM_SERIAL_TIERS:
-            c->serial_tiers = value != 0;
+        case HELIOS_PARAM_SPLIT_COPIES:
+            c->split_copies = value != 0;
             return HELIOS_OK;
         case HELIOS_PARAM_MISSQ_TIMEOUT_US:
             c->missq_timeout_us = value < 1 ? 1 : value > 60000000 ? 60000000 : value;
@@ -783,10 +1068,30 @@ int helios_set_param(helios_ctx* c, int param, int64_t value) {
     }
 }
 
-int helios_set_timing(helios_ctx* c, int enabled) {
+int helios_set_timing(helios_ctx* c, int level) {
     if (!c) return HELIOS_EINVAL;
-    c->timing = enabled < 0 ? 0 : enabled > 2 ? 2 : enabled;
-    c->timed_hbm = c->timed_host = false;
+    c->timing = level < 0 ? 0 : level > 2 ? 2 : level;
+    reset_stamps(c);
+    return HELIOS_OK;
+}
+
+int helios_batch_ticks(helios_ctx* c, helios_role_ticks* out, int32_t cap, int32_t* n_out, double* ticks_per_us) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !out)) return HELIOS_EINVAL;
+    DeviceGuard guard(c->device);
+    *n_out = 0;
+    if (ticks_per_us) *ticks_per_us = c->clock_khz / 1000.0;
+    if (c->n_stamps == 0) return HELIOS_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));          // the publish kernel has written the pinned words
+    for (int q = 0; q < c->n_stamps && *n_out < cap; ++q) {
+        const volatile uint64_t* k = c->clock_host + 2 * q;
+        helios_role_ticks& r = out[(*n_out)++];
+        const bool ok = k[0] != ~0ull && k[1] >= k[0];
+        r.kind = c->stamp_roles[q].kind;
+        r.stage = c->stamp_roles[q].stage;
+        r.workgroups = c->stamp_roles[q].workgroups;
+        r.start = ok ? k[0] : 0;
+        r.end = ok ? k[1] : 0;
+    }
     return HELIOS_OK;
 }
 
@@ -796,36 +1101,20 @@ int helios_gather_times(helios_ctx* c, float* hbm_ms, float* host_ms, float* hbm
     *hbm_ms = *host_ms = 0.f;
     if (hbm_event_ms) *hbm_event_ms = 0.f;
     if (host_event_ms) *host_event_ms = 0.f;
-    if (!c->timed_hbm && !c->timed_host) return HELIOS_OK;
-    HIP_TRY(c, hipStreamSynchronize(c->stream));          // the publish kernels have written the pinned words
-    for (int t = 0; t < 2; ++t) {
-        if (!(t == 0 ? c->timed_hbm : c->timed_host)) continue;
-        const volatile uint64_t* k = c->clock_host + 2 * t;
-        const uint64_t lo = k[0], hi = k[1];
-        const float ms = hi >= lo && lo != ~0ull ? static_cast<float>(static_cast<double>(hi - lo) / c->clock_khz) : 0.f;
-        float ev = 0.f;
-        if (c->timing > 1)
-            HIP_TRY(c, hipEventElapsedTime(&ev, t == 0 ? c->t_hbm[0] : c->t_host[0], t == 0 ? c->t_hbm[1] : c->t_host[1]));
-        if (t == 0) { *hbm_ms = ms; if (hbm_event_ms) *hbm_event_ms = ev; }
-        else { *host_ms = ms; if (host_event_ms) *host_event_ms = ev; }
-    }
-    return HELIOS_OK;
-}
-
-int helios_gather_ticks(helios_ctx* c, uint64_t* ticks4, double* ticks_per_us) {
-    if (!c || !ticks4) return HELIOS_EINVAL;
-    DeviceGuard guard(c->device);
-    for (int i = 0; i < 4; ++i) ticks4[i] = 0;
-    if (ticks_per_us) *ticks_per_us = c->clock_khz / 1000.0;
-    if (!c->timed_hbm && !c->timed_host) return HELIOS_OK;
+    if (c->n_stamps == 0 && !c->timed_events) return HELIOS_OK;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    for (int t = 0; t < 2; ++t) {
-        if (!(t == 0 ? c->timed_hbm : c->timed_host)) continue;
-        const volatile uint64_t* k = c->clock_host + 2 * t;
-        if (k[0] != ~0ull && k[1] >= k[0]) {
-            ticks4[2 * t] = k[0];
-            ticks4[2 * t + 1] = k[1];
-        }
+    for (int q = 0; q < c->n_stamps; ++q) {
+        const volatile uint64_t* k = c->clock_host + 2 * q;
+        if (k[0] == ~0ull || k[1] < k[0]) continue;
+        const float ms = static_cast<float>(static_cast<double>(k[1] - k[0]) / c->clock_khz);
+        if (c->stamp_roles[q].kind == HELIOS_ROLE_COPY_HBM) *hbm_ms += ms;
+        if (c->stamp_roles[q].kind == HELIOS_ROLE_COPY_HOST) *host_ms += ms;
+    }
+    if (c->timed_events) {
+        float ev = 0.f;
+        if (c->n_hbm > 0 && hbm_event_ms && hipEventElapsedTime(&ev, c->t_hbm[0], c->t_hbm[1]) == hipSuccess) *hbm_event_ms = ev;
+        if (c->n_host > 0 && host_event_ms && hipEventElapsedTime(&ev, c->t_host[0], c->t_host[1]) == hipSuccess) *host_event_ms = ev;
+        (void)hipGetLastError();
     }
     return HELIOS_OK;
 }

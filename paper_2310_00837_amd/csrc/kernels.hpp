@@ -1,10 +1,12 @@
-// Host-side launchers of the Helios kernels (one per step of the path).
+// Host-side launchers of the Helios kernels.
 // Every launcher enqueues on `stream` and returns the hipError_t of the launch.
 #pragma once
 #include "common.hpp"
+#include "compact_dev.hpp"
+#include "gather_dev.hpp"
 #include "hashtable.hpp"
+#include "sample_dev.hpp"
 #include "scan.hpp"
-#define HELIOS_KERNELS_MAX_SEG 9
 
 namespace helios {
 
@@ -15,82 +17,49 @@ struct CsrView {
 };
 
 // ---- sample.hip
-// Count pass of hop 0: indptr[i] = start of frontier[i]'s samples in flat, indptr[n] = total
-// (also to *n_flat_dev); size_out (nullable, device-accessible) gets {n, total}.  frontier_out
-// (nullable, may equal frontier) receives a copy of the frontier; feed.ring (nullable): a recorded
-// batch, whose variables this kernel takes from the host's ring (the frontier is their seeds).  The later hops get their indptr from launch_dedup_compact.  clear_a / clear_b: tables
-// set to all ones on the way (those the sampling pass of hop 0 inserts into).
+// Count pass of hop 0 as a kernel of its own, for seed lists too long for the folded count of the
+// sampling pass: indptr[i] = start of frontier[i]'s samples in flat, indptr[n] = total (also to
+// *n_flat_dev); size_out (nullable, device-accessible) gets {n, total}.  frontier_out (nullable, may
+// equal frontier) receives a copy of the frontier; feed.ring (nullable): a recorded batch, whose
+// variables this kernel takes from the host's ring (the frontier is their seeds).
 hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int32_t* frontier, const BatchFeed& feed,
                                  int32_t* frontier_out, Count n, int64_t n_max, int32_t fanout, int64_t* indptr,
-                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, ClearJob clear_a, ClearJob clear_b,
-                                 const ScanState& scan, int32_t* err);
-// Sampling pass: flat[indptr[i] + k] = k-th sample of frontier[i].  vars (nullable) overrides
-// rng_seed.  Every sample is also inserted into hop_table (position = its place in flat) and into
-// batch_table (position = its place in [seeds | flat_0 | ...], which cat_out receives; with hop == 0
-// the frontier itself is inserted as the seeds; prev_flat = sizes of flat_0 .. flat_{hop-1}); either
-// table may be absent.  clear: a table set to all ones on the way (one that a later kernel fills).
-hipError_t launch_sample_hop(hipStream_t stream, const CsrView& g, const int32_t* frontier, const int64_t* indptr,
-                             Count n_frontier, int64_t n_frontier_max, int32_t fanout, int32_t hop, uint64_t rng_seed,
-                             const BatchVars* vars, int32_t* flat, int64_t flat_cap, ClearJob clear, InsertInto hop_table,
-                             InsertInto batch_table, int32_t* cat_out, int64_t n_seeds, const Count* prev_flat,
-                             uint32_t* batches_run /* nullable: hop 0 of a recorded batch advances it */, int32_t* err);
+                                 int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, const ScanState& scan, int32_t* err);
 
-// ---- dedup.hip
-struct DedupScratch {
-    unsigned long long* table;   // n_slots entries {id:32, first position:32}; all ones = empty
-    uint32_t n_slots;            // power of two
-    int32_t* slot_of;            // [n] table slot of every input position
-    int32_t* index_of_first;     // [n] index in `unique` of a first occurrence
+// ---- pipeline.hip: the launches of the sampling / whole-path pipeline; each carries one or more roles
+// Sampling pass of one hop (see sample_dev.hpp), and beside it, if link_blocks > 0, a row copy from a
+// source behind the host link (the cached rows that the stage before has just listed).
+hipError_t launch_sample(hipStream_t stream, const HopArgs& hop, unsigned hop_blocks, const GatherArgs& link, unsigned link_blocks);
+// Compaction pass(es) after a hop: the hop's samples into the next frontier (hop_blocks > 0) and the
+// stage of the batch's ID list that the hop has completed, with its cache lookup (look_blocks > 0).
+hipError_t launch_compact(hipStream_t stream, const CompactArgs& hop, unsigned hop_blocks, const CompactArgs& look,
+                          unsigned look_blocks);
+// The end of a batch in one launch: host-tier copy of the last stage, HBM-tier copy of all stages, the
+// inverse map, and the emptying of the table that the next batch of the context uses.  Any of the four
+// may be absent (0 workgroups).  With vars (a recorded batch) the table to empty is the one after the batch's
+// own among bt's, whatever clear.table says.
+hipError_t launch_finish(hipStream_t stream, const GatherArgs& hbm, unsigned hbm_blocks, const GatherArgs& link,
+                         unsigned link_blocks, const InverseArgs& inv, unsigned inv_blocks, const ClearJob& clear,
+                         unsigned clear_blocks, const BatchTables& bt, const BatchVars* vars);
+hipError_t launch_clear(hipStream_t stream, const ClearJob& job);
+// reduces the stamps of n_roles roles (role q: workgroups[q] workgroups, stamps at clock + offset[q]) to
+// {earliest start, latest end} pairs in pinned host memory
+constexpr int kMaxStampRoles = 48;
+struct StampTable {
+    uint32_t offset[kMaxStampRoles];
+    uint32_t workgroups[kMaxStampRoles];
 };
-// The lengths of up to HELIOS_KERNELS_MAX_SEG segments whose concatenation is de-duplicated (each may be
-// known only on the device).
-struct SegLens {
-    Count len[HELIOS_KERNELS_MAX_SEG];
-    int n_seg;
-};
-// What the de-duplication between two hops also computes for the hop that follows: the sample
-// counts min(deg, fanout) of the new frontier, scanned into indptr (indptr[n_unique] = total, also
-// to *n_flat_dev); size_out (nullable, device-accessible) gets {n_unique, total}.
-struct NextHopCount {
-    const int64_t* offsets;
-    int64_t n_nodes;
-    int32_t fanout;
-    int64_t* indptr;
-    int64_t flat_cap;
-    int64_t* n_flat_dev;
-    int64_t* size_out;
-};
-struct TierLists {
-    int32_t* pos[2];    // positions in the ID list, per cached tier (0 = HBM, 1 = host)
-    int32_t* slot[2];   // row in the tier table
-    int64_t* count;     // device int64[3]: tier 0, tier 1, misses
-};
-// What the batch's final de-duplication also computes: the cache lookup of the unique IDs (see
-// launch_lookup_partition, whose outputs these are, with positions = indices into `unique`).
-struct LookupOut {
-    const int32_t* rank;
-    int64_t n_hbm, n_host;
-    TierLists lists;
-    int32_t *miss_pos, *miss_id, *miss_slot;
-    int64_t miss_cap;
-    int64_t* stats_out;          // device-accessible int64[4], nullable
-};
-// First pass of a de-duplication as a kernel of its own (for IDs that no kernel of this library
-// produced): clears s.table unless table_is_clear, then inserts ids[0, n).
+hipError_t launch_clock_publish(hipStream_t stream, const uint64_t* clock, const StampTable& table, int n_roles,
+                                uint64_t* host_out);
+
+// ---- dedup.hip (the stand-alone de-duplication)
+// First pass as a kernel of its own (for IDs that no kernel of this library produced): inserts ids[0, n)
+// into s.table, which must be empty.
 hipError_t launch_dedup_insert(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
-                               const DedupScratch& s, bool table_is_clear, int32_t* err);
-// Second pass: the IDs ids[0, n), n = the sum of lens (n_max bounds it; *n_total_dev receives it), have
-// been inserted into s.table with their positions and s.slot_of is filled.  unique = the first
-// occurrences in input order (*n_unique_dev, *n_unique_out (nullable) = their number),
-// s.index_of_first[j] = index in unique of a first occurrence j.
-hipError_t launch_dedup_compact(hipStream_t stream, const int32_t* ids, const SegLens& lens, int64_t n_max,
-                                int64_t* n_total_dev, const DedupScratch& s, int32_t* unique, int64_t unique_cap,
-                                int64_t* n_unique_dev, int64_t* n_unique_out, const NextHopCount* next /* nullable */,
-                                const LookupOut* look /* nullable; not together with next */, const ScanState& scan,
-                                int32_t* err);
-// Third pass (optional): inverse[j] = index in unique of ids[j], for j < *n_total_dev.
-hipError_t launch_dedup_inverse(hipStream_t stream, const int64_t* n_total_dev, int64_t n_max, const DedupScratch& s,
-                                int32_t* inverse);
+                               const DedupScratch& s, int32_t* err);
+// Second pass over the whole list, and the optional third pass.
+hipError_t launch_dedup_compact_plain(hipStream_t stream, const CompactArgs& a, int64_t n_max);
+hipError_t launch_dedup_inverse(hipStream_t stream, const InverseArgs& a, int64_t n_max);
 
 // ---- cache.hip
 hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n_nodes, int32_t* rank, int32_t* err);
@@ -102,20 +71,16 @@ hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count
                                    const ScanState& scan, int32_t* err);
 
 // ---- gather.hip
-// out[pos[k], :] = table[slot[k], :] for k < n; pos == nullptr means pos[k] = k.
-// far_source selects the launch shape for a source behind the host link (few workgroups, one per CU).
-// clock (nullable): device uint64[2 * kGatherMaxBlocks]; workgroup b stores its first and last tick of
-// the constant-rate device clock at [b] and [blocks + b]; *blocks_out = workgroups launched.
-// launch_clock_publish reduces them to {earliest start, latest end} in pinned host memory.
-constexpr unsigned kGatherMaxBlocks = 8192;
-hipError_t launch_gather_rows(hipStream_t stream, const void* table, const int32_t* pos, const int32_t* slot,
-                              Count n, int64_t n_max, int32_t row_bytes, void* out, bool far_source,
-                              uint64_t* clock, unsigned* blocks_out, unsigned blocks_limit /* 0 = default */);
-hipError_t launch_clock_publish(hipStream_t stream, const uint64_t* clock, unsigned n_blocks, uint64_t* host_out);
+// The row copy as a kernel of its own.  far_source selects the launch shape for a source behind the host
+// link (few workgroups, one per CU).  With t_start / t_stop (nullable) the launch carries HIP events that
+// take the kernel's own begin and end, as a kernel trace reports them.  *blocks_out = workgroups launched.
+hipError_t launch_gather_rows(hipStream_t stream, const GatherArgs& a, int64_t n_max, bool far_source, bool standin,
+                              unsigned blocks_limit /* 0 = default */, hipEvent_t t_start, hipEvent_t t_stop,
+                              unsigned* blocks_out);
 
 // ---- blocks.hip
-// out[j] = index in the last de-duplication's unique list of ids[j] (s = the scratch that
-// de-duplication used, untouched since); an ID that is not in the list raises kErrData.
+// out[j] = index in a de-duplication's unique list of ids[j] (s = the scratch that de-duplication used,
+// untouched since); an ID that is not in the list raises kErrData.
 hipError_t launch_local_ids(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, const DedupScratch& s,
                             int32_t* out, int32_t* err);
 

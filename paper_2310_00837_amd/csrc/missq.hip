@@ -93,6 +93,7 @@ struct SubmitArgs {
     MissqView q;
     const int32_t* miss_pos;
     const int32_t* miss_slot;
+    int64_t standin_rows, out_rows;   // a command outside either is reported and served into nowhere
     Count n;
     uint32_t round;
     const BatchVars* vars;          // nullable: the round is vars->io_round (recorded batch)
@@ -109,14 +110,26 @@ __global__ __launch_bounds__(kBlock) void missq_submit_kernel(SubmitArgs a) {
         if (blockIdx.x == 0 && threadIdx.x == 0) raise(a.err, kErrCapacity);
         n = cap;
     }
+    if (n > 0 && a.standin_rows <= 0) {          // every node is cached: nothing can miss, the list is wrong
+        if (blockIdx.x == 0 && threadIdx.x == 0) raise(a.err, kErrData);
+        n = 0;
+    }
     const uint32_t round = a.vars ? a.vars->io_round : a.round;
     const int64_t per_q = (n + a.q.n_queues - 1) / a.q.n_queues;
     const int64_t step = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; j < n; j += step) {
         const int64_t q = j / per_q;
         const int64_t at = q * a.q.depth + (j - q * per_q);
-        a.q.cmd_pos[at] = a.miss_pos[j];
-        a.q.sq[at] = (static_cast<unsigned long long>(at) << 32) | static_cast<uint32_t>(a.miss_slot[j]);
+        int32_t pos = a.miss_pos[j], slot = a.miss_slot[j];
+        if (pos < 0 || pos >= a.out_rows || slot < 0 || slot >= a.standin_rows) {
+            // the caller's list is wrong here: the command still takes its place in the queue (the counts per queue
+            // are fixed), but it reads row 0 and its data goes nowhere
+            raise(a.err, kErrData);
+            pos = -1;
+            slot = 0;
+        }
+        a.q.cmd_pos[at] = pos;
+        a.q.sq[at] = (static_cast<unsigned long long>(at) << 32) | static_cast<uint32_t>(slot);
     }
     __threadfence_system();                    // the commands are in host memory before this workgroup counts as done
     __syncthreads();
@@ -203,8 +216,11 @@ __global__ __launch_bounds__(kBlock) void missq_complete_kernel(CompleteArgs a) 
                     dst[u] = -1;
                     if (valid && c_r < static_cast<uint32_t>(count)) {
                         const int64_t row = base + c_r;
-                        v[u] = __builtin_nontemporal_load(staging + row * a.chunks + piece);
-                        dst[u] = static_cast<int64_t>(a.q.cmd_pos[row]) * a.chunks + piece;
+                        const int64_t to = a.q.cmd_pos[row];       // negative: a command the submission refused
+                        if (to >= 0) {
+                            v[u] = __builtin_nontemporal_load(staging + row * a.chunks + piece);
+                            dst[u] = to * a.chunks + piece;
+                        }
                     }
                 }
 #pragma unroll
@@ -373,8 +389,8 @@ void announce(helios_missq* m) {
 }
 
 int launch_submit(helios_ctx* c, helios_missq* m, const int32_t* miss_pos, const int32_t* miss_slot, Count n,
-                  int64_t n_max, uint32_t round, const BatchVars* vars) {
-    SubmitArgs a{m->v, miss_pos, miss_slot, n, round, vars, c->err};
+                  int64_t n_max, int64_t out_rows, uint32_t round, const BatchVars* vars) {
+    SubmitArgs a{m->v, miss_pos, miss_slot, m->standin_rows, out_rows, n, round, vars, c->err_now};
     int64_t blocks = (n_max + kBlock * kCommandsPerThread - 1) / (kBlock * kCommandsPerThread);
     blocks = blocks < 1 ? 1 : blocks > 16 ? 16 : blocks;     // every workgroup ends with a system-scope fence and a ticket: few of them
     hipLaunchKernelGGL(missq_submit_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, c->stream, a);
@@ -390,27 +406,33 @@ bool missq_matches_cache(const helios_ctx* c, const helios_missq* q) {
     return q && q->ctx == c && c->has_cache && q->cache_generation == c->cache_generation;
 }
 
-int missq_open_round(helios_ctx* c, helios_missq* q, uint32_t* round_out) {
+
+int missq_next_round(helios_ctx* c, helios_missq* q, uint32_t* round_out) {
     if (!missq_matches_cache(c, q)) return fail(c, HELIOS_ESTATE, "the miss queue was made for another cache; create it again");
     if (q->open) return fail(c, HELIOS_ESTATE, "the previous round of the miss queue has not been completed (helios_missq_complete)");
-    q->round += 1;
-    q->open = true;
-    *round_out = q->round;
-    announce(q);
+    *round_out = q->round + 1;
     return HELIOS_OK;
 }
 
+void missq_commit_round(helios_missq* q, uint32_t round) {
+    q->round = round;
+    q->open = true;
+    announce(q);
+}
+
 int missq_submit_from_batch(helios_ctx* c, const int32_t* miss_pos, const int32_t* miss_slot, Count n_miss,
-                            int64_t n_miss_max) {
+                            int64_t n_miss_max, int64_t out_rows) {
     helios_missq* q = c->missq;
     if (c->recording) {             // the round is opened at every launch of the recording
         if (!missq_matches_cache(c, q)) return fail(c, HELIOS_ESTATE, "the miss queue was made for another cache; create it again");
-        return launch_submit(c, q, miss_pos, miss_slot, n_miss, n_miss_max, 0, c->vars);
+        return launch_submit(c, q, miss_pos, miss_slot, n_miss, n_miss_max, out_rows, 0, c->vars);
     }
     uint32_t round = 0;
-    int rc = missq_open_round(c, q, &round);
+    int rc = missq_next_round(c, q, &round);
     if (rc) return rc;
-    return launch_submit(c, q, miss_pos, miss_slot, n_miss, n_miss_max, round, nullptr);
+    rc = launch_submit(c, q, miss_pos, miss_slot, n_miss, n_miss_max, out_rows, round, nullptr);
+    if (rc == HELIOS_OK) missq_commit_round(q, round);
+    return rc;
 }
 
 }  // namespace helios
@@ -491,16 +513,18 @@ int helios_missq_attach(helios_ctx* c, helios_missq* m) {
 }
 
 int helios_missq_submit(helios_missq* m, const int32_t* miss_pos, const int32_t* miss_slot, int64_t n_miss_max,
-                        const int64_t* n_miss_dev) {
+                        const int64_t* n_miss_dev, int64_t out_rows) {
     if (!m) return HELIOS_EINVAL;
     helios_ctx* c = m->ctx;
-    if (n_miss_max < 0) return fail(c, HELIOS_EINVAL, "negative size");
+    if (n_miss_max < 0 || out_rows < 0) return fail(c, HELIOS_EINVAL, "negative size");
     if (n_miss_max > 0 && (!miss_pos || !miss_slot)) return fail(c, HELIOS_EINVAL, "NULL pointer");
     DeviceGuard guard(c->device);
     uint32_t round = 0;
-    int rc = missq_open_round(c, m, &round);
+    int rc = missq_next_round(c, m, &round);
     if (rc) return rc;
-    return launch_submit(c, m, miss_pos, miss_slot, Count{n_miss_dev, n_miss_max}, n_miss_max, round, nullptr);
+    rc = launch_submit(c, m, miss_pos, miss_slot, Count{n_miss_dev, n_miss_max}, n_miss_max, out_rows, round, nullptr);
+    if (rc == HELIOS_OK) missq_commit_round(m, round);
+    return rc;
 }
 
 int helios_missq_complete(helios_missq* m, void* out) {

@@ -100,12 +100,27 @@ extern "C" int helios_dedup_noalloc(helios_ctx* c, const int32_t* ids, int64_t n
     // call keeps a captured call replayable
     const ScanState scan{status, ticket, kStride, 1u, nullptr};
     const Count n{nullptr, n_ids};
-    SegLens lens{};
-    lens.n_seg = 1;
-    lens.len[0] = n;
-    HIP_TRY(c, launch_dedup_insert(c->stream, ids, n, n_ids, c->g.n_nodes, s, /*table_is_clear=*/true, c->err));
-    HIP_TRY(c, launch_dedup_compact(c->stream, ids, lens, n_ids, counters + 0, s, unique, unique_cap, counters + 1, n_unique,
-                                    nullptr, nullptr, scan, c->err));
-    if (inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, counters + 0, n_ids, s, inverse));
+    HIP_TRY(c, launch_dedup_insert(c->stream, ids, n, n_ids, c->g.n_nodes, s, c->err));
+    CompactArgs a{};
+    a.ids = ids;
+    a.lens.n_seg = 1;
+    a.lens.first_here = 0;
+    a.lens.len[0] = n;
+    a.n_max = n_ids;
+    a.n_total_dev = counters + 0;
+    a.s = s;
+    a.unique = unique;
+    a.unique_cap = unique_cap;
+    a.last = true;
+    a.n_unique_dev = counters + 1;
+    a.n_unique_out = n_unique;
+    a.scan = scan;
+    a.err = c->err;
+    HIP_TRY(c, launch_dedup_compact_plain(c->stream, a, n_ids));
+    if (inverse) {
+        const InverseArgs inv{Count{counters + 0, n_ids}, s, BatchTables{nullptr, 0, nullptr, 0, 0, nullptr, 0}, nullptr, inverse,
+                              Stamps{nullptr}};
+        HIP_TRY(c, launch_dedup_inverse(c->stream, inv, n_ids));
+    }
     return HELIOS_OK;
 }

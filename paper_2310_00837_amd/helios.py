@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libhelios.so")
 OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 MAX_HOPS, MAX_FANOUT = 8, 1024
 DEDUP_NOALLOC_MAX_IDS = 262144
-PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SERIAL_TIERS = 1, 2, 3
+PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SPLIT_COPIES = 1, 2, 3
 PARAM_MISSQ_TIMEOUT_US, PARAM_MISSQ_WAVES = 4, 5
 _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
           -5: "HELIOS_EDATA", -6: "HELIOS_EINTERNAL"}
@@ -30,8 +30,8 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup", "helios_dedup_noalloc",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
-           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_wait", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
-           "helios_gather_times", "helios_gather_ticks", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
+           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_wait", "helios_plan_make_blocks", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
+           "helios_gather_times", "helios_batch_ticks", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
            "helios_missq_attach", "helios_missq_faulted", "helios_missq_counters", "helios_missq_destroy"]
 
 
@@ -42,6 +42,14 @@ class HopOut(C.Structure):
 
 class BlockOut(C.Structure):
     _fields_ = [("row_local", C.c_void_p), ("col_local", C.c_void_p)]
+
+
+class RoleTicks(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("stage", C.c_int32), ("workgroups", C.c_int64), ("start", C.c_uint64),
+                ("end", C.c_uint64)]
+
+
+ROLE_SAMPLE, ROLE_COMPACT_HOP, ROLE_COMPACT_LOOKUP, ROLE_COPY_HOST, ROLE_COPY_HBM, ROLE_INVERSE = 1, 2, 3, 4, 5, 6
 
 
 class HeliosError(RuntimeError):
@@ -70,7 +78,7 @@ def load_library() -> C.CDLL:
     lib.helios_dedup.argtypes = [vp, vp, i64, vp, i64, vp, vp]
     lib.helios_dedup_noalloc.argtypes = [vp, vp, i64, vp, i64, vp, vp]
     lib.helios_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, i64, vp]
-    lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp]
+    lib.helios_gather_miss.argtypes = [vp, vp, vp, i64, vp, vp, i64]
     lib.helios_prepare_batch.argtypes = [vp, vp, i64, C.POINTER(i32), i32, C.c_uint64, C.POINTER(HopOut), vp,
                                          vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.helios_calibration_copy.argtypes = [vp, vp, vp, i64]
@@ -81,6 +89,7 @@ def load_library() -> C.CDLL:
                                        vp, i64, vp, C.POINTER(vp)]
     lib.helios_plan_launch.argtypes = [vp, vp, C.c_uint64]
     lib.helios_plan_wait.argtypes = [vp]
+    lib.helios_plan_make_blocks.argtypes = [vp, C.POINTER(BlockOut)]
     lib.helios_plan_destroy.argtypes = [vp]
     lib.helios_host_alloc.argtypes = [i64]
     lib.helios_host_alloc.restype = vp
@@ -88,9 +97,9 @@ def load_library() -> C.CDLL:
     lib.helios_set_param.argtypes = [vp, C.c_int, i64]
     lib.helios_set_timing.argtypes = [vp, C.c_int]
     lib.helios_gather_times.argtypes = [vp] + [C.POINTER(C.c_float)] * 4
-    lib.helios_gather_ticks.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
+    lib.helios_batch_ticks.argtypes = [vp, C.POINTER(RoleTicks), i32, C.POINTER(i32), C.POINTER(C.c_double)]
     lib.helios_missq_create.argtypes = [vp, i32, i32, i32, C.POINTER(vp)]
-    lib.helios_missq_submit.argtypes = [vp, vp, vp, i64, vp]
+    lib.helios_missq_submit.argtypes = [vp, vp, vp, i64, vp, i64]
     lib.helios_missq_complete.argtypes = [vp, vp]
     lib.helios_missq_attach.argtypes = [vp, vp]
     lib.helios_missq_faulted.argtypes = [vp]
@@ -196,8 +205,19 @@ class Plan:
         self._ctx._check(_lib.helios_plan_launch(self._p, _ptr(seeds), C.c_uint64(rng_seed)))
 
     def wait(self) -> None:
-        """Waits for this plan's last launch only; raises on device-side errors like Helios.sync()."""
+        """Waits for this plan's last launch only; raises on the device-side errors of this plan's batches."""
         self._ctx._check(_lib.helios_plan_wait(self._p))
+
+    def make_blocks(self, row_local: Sequence[torch.Tensor], col_local: Sequence[torch.Tensor]) -> None:
+        """The hops of the plan's last launch in local numbering (see helios_plan_make_blocks)."""
+        hops = self._keep[0]
+        arr = (BlockOut * len(hops))()
+        for i, hb in enumerate(hops):
+            _dev(row_local[i], torch.int32, "row_local"), _dev(col_local[i], torch.int32, "col_local")
+            assert row_local[i].numel() >= min(hb.frontier.numel(), hb.indptr.numel() - 1)
+            assert col_local[i].numel() >= hb.flat.numel()
+            arr[i] = BlockOut(row_local[i].data_ptr(), col_local[i].data_ptr())
+        self._ctx._check(_lib.helios_plan_make_blocks(self._p, arr))
 
     def destroy(self) -> None:
         if self._p is not None and self._p.value:
@@ -221,12 +241,13 @@ class MissQueue:
         ctx._children.append(self)
 
     def submit(self, miss_pos: torch.Tensor, miss_slot: torch.Tensor, n_miss_max: int,
-               n_miss_dev: Optional[torch.Tensor]) -> None:
+               n_miss_dev: Optional[torch.Tensor], out_rows: int) -> None:
         _dev(miss_pos, torch.int32, "miss_pos"), _dev(miss_slot, torch.int32, "miss_slot")
         assert n_miss_max <= min(miss_pos.numel(), miss_slot.numel())
         if n_miss_dev is not None:
             _dev_accessible(n_miss_dev, torch.int64, "n_miss_dev")
-        self._ctx._check(_lib.helios_missq_submit(self._q, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev)))
+        self._ctx._check(_lib.helios_missq_submit(self._q, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev),
+                                                  out_rows))
 
     def complete(self, out: torch.Tensor) -> None:
         if not out.is_cuda or not out.is_contiguous():
@@ -326,7 +347,7 @@ class Helios:
         self._check(_lib.helios_set_param(self._h, param, value))
 
     def set_timing(self, level: int) -> None:
-        """0 off, 1 device clock, 2 device clock and HIP events."""
+        """0 off, 1 device clock per role, 2 HIP events on the two copy kernels (split copies, direct launches)."""
         self._check(_lib.helios_set_timing(self._h, int(level)))
 
     def gather_times(self):
@@ -335,11 +356,11 @@ class Helios:
         self._check(_lib.helios_gather_times(self._h, *[C.byref(x) for x in v]))
         return tuple(x.value for x in v)
 
-    def gather_ticks(self):
-        """((hbm_start, hbm_end, host_start, host_end) in ticks of the GPU's clock, ticks per microsecond)"""
-        v, rate = (C.c_uint64 * 4)(), C.c_double()
-        self._check(_lib.helios_gather_ticks(self._h, v, C.byref(rate)))
-        return tuple(v), rate.value
+    def batch_ticks(self):
+        """([(kind, stage, workgroups, start, end), ...] of the timed roles of the last batch, ticks per microsecond)"""
+        buf, n, rate = (RoleTicks * 48)(), C.c_int32(), C.c_double()
+        self._check(_lib.helios_batch_ticks(self._h, buf, 48, C.byref(n), C.byref(rate)))
+        return [(r.kind, r.stage, r.workgroups, r.start, r.end) for r in buf[:n.value]], rate.value
 
     # ---- S0
     def csr_load(self, offsets: torch.Tensor, indices: torch.Tensor) -> None:
@@ -431,13 +452,16 @@ class Helios:
 
     # ---- S6
     def gather_miss(self, miss_pos: torch.Tensor, miss_slot: torch.Tensor, n_miss_max: int,
-                    n_miss_dev: Optional[torch.Tensor], out: torch.Tensor) -> None:
+                    n_miss_dev: Optional[torch.Tensor], out: torch.Tensor, out_rows: Optional[int] = None) -> None:
         _dev(miss_pos, torch.int32, "miss_pos"), _dev(miss_slot, torch.int32, "miss_slot")
         assert n_miss_max <= min(miss_pos.numel(), miss_slot.numel())
         if n_miss_dev is not None:
             _dev_accessible(n_miss_dev, torch.int64, "n_miss_dev")
+        if not out.is_cuda or not out.is_contiguous():
+            raise TypeError("out must be a contiguous GPU tensor")
+        rows = out.numel() * out.element_size() // max(self.row_bytes, 1) if out_rows is None else out_rows
         self._check(_lib.helios_gather_miss(self._h, _ptr(miss_pos), _ptr(miss_slot), n_miss_max, _ptr(n_miss_dev),
-                                            _ptr(out)))
+                                            _ptr(out), rows))
 
     # ---- recorded batch (HIP graph)
     def plan_create(self, n_seeds: int, fanouts: Sequence[int], hops: Sequence[HopBuffers], sizes: torch.Tensor,

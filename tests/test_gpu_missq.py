@@ -58,7 +58,7 @@ def test_missq_rounds_match_the_oracle(h, helios, oracle, row_bytes, shape):
         mi, ms = mp.clone(), mp.clone()
         stats = torch.full((4,), -9, dtype=torch.int64).pin_memory()
         h.gather(torch.from_numpy(ids).cuda(), out, mp, mi, ms, stats, n_ids=n_ids)
-        q.submit(mp, ms, mp.numel(), stats[3:4])
+        q.submit(mp, ms, mp.numel(), stats[3:4], out.shape[0])
         q.complete(out)
         h.sync()
         wout = np.full((n_ids, row_bytes), SENTINEL, np.uint8)
@@ -183,9 +183,9 @@ def test_missq_capacity_and_state_errors(h, helios, oracle):
     mi, ms = mp.clone(), mp.clone()
     stats = torch.zeros(4, dtype=torch.int64).pin_memory()
     h.gather(torch.from_numpy(ids).cuda(), out, mp, mi, ms, stats)
-    q.submit(mp, ms, 500, stats[3:4])
+    q.submit(mp, ms, 500, stats[3:4], out.shape[0])
     with pytest.raises(HE) as e:
-        q.submit(mp, ms, 500, stats[3:4])
+        q.submit(mp, ms, 500, stats[3:4], out.shape[0])
     assert e.value.code == helios.ESTATE
     q.complete(out)
     with pytest.raises(HE) as e:
@@ -196,7 +196,7 @@ def test_missq_capacity_and_state_errors(h, helios, oracle):
     assert (got[128:] == SENTINEL).all()
     # the queue works again with a list that fits
     out.fill_(SENTINEL)
-    q.submit(mp, ms, 100, None)
+    q.submit(mp, ms, 100, None, out.shape[0])
     q.complete(out)
     h.sync()
     got = out.cpu().numpy()
@@ -205,7 +205,7 @@ def test_missq_capacity_and_state_errors(h, helios, oracle):
     h.cache_build(cache.order, 0, 0, row_bytes, None, None, cache.standin)
     h.sync()
     with pytest.raises(HE) as e:
-        q.submit(mp, ms, 100, None)
+        q.submit(mp, ms, 100, None, out.shape[0])
     assert e.value.code == helios.ESTATE
     q.destroy()
     for bad in ((0, 4, 1), (5000, 4, 1), (4, 0, 1), (4, 4, 65)):
@@ -228,7 +228,7 @@ def test_missq_time_limit(h, helios):
     mi, ms = mp.clone(), mp.clone()
     stats = torch.zeros(4, dtype=torch.int64).pin_memory()
     h.gather(ids, out, mp, mi, ms, stats)
-    q.submit(mp, ms, 700, stats[3:4])
+    q.submit(mp, ms, 700, stats[3:4], out.shape[0])
     q.complete(out)
     with pytest.raises(helios.HeliosError) as e:
         h.sync()

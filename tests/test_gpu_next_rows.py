@@ -84,12 +84,87 @@ def test_blocks_in_local_numbering(helios, oracle, small, cfg):
             # the block addresses feature rows: row i of the hop is out[row_local[i]] = feat(frontier[i])
             got = b["out"][rows[k][:nf].long()].cpu().numpy()
             assert np.array_equal(got, to_bytes(feats)[fr])
-    # the relabelling needs the batch's hash table: any other de-duplication in between invalidates it
-    h.dedup(seeds, b["unique"], None, b["n_unique"])
+    # the relabelling reads the batch's own hash table, which a stand-alone de-duplication in between leaves alone
+    # (it works on the table of the context's next batch)
+    want_rows = [r.clone() for r in rows]
+    scratch_u = torch.empty_like(b["unique"])
+    scratch_n = torch.zeros(1, dtype=torch.int64).pin_memory()
+    h.dedup(seeds, scratch_u, None, scratch_n)
+    for r in rows:
+        r.fill_(-7)
+    h.make_blocks(b["hops"], rows, cols)
+    h.sync()
+    for k, hb in enumerate(b["hops"]):
+        nf = int(b["sizes"][2 * k])
+        assert np.array_equal(rows[k][:nf].cpu().numpy(), want_rows[k][:nf].cpu().numpy())
+    # before any batch there is nothing to relabel
+    fresh = helios.Helios(0)
+    fresh.csr_load(g.offsets.cuda(), g.indices.cuda())
     with pytest.raises(helios.HeliosError) as e:
-        h.make_blocks(b["hops"], rows, cols)
+        fresh.make_blocks(b["hops"], rows, cols)
+    assert e.value.code == helios.ESTATE
+    fresh.close()
+    h.close()
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_blocks_of_queued_plans(helios, oracle, small, cfg):
+    """Two recorded plans over two buffer sets on one context, used in turn (the benchmark's launch pattern): the
+    blocks of batch A are made after batch B has been launched behind it, from A's own table and buffers."""
+    sp, g, feats = small(cfg)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    stream = torch.cuda.Stream()
+    h = helios.Helios(0, stream=stream)
+    h.csr_load(g.offsets.cuda(), g.indices.cuda())
+    cache = GpuCache(h, feats, g.order, n_hbm, n_host)  # noqa: F841
+    B = sp.batch
+    sets = []
+    for _ in range(2):
+        b = _batch_buffers(helios, h, sp, B)
+        b["rows"] = [torch.full((hb.frontier.numel(),), -7, dtype=torch.int32, device="cuda") for hb in b["hops"]]
+        b["cols"] = [torch.full((hb.flat.numel(),), -7, dtype=torch.int32, device="cuda") for hb in b["hops"]]
+        sets.append(b)
+    h.reserve(sets[0]["unique"].numel())
+    torch.cuda.synchronize()
+    for b in sets:
+        b["plan"] = h.plan_create(B, sp.fanouts, b["hops"], b["sizes"], b["unique"], b["inverse"], b["n_unique"], b["out"],
+                                  b["mp"], b["mi"], b["ms"], b["stats"])
+    n_batches = 7
+
+    def check(b, batch):
+        U = int(b["n_unique"][0])
+        uniq = b["unique"][:U].cpu().numpy()
+        want_u, _ = oracle.dedup(g.n_nodes, np.concatenate(
+            [W.seed_batch(sp, g, batch).numpy()] + [hb.flat[:int(b["sizes"][2 * k + 1])].cpu().numpy() for k, hb in enumerate(b["hops"])]))
+        assert np.array_equal(uniq, want_u)
+        for k, hb in enumerate(b["hops"]):
+            nf, nfl = int(b["sizes"][2 * k]), int(b["sizes"][2 * k + 1])
+            fr, fl = hb.frontier[:nf].cpu().numpy(), hb.flat[:nfl].cpu().numpy()
+            assert np.array_equal(b["rows"][k][:nf].cpu().numpy(), oracle.local_ids(g.n_nodes, uniq, fr)), (batch, k)
+            assert np.array_equal(b["cols"][k][:nfl].cpu().numpy(), oracle.local_ids(g.n_nodes, uniq, fl)), (batch, k)
+
+    seeds = [W.seed_batch(sp, g, k).cuda() for k in range(n_batches)]
+    sets[0]["plan"].launch(seeds[0], W.batch_rng_seed(SEED, 0))
+    for batch in range(1, n_batches + 1):
+        prev = sets[(batch - 1) % 2]
+        if batch < n_batches:
+            sets[batch % 2]["plan"].launch(seeds[batch], W.batch_rng_seed(SEED, batch))     # queued behind the previous batch
+        prev["plan"].wait()
+        prev["plan"].make_blocks(prev["rows"], prev["cols"])                                   # after the next batch's launch
+        torch.cuda.synchronize()
+        prev["plan"].wait()                                                                    # would report an ID that is not in the table
+        check(prev, batch - 1)
+    # two more batches launched since a plan's: its table has been emptied for a later batch
+    sets[1]["plan"].launch(seeds[1], 2)
+    sets[0]["plan"].launch(seeds[2], 3)
+    sets[1]["plan"].make_blocks(sets[1]["rows"], sets[1]["cols"])                              # one batch behind: still fine
+    sets[0]["plan"].launch(seeds[3], 4)
+    with pytest.raises(helios.HeliosError) as e:
+        sets[1]["plan"].make_blocks(sets[1]["rows"], sets[1]["cols"])
     assert e.value.code == helios.ESTATE
     h.sync()
+    for b in sets:
+        b["plan"].destroy()
     h.close()
 
 

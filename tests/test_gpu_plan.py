@@ -125,10 +125,10 @@ def test_two_batches_queued_per_context(helios, oracle):
     first.close()
 
 
-@pytest.mark.parametrize("params", [dict(serial=0), dict(serial=0, hbm_blocks=7, host_blocks=3), dict(serial=1, hbm_blocks=8192, host_blocks=1)])
+@pytest.mark.parametrize("params", [dict(split=1), dict(split=0, hbm_blocks=7, host_blocks=3), dict(split=1, hbm_blocks=8192, host_blocks=1), dict(split=0, hbm_blocks=1, host_blocks=300)])
 def test_launch_parameters_do_not_change_results(helios, oracle, params):
-    """The tuning parameters (tier copies side by side on two streams, grid sizes of the row copies) only
-    change launch shapes: directly launched and recorded batches still match the oracle."""
+    """The tuning parameters (tier copies as kernels of their own or as roles of the batch's other launches, grid
+    sizes of the row copies) only change launch shapes: directly launched and recorded batches still match the oracle."""
     sp = W.spec(0)
     g = W.make_graph(sp, SEED, "cpu")
     feats = W.feature_rows(SEED, torch.arange(g.n_nodes), sp.dim, sp.dtype)
@@ -144,7 +144,7 @@ def test_launch_parameters_do_not_change_results(helios, oracle, params):
             np.ascontiguousarray(by_rank[n_hbm + n_host:])]
 
     def tune(ctx):
-        ctx.set_param(helios.PARAM_SERIAL_TIERS, params["serial"])
+        ctx.set_param(helios.PARAM_SPLIT_COPIES, params["split"])
         ctx.set_param(helios.PARAM_HBM_GATHER_BLOCKS, params.get("hbm_blocks", 0))
         ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, params.get("host_blocks", 0))
 
