@@ -1,24 +1,32 @@
 """Benchmark of the Helios mini-batch preparation path on one MI355X.
 
 A step is one pass of the whole path (k-hop sampling, de-duplication, cache lookup, gather of
-both cached tiers, miss list: helios_prepare_batch + helios_sync) over one batch of seeds of a
-synthetic workload whose graph, feature tables and seeds are resident before the timed region
-(graph, cache map and HBM tier in HBM; host tier and storage stand-in in pinned host memory,
-where the method keeps them).  Prints ONE JSON line.
+both cached tiers, miss list: a recorded helios_prepare_batch + one wait for that batch) over one
+batch of seeds of a synthetic workload whose graph, feature tables and seeds are resident before
+the timed region (graph, cache map and HBM tier in HBM; host tier and storage stand-in in pinned
+host memory, where the method keeps them).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--hbm-frac P]
+
+Default workload: benchmark configs[3] (50 M nodes, 1 B edges, 2 KB rows, 3 hops), the largest
+one-GPU workload; the same line carries a shorter block for configs[2] (the paper's PA shape)
+under "also" unless --also -1.
+
+    python bench.py --only roofline ...   runs only the set-up and the region the two "roofline"
+                                          objects come from (what profiles/kernel_trace_* trace)
 """
 import argparse
 import json
 import os
+import statistics
 import sys
-import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+ROLE_NAMES = {1: "sample", 2: "compact_hop", 3: "compact_lookup", 4: "copy_host", 5: "copy_hbm", 6: "inverse"}
 
 
 def log(msg: str) -> None:
@@ -43,127 +51,74 @@ def measure_host_link(torch, gib: float = 1.0) -> float:
     return best
 
 
-def probe_launch_delay(torch, helios, dev, args) -> int:
-    """What a kernel launch costs while the host link is saturated: stream B runs a chain of `chain` one-workgroup
-    copies (64 B each) with and without a long row copy from pinned host memory running on stream A (512 B rows,
-    --host-blocks workgroups, library default if 0).  The difference is what every launch of a mini-batch's
-    front pays while another mini-batch's host-tier copy is running."""
-    rb, table_rows, n_rows, chain = 512, 600_000, 1 << 19, 200
-    table = helios.pinned_empty((table_rows, rb), torch.uint8)
-    table.tensor.fill_(1)
-    out = torch.empty((n_rows, rb), dtype=torch.uint8, device=dev)
+def measure_plain_copy(torch, h) -> float:
+    """A plain 1 GiB device copy with the row copy's accesses (known traffic: 1 GiB read + 1 GiB written), GB/s."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    src.fill_(3)
+    best = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        h.calibration_copy(src, dst)
+        e1.record()
+        e1.synchronize()
+        best = max(best, 2.0 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    return best
+
+
+def large_list(torch, helios, dev, rb: int, table_gb: float, seed: int):
+    """The HBM-tier copy where it is bound by bandwidth: helios_gather of 1 M random IDs (fewer for rows
+    above 1 KB) that all hit an HBM tier of table_gb, far larger than the last-level cache; the copy kernel
+    is launched with HIP events that take its own begin and end (as a kernel trace reports them)."""
+    n_tab = int(table_gb * 1e9) // rb
+    n_ids = 1_000_000 if rb <= 1024 else 500_000
+    if n_tab < 2 * n_ids:
+        return None
+    table = torch.empty((n_tab, rb), dtype=torch.uint8, device=dev)
+    table.fill_(5)
+    order_l = torch.arange(n_tab, device=dev, dtype=torch.int32)       # the IDs are random, so are the rows
     gen = torch.Generator(device=dev)
-    gen.manual_seed(args.seed)
-    slot = torch.randint(0, table_rows, (n_rows,), device=dev, dtype=torch.int32, generator=gen)
-    pos = torch.arange(n_rows, device=dev, dtype=torch.int32)
-    small_src = torch.zeros(64, dtype=torch.uint8, device=dev)
-    small_dst = torch.zeros(64, dtype=torch.uint8, device=dev)
-    sa, sb = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
-    a, b = helios.Helios(0, stream=sa), helios.Helios(0, stream=sb)
-    n1 = torch.tensor([0, 1], dtype=torch.int64, device=dev)
-    order = torch.tensor([0], dtype=torch.int32, device=dev)
-    for ctx in (a, b):                       # a one-node graph whose only row lives in the stand-in: the long copy is S6
-        ctx.csr_load(n1, order)
-    a.cache_build(order, 0, 0, rb, None, None, table.tensor)
-    if args.host_blocks:
-        a.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
-    a.sync()
-    res = {}
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(sa)
-    a._check(helios._lib.helios_gather_miss(a._h, pos.data_ptr(), slot.data_ptr(), n_rows, None, out.data_ptr()))
-    e1.record(sa)
-    e1.synchronize()
-    res["link_copy_alone_GBs"] = n_rows * rb / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    # the chain as one recorded graph, so that the host's launch rate does not hide what the GPU does
-    graph = torch.cuda.CUDAGraph()
-    torch.cuda.synchronize()
-    with torch.cuda.graph(graph, stream=sb):
-        for _ in range(chain):
-            b.calibration_copy(small_src, small_dst)
-    torch.cuda.synchronize()
-    for with_link in (0, 1):
-        best = 1e30
-        for _ in range(5):
-            torch.cuda.synchronize()
-            if with_link:
-                a._check(helios._lib.helios_gather_miss(a._h, pos.data_ptr(), slot.data_ptr(), n_rows, None, out.data_ptr()))
-            t0 = time.perf_counter()
-            with torch.cuda.stream(sb):
-                graph.replay()
-            sb.synchronize()
-            best = min(best, (time.perf_counter() - t0) / chain * 1e6)
-            torch.cuda.synchronize()
-        res["us_per_launch_link_busy" if with_link else "us_per_launch_link_idle"] = best
-    res["chain"] = chain
-    res["what"] = ("a recorded chain of one-workgroup kernels on one stream; the other stream copies 2^19 rows of 512 B "
-                   "from pinned host memory")
-    a.close()
-    b.close()
-    table.free()
-    print(json.dumps(res))
-    return 0
+    gen.manual_seed(seed)
+    ids = torch.randint(0, n_tab, (n_ids,), device=dev, dtype=torch.int32, generator=gen)
+    out = torch.empty((n_ids, rb), dtype=torch.uint8, device=dev)
+    mp = torch.empty(16, dtype=torch.int32, device=dev)
+    stats = torch.zeros(4, dtype=torch.int64).pin_memory()
+    ctx = helios.Helios(0, stream=torch.cuda.Stream(device=dev))
+    ctx.csr_load(torch.zeros(n_tab + 1, dtype=torch.int64, device=dev), torch.zeros(1, dtype=torch.int32, device=dev))
+    ctx.cache_build(order_l, n_tab, 0, rb, table, None, None)
+    ctx.set_timing(2)
+    times = []
+    for _ in range(7):
+        ctx.gather(ids, out, mp, mp.clone(), mp.clone(), stats)
+        ctx.sync()
+        times.append(ctx.gather_times()[2])
+    ctx.close()
+    ms = statistics.median(times[2:])
+    gbs = 2.0 * n_ids * rb / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+    return {"rows": n_ids, "row_bytes": rb, "table_GB": n_tab * rb / 1e9, "kernel_us": ms * 1e3, "achieved": gbs,
+            "frac": gbs / HBM_PEAK_GBS,
+            "note": "gather_rows_kernel alone on a list long enough to be bound by bandwidth; median of 5 launches, HIP "
+                    "events on the kernel"}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="workload index in BASELINE.json configs (0-based)")
-    ap.add_argument("--hbm-frac", type=float, default=None, help="config 4 only: HBM-tier fraction of the sweep")
-    ap.add_argument("--seed", type=int, default=1234)
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time given to the CPU-oracle leg")
-    ap.add_argument("--depth", type=int, default=3,
-                    help="mini-batches in flight during the timed region (each on its own context and stream)")
-    ap.add_argument("--per-lane", type=int, default=2,
-                    help="mini-batches queued per lane in the timed region (buffer sets per context): one runs, "
-                         "the next waits behind it on the lane's stream")
-    ap.add_argument("--threads", type=int, default=0, help="0: one host thread drives all lanes (default, fastest); 1: one host thread per lane")
-    ap.add_argument("--graph", type=int, default=1, help="1: replay a recorded batch (HIP graph) per step; 0: launch directly")
-    ap.add_argument("--hbm-blocks", type=int, default=0, help="workgroups of the HBM-tier copy (0 = library default)")
-    ap.add_argument("--host-blocks", type=int, default=0, help="workgroups of the host-link copies (0 = library default)")
-    ap.add_argument("--missq-queues", type=int, default=128,
-                    help="queues of the asynchronous miss queue region (0 skips the region)")
-    ap.add_argument("--missq-threads", type=int, default=4, help="service threads per miss queue (one queue per lane)")
-    ap.add_argument("--large-list-gb", type=float, default=20.0,
-                    help="table size of the bandwidth-bound run of the HBM-tier copy (1 M random rows; 0 skips it)")
-    ap.add_argument("--serial-tiers", type=int, default=1,
-                    help="1: the host-tier copy follows the HBM-tier copy on the lane's stream (library default); "
-                         "0: the two run side by side on two streams")
-    ap.add_argument("--probe-launch-delay", action="store_true",
-                    help="instead of the benchmark: time a chain of small kernels on one stream while another "
-                         "stream's row copy saturates the host link, and print that as one JSON line")
-    ap.add_argument("--presample-batches", type=int, default=0,
-                    help="0: tiers in the in-degree order BASELINE.json names; N > 0: in the order of hotness counted over "
-                         "N pre-sampling batches (the paper's policy); -1: over one epoch of the train split")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--link-gbs", type=float, default=None,
-                    help="skip the host-link probe and use this rate (for runs under a counter profiler)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU; the path shards by giving each GPU its own "
-              "mini-batches, which needs no code here. Use --gpus 1.", file=sys.stderr)
-        return 2
-
+def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, full: bool):
+    """Sets workload `cfg` up, runs the timed regions, returns the result dict (full: with every region and the
+    CPU-oracle leg; else the headline figures only)."""
     import numpy as np
     import torch
 
     from paper_2310_00837_amd import helios, workload as W
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        return 2
     dev = torch.device("cuda", 0)
-    torch.cuda.set_device(dev)
-    if args.probe_launch_delay:
-        return probe_launch_delay(torch, helios, dev, args)
-    sp = W.spec(args.config, args.hbm_frac)
-    K, Wm = args.steps, args.warmup
+    sp = W.spec(cfg, hbm_frac)
+    only = args.only
 
     # ---------------- inputs (untimed)
     t0 = time.time()
-    gen_dev = dev if sp.n_nodes > 5_000_000 else "cpu"
-    g = W.make_graph(sp, args.seed, gen_dev, progress=log if sp.n_nodes > 5_000_000 else None)
+    big = sp.n_nodes > 5_000_000
+    gen_dev = dev if big else "cpu"
+    g = W.make_graph(sp, args.seed, gen_dev, progress=log if big else None)
     log(f"{sp.name}: N={g.n_nodes} E={g.n_edges} generated on {gen_dev} in {time.time() - t0:.1f}s")
     offsets, indices, order = g.offsets.to(dev), g.indices.to(dev), g.order.to(dev)
     g.offsets, g.indices, g.order, g.perm_seed = offsets, indices, order, g.perm_seed.to(dev)
@@ -204,26 +159,12 @@ def main() -> int:
         pinned_bufs.append(helios.pinned_empty(shape, dtype))
         return pinned_bufs[-1].tensor
 
-    tiers = W.make_tiers(sp, g, dev, progress=log if sp.n_nodes > 5_000_000 else None, pinned_empty=pinned_exact)
+    tiers = W.make_tiers(sp, g, dev, progress=log if big else None, pinned_empty=pinned_exact)
     log(f"tiers: hbm {tiers.n_hbm} host {tiers.n_host} stand-in {tiers.n_rest} rows x {sp.row_bytes} B "
         f"filled in {time.time() - t1:.1f}s")
-    link_gbs = args.link_gbs if args.link_gbs else measure_host_link(torch)
-    log(f"host link (pinned H2D copy): {link_gbs:.1f} GB/s" + (" (given)" if args.link_gbs else ""))
 
-    h = helios.Helios(0)
-    # yardstick: a plain 1 GiB device copy with the row copy's accesses (known traffic: 1 GiB read + 1 GiB written)
-    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cal_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cal_src.fill_(3)
-    copy_gbs = 0.0
-    for _ in range(3):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        h.calibration_copy(cal_src, cal_dst)
-        e1.record()
-        e1.synchronize()
-        copy_gbs = max(copy_gbs, 2.0 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    del cal_src, cal_dst
+    h = helios.Helios(0)                     # the default stream: set-up and the parity check only
+    copy_gbs = measure_plain_copy(torch, h)
     log(f"plain device copy (1 GiB, read+write): {copy_gbs:.0f} GB/s")
     h.csr_load(offsets, indices)
     h.cache_build(order, tiers.n_hbm, tiers.n_host, sp.row_bytes, tiers.hbm, tiers.host, tiers.standin)
@@ -233,6 +174,8 @@ def main() -> int:
     n_batches = K + Wm
     seeds = [W.seed_batch(sp, g, b).to(dev) for b in range(n_batches)]
     rng_seeds = [W.batch_rng_seed(args.seed, b) for b in range(n_batches)]
+    rb = sp.row_bytes
+    n_hops = len(sp.fanouts)
 
     class Buffers:
         """Caller-owned outputs of one mini-batch, and the recordings that write to them."""
@@ -241,15 +184,19 @@ def main() -> int:
             self.hops = helios.alloc_hops(B, sp.fanouts, dev)
             self.unique = torch.empty(cap, dtype=torch.int32, device=dev)
             self.inverse = torch.empty(cap, dtype=torch.int32, device=dev)
-            self.out = torch.empty((cap, sp.row_bytes), dtype=torch.uint8, device=dev)
+            self.out = torch.empty((cap, rb), dtype=torch.uint8, device=dev)
             self.mp = torch.empty(cap, dtype=torch.int32, device=dev)
             self.mi, self.ms = torch.empty_like(self.mp), torch.empty_like(self.mp)
-            self.sizes = torch.zeros(2 * len(sp.fanouts), dtype=torch.int64).pin_memory()
+            self.sizes = torch.zeros(2 * n_hops, dtype=torch.int64).pin_memory()
             self.n_unique = torch.zeros(1, dtype=torch.int64).pin_memory()
             self.stats = torch.zeros(4, dtype=torch.int64).pin_memory()
             # zero-copy numpy views of the pinned result words: reading them costs the host almost nothing
             self.stats_np, self.sizes_np = self.stats.numpy(), self.sizes.numpy()
             self.plans = {}
+
+        def args(self):
+            return (self.hops, self.sizes, self.unique, self.inverse, self.n_unique, self.out, self.mp, self.mi, self.ms,
+                    self.stats)
 
     class Lane:
         """One library context on its own stream.  It has two buffer sets: one mini-batch of the lane runs
@@ -262,292 +209,268 @@ def main() -> int:
                 width *= f
                 cap += width
             self.h.reserve(cap)
-            self.sets = [Buffers(cap) for _ in range(max(1, args.per_lane))]
-            first = self.sets[0]                 # the set the one-per-lane regions use
-            for name in ("hops", "unique", "inverse", "out", "mp", "mi", "ms", "sizes", "n_unique", "stats", "stats_np",
-                         "sizes_np", "plans"):
-                setattr(self, name, getattr(first, name))
             self.cap = cap
+            self.sets = [Buffers(cap) for _ in range(max(1, args.per_lane))]
             self.queue = None
+
+        def record(self) -> None:
+            """One recording (HIP graph) of the whole-path call per buffer set, and one with the roles timed.  A
+            directly launched batch comes first: the library sizes the grid of the HBM-tier copy from the hit counts
+            of the context's last finished batch, and a recording keeps the grid it was made with."""
+            self.h.prepare_batch(seeds[0], sp.fanouts, rng_seeds[0], *self.sets[0].args())
+            self.h.sync()
+            for bs in self.sets:
+                bs.plans[0] = self.h.plan_create(B, sp.fanouts, *bs.args())
+            self.h.set_timing(1)
+            self.sets[0].plans[1] = self.h.plan_create(B, sp.fanouts, *self.sets[0].args())
+            self.h.set_timing(0)
 
         def record_with_queue(self) -> None:
             """A miss queue of this lane's own and a recording in which the batch submits its misses to it."""
             nq = args.missq_queues
             self.queue = helios.MissQueue(self.h, nq, (self.cap + nq - 1) // nq, args.missq_threads)
             self.queue.attach()
-            self.h.set_timing(0)
-            self.plans["queue"] = self.h.plan_create(B, sp.fanouts, self.hops, self.sizes, self.unique, self.inverse,
-                                                     self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
+            self.sets[0].plans["queue"] = self.h.plan_create(B, sp.fanouts, *self.sets[0].args())
 
-        def record(self) -> None:
-            """One recording (HIP graph) of the whole-path call per timing level (and per buffer set for level 0)."""
-            for level in (0, 1):
-                self.h.set_timing(level)
-                for bs in (self.sets if level == 0 else self.sets[:1]):
-                    bs.plans[level] = self.h.plan_create(B, sp.fanouts, bs.hops, bs.sizes, bs.unique, bs.inverse,
-                                                         bs.n_unique, bs.out, bs.mp, bs.mi, bs.ms, bs.stats)
-            self.h.set_timing(0)
+        def drop_queue(self) -> None:
+            self.sets[0].plans.pop("queue").destroy()
+            self.queue.destroy()
+            self.queue = None
 
-        def launch_set(self, which: int, b: int) -> None:
-            """Batch b into buffer set `which` (timing off)."""
-            bs = self.sets[which]
-            if args.graph:
-                bs.plans[0].launch(seeds[b], rng_seeds[b])
-            else:
-                self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], bs.hops, bs.sizes, bs.unique, bs.inverse,
-                                     bs.n_unique, bs.out, bs.mp, bs.mi, bs.ms, bs.stats)
-
-        def launch(self, b: int, serve_misses, timing: int = 0) -> None:
-            if serve_misses == "queue":          # the batch submits its misses itself; the completion kernel follows
-                if args.graph:
-                    self.plans["queue"].launch(seeds[b], rng_seeds[b])
-                else:
-                    self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], self.hops, self.sizes, self.unique,
-                                         self.inverse, self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
-                self.queue.complete(self.out)
-                return
-            plan = self.plans.get(timing) if args.graph else None
-            if plan is not None:
-                plan.launch(seeds[b], rng_seeds[b])
-            else:
-                self.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], self.hops, self.sizes, self.unique,
-                                     self.inverse, self.n_unique, self.out, self.mp, self.mi, self.ms, self.stats)
-            if serve_misses:
-                self.h.gather_miss(self.mp, self.ms, self.mp.numel(), self.stats[3:4], self.out)
-
-    # every lane gets a stream of its own (a batch cannot be recorded on the NULL stream); `h` keeps the
-    # default stream and is used for set-up and the parity check only
     lanes = []
     for _ in range(max(1, args.depth)):
         st = torch.cuda.Stream(device=dev)
         ctx = helios.Helios(0, stream=st)
         ctx.csr_load(offsets, indices)
-        ctx.cache_build(order, tiers.n_hbm, tiers.n_host, sp.row_bytes, tiers.hbm, tiers.host, tiers.standin)
+        ctx.cache_build(order, tiers.n_hbm, tiers.n_host, rb, tiers.hbm, tiers.host, tiers.standin)
         ctx.sync()
-        if args.host_blocks:
-            ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, args.host_blocks)
-        if args.hbm_blocks:
-            ctx.set_param(helios.PARAM_HBM_GATHER_BLOCKS, args.hbm_blocks)
-        if not args.serial_tiers:
-            ctx.set_param(helios.PARAM_SERIAL_TIERS, 0)
         lanes.append(Lane(ctx, st))
     torch.cuda.synchronize()
-    if args.graph:
-        for ln in lanes:
-            ln.record()
+    for ln in lanes:
+        ln.record()
+    torch.cuda.synchronize()
+    D, P = len(lanes), max(1, args.per_lane)
+
+    def new_acc():
+        return dict(hbm_rows=0, host_rows=0, miss=0, unique=0, raw=0)
+
+    def tally(acc, bs):
+        st = bs.stats_np
+        acc["hbm_rows"] += int(st[1])
+        acc["host_rows"] += int(st[2])
+        acc["miss"] += int(st[3])
+        acc["unique"] += int(st[0])
+        acc["raw"] += int(bs.sizes_np[1::2].sum())
+
+    def region_queued(first: int, count: int):
+        """`count` steps on D lanes with P buffer sets each: a batch is queued behind the lane's running one and
+        each batch is waited for by itself (helios_plan_wait).  Returns (seconds, sums)."""
+        acc = new_acc()
+        units = [(ln, w) for w in range(P) for ln in lanes]      # lane 0 set 0, lane 1 set 0, ..., lane 0 set 1, ...
         torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for k in range(count):
+            ln, w = units[k % len(units)]
+            bs = ln.sets[w]
+            if k >= len(units):
+                bs.plans[0].wait()
+                tally(acc, bs)
+            bs.plans[0].launch(seeds[first + k], rng_seeds[first + k])
+        for k in range(max(0, count - len(units)), count):
+            ln, w = units[k % len(units)]
+            ln.sets[w].plans[0].wait()
+            tally(acc, ln.sets[w])
+        for ln in lanes:
+            ln.h.sync()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_begin, acc
 
-    def run_region(first: int, count: int, depth: int, timing: int, serve_misses, per_lane: int = 1):
-        """`count` whole steps on `depth` lanes.  per_lane == 1: lane b % depth takes batch b and is waited for
-        (helios_sync) before it is reused.  per_lane > 1 (recorded batches, no timing, no miss service): every
-        lane has per_lane buffer sets, a batch is queued behind the lane's running one, and each batch is waited
-        for by itself (helios_plan_wait).  Returns (seconds, sums)."""
-        acc = dict(hbm_ms=0.0, host_ms=0.0, hbm_ev_ms=0.0, host_ev_ms=0.0, hbm_rows=0, host_rows=0, miss=0, unique=0,
-                   raw=0)
+    def region_serial(first: int, count: int, depth: int, serve):
+        """`count` steps, lane b % depth takes batch b on its first buffer set and is synchronised (helios_sync)
+        before it is reused.  serve: None, "zero-copy" (helios_gather_miss) or "queue" (the asynchronous miss
+        queue).  Returns (seconds, sums)."""
+        acc = new_acc()
         use = lanes[:depth]
-        for ln in use:
-            ln.h.set_timing(timing)
 
-        def tally(bs):
-            st = bs.stats_np
-            acc["hbm_rows"] += int(st[1])
-            acc["host_rows"] += int(st[2])
-            acc["miss"] += int(st[3])
-            acc["unique"] += int(st[0])
-            acc["raw"] += int(bs.sizes_np[1::2].sum())
+        def launch(ln, b):
+            bs = ln.sets[0]
+            if serve == "queue":
+                bs.plans["queue"].launch(seeds[b], rng_seeds[b])
+                ln.queue.complete(bs.out)
+                return
+            bs.plans[0].launch(seeds[b], rng_seeds[b])
+            if serve == "zero-copy":
+                ln.h.gather_miss(bs.mp, bs.ms, bs.mp.numel(), bs.stats[3:4], bs.out)
 
         def retire(ln):
             ln.h.sync()
-            if timing:
-                a_ms, b_ms, a_ev, b_ev = ln.h.gather_times()
-                acc["hbm_ms"] += a_ms
-                acc["host_ms"] += b_ms
-                acc["hbm_ev_ms"] += a_ev
-                acc["host_ev_ms"] += b_ev
-            tally(ln)
-
-        def worker(w: int) -> None:          # lane w takes batches w, w + depth, ... one after the other
-            ln = use[w]
-            for k in range(w, count, depth):
-                ln.launch(first + k, serve_misses, timing)
-                retire(ln)
+            tally(acc, ln.sets[0])
 
         torch.cuda.synchronize()
         t_begin = time.perf_counter()
-        if per_lane > 1 and args.graph and not timing and not serve_misses:
-            units = [(ln, w) for w in range(per_lane) for ln in use]      # lane 0 set 0, lane 1 set 0, ..., lane 0 set 1, ...
-            for k in range(count):
-                ln, w = units[k % len(units)]
-                if k >= len(units):
-                    ln.sets[w].plans[0].wait()
-                    tally(ln.sets[w])
-                ln.launch_set(w, first + k)
-            for k in range(max(0, count - len(units)), count):
-                ln, w = units[k % len(units)]
-                ln.sets[w].plans[0].wait()
-                tally(ln.sets[w])
-            for ln in use:
-                ln.h.sync()
-        elif depth == 1 or not args.threads:
-            for k in range(count):
-                ln = use[k % depth]
-                if k >= depth:
-                    retire(ln)
-                ln.launch(first + k, serve_misses, timing)
-            for k in range(max(0, count - depth), count):
-                retire(use[k % depth])
-        else:                                # one host thread per lane (the library calls release the GIL)
-            ts = [threading.Thread(target=worker, args=(w,)) for w in range(depth)]
-            for t in ts:
-                t.start()
-            for t in ts:
-                t.join()
+        for k in range(count):
+            ln = use[k % depth]
+            if k >= depth:
+                retire(ln)
+            launch(ln, first + k)
+        for k in range(max(0, count - depth), count):
+            retire(use[k % depth])
         torch.cuda.synchronize()
-        seconds = time.perf_counter() - t_begin
-        for ln in use:
-            ln.h.set_timing(0)
-        return seconds, acc
+        return time.perf_counter() - t_begin, acc
 
-    # ---------------- timed region: W warm-up steps, then K whole steps (S1-S5) with `depth` mini-batches in
-    # flight; the row-copy kernels are timed with the device clock inside the same region
-    D = len(lanes)
-    P = max(1, args.per_lane) if args.graph else 1
-    run_region(0, Wm, D, 0, False, P)
-    elapsed, acc = run_region(Wm, K, D, 0, False, P)
-    # the same K steps: one batch per lane with the copies timed by the device clock; one batch in flight; with
-    # the miss list served (S6); with HIP events around the copies
-    run_region(0, Wm, D, 1, False)
-    ov_elapsed, ov_acc = run_region(Wm, K, D, 1, False)
-    run_region(0, Wm, 1, 1, False)
-    one_elapsed, one_acc = run_region(Wm, K, 1, 1, False)
-    elapsed_s6, _ = run_region(Wm, K, D, 0, True)
-    _, ev_acc = run_region(Wm, min(K, 50), 1, 2, False)
-    # S6 through the asynchronous miss queue: submission kernel after the lookup, host service threads,
-    # completion kernel after the cached tiers (each lane has a queue of its own)
-    elapsed_q = None
+    def repeated(fn, *a):
+        """The K-step region several times over: (median seconds, sums of the median run, all seconds)."""
+        runs = [fn(*a) for _ in range(max(1, args.repeats))]
+        runs.sort(key=lambda r: r[0])
+        mid = runs[len(runs) // 2]
+        return mid[0], mid[1], [r[0] for r in runs]
+
+    def region_roofline(count: int):
+        """One mini-batch in flight, launched directly with the two tier copies as kernels of their own
+        (HELIOS_PARAM_SPLIT_COPIES), each carrying HIP events that take the kernel's own begin and end: what a
+        kernel trace of this region shows per launch.  A second pass takes the same kernels' in-kernel span
+        (first workgroup start to last end, device clock)."""
+        ln = lanes[0]
+        bs = ln.sets[0]
+        ln.h.set_param(helios.PARAM_SPLIT_COPIES, 1)
+        res = {}
+        for level, keys in ((2, ("hbm_event_ms", "host_event_ms")), (1, ("hbm_span_ms", "host_span_ms"))):
+            ln.h.set_timing(level)
+            acc = new_acc()
+            sums = [0.0, 0.0]
+            for k in range(Wm + count):
+                b = k % n_batches
+                ln.h.prepare_batch(seeds[b], sp.fanouts, rng_seeds[b], *bs.args())
+                ln.h.sync()
+                if k < Wm:
+                    continue
+                t = ln.h.gather_times()
+                sums[0] += t[2] if level == 2 else t[0]
+                sums[1] += t[3] if level == 2 else t[1]
+                tally(acc, bs)
+            res[keys[0]], res[keys[1]] = sums[0] / count, sums[1] / count
+            res["hbm_rows"], res["host_rows"] = acc["hbm_rows"] / count, acc["host_rows"] / count
+        ln.h.set_timing(0)
+        ln.h.set_param(helios.PARAM_SPLIT_COPIES, 0)
+        return res
+
+    def region_roles(count: int):
+        """One mini-batch in flight, the recorded (fused) batch with every role timed by the device clock: average
+        span per role, and where the host-tier copies sit relative to the sampling passes."""
+        ln = lanes[0]
+        bs = ln.sets[0]
+        spans, first_link_start, last_sample_end, batch_span = {}, 0.0, 0.0, 0.0
+        for k in range(count):
+            b = (Wm + k) % n_batches
+            bs.plans[1].launch(seeds[b], rng_seeds[b])
+            ln.h.sync()
+            roles, per_us = ln.h.batch_ticks()
+            live = [r for r in roles if r[4] > r[3]]
+            if not live:
+                continue
+            t0_ = min(r[3] for r in live)
+            for kind, stage, wgs, a, z in live:
+                spans.setdefault(f"{ROLE_NAMES.get(kind, kind)}_{stage}", []).append((z - a) / per_us)
+            links = [r for r in live if r[0] == helios.ROLE_COPY_HOST]
+            samples = [r for r in live if r[0] == helios.ROLE_SAMPLE]
+            if links and samples:
+                first_link_start += (min(r[3] for r in links) - t0_) / per_us
+                last_sample_end += (max(r[4] for r in samples) - t0_) / per_us
+            batch_span += (max(r[4] for r in live) - t0_) / per_us
+        return {"avg_us_per_role": {k: sum(v) / len(v) for k, v in spans.items()},
+                "first_host_tier_copy_starts_at_us": first_link_start / count,
+                "last_sampling_pass_ends_at_us": last_sample_end / count,
+                "batch_span_us": batch_span / count,
+                "note": "device clock, one mini-batch in flight, recorded batch; times from the batch's first workgroup"}
+
+    result = {"dtype": "int32 ids / byte rows (" + ("fp32" if sp.dtype == torch.float32 else "fp16") + " features)",
+              "config": {"workload": f"BASELINE.json configs[{cfg}] {sp.name}", "n_nodes": g.n_nodes, "n_edges": g.n_edges,
+                         "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
+                         "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed,
+                         "cache_order": cache_order,
+                         "step": "helios_plan_launch (recorded helios_prepare_batch: sample, dedup, lookup, HBM+host gather, "
+                                 "miss list) + one helios_plan_wait per batch, %d contexts on %d streams, %d mini-batches "
+                                 "queued on each; median of %d runs of the K steps" % (D, D, P, args.repeats)}}
+
+    # ---------------- the roofline region: the two row copies as kernels of their own
+    roof = region_roofline(min(K, 100))
+    hbm_gbs = 2.0 * roof["hbm_rows"] * rb / (roof["hbm_event_ms"] * 1e-3) / 1e9 if roof["hbm_event_ms"] > 0 else 0.0
+    host_gbs = 1.0 * roof["host_rows"] * rb / (roof["host_event_ms"] * 1e-3) / 1e9 if roof["host_event_ms"] > 0 else 0.0
+    result["roofline"] = {
+        "kernel": "gather_rows_kernel<.., 0> (HBM-tier row copy)", "bound": "hbm", "achieved": hbm_gbs, "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None,
+        "avg_kernel_us": roof["hbm_event_ms"] * 1e3, "in_kernel_span_us": roof["hbm_span_ms"] * 1e3,
+        "rows_per_launch": roof["hbm_rows"], "bytes_per_row": 2 * rb,
+        "timer": "HIP events carried by the kernel launch (the kernel's own begin and end, as rocprofv3 --kernel-trace "
+                 "reports them); in_kernel_span_us: first workgroup start to last end by the device clock",
+        "region": "%d mini-batches, one in flight, launched directly with HELIOS_PARAM_SPLIT_COPIES (the tier copies as "
+                  "kernels of their own, as `bench.py --only roofline` runs them under the profiler)" % min(K, 100),
+        "plain_copy_GBs_on_this_box": copy_gbs}
+    result["roofline_host_link"] = {
+        "kernel": "gather_rows_kernel<.., 1> (host-tier row copy)", "bound": "host_link", "achieved": host_gbs, "peak": link_gbs,
+        "unit": "GB/s", "frac": host_gbs / link_gbs if link_gbs > 0 else None,
+        "peak_source": "given on the command line" if args.link_gbs else "pinned H2D copy measured in this run",
+        "avg_kernel_us": roof["host_event_ms"] * 1e3, "in_kernel_span_us": roof["host_span_ms"] * 1e3,
+        "rows_per_launch": roof["host_rows"], "bytes_per_row": rb}
+    if only == "roofline":
+        for ln in lanes:
+            for bs in ln.sets:
+                for pl in bs.plans.values():
+                    pl.destroy()
+            ln.h.close()
+        h.close()
+        return result
+
+    # ---------------- the timed region: W warm-up steps, then K whole steps (S1-S5), D x P mini-batches in flight
+    region_queued(0, Wm)
+    elapsed, acc, all_runs = repeated(region_queued, Wm, K)
+    result.update(value=K / elapsed, ms_per_step=elapsed / K * 1e3, runs_ms_per_step=[s / K * 1e3 for s in all_runs],
+                  batches_in_flight=D * P)
+    link_whole_run = 1.0 * acc["host_rows"] * rb / elapsed / 1e9
+    result["roofline_host_link"]["in_the_timed_region"] = {
+        "link_GBs": link_whole_run, "frac": link_whole_run / link_gbs if link_gbs > 0 else None,
+        "note": "host-tier bytes of the K steps / wall time of the timed region (value)"}
+    result["per_batch"] = {"raw_sampled_ids": acc["raw"] / K, "unique_ids": acc["unique"] / K,
+                           "hit_ratio_hbm": acc["hbm_rows"] / max(acc["unique"], 1),
+                           "hit_ratio_host": acc["host_rows"] / max(acc["unique"], 1),
+                           "miss_ratio": acc["miss"] / max(acc["unique"], 1)}
+    region_serial(0, Wm, 1, None)
+    one_elapsed, _, _ = repeated(region_serial, Wm, K, 1, None)
+    result["one_batch_in_flight"] = {"value": K / one_elapsed, "ms_per_step": one_elapsed / K * 1e3,
+                                     "note": "the same K steps with helios_sync after every batch"}
+    result["roles"] = region_roles(min(K, 50))
+    if not full:
+        for ln in lanes:
+            for bs in ln.sets:
+                for pl in bs.plans.values():
+                    pl.destroy()
+            ln.h.close()
+        h.close()
+        for pb in pinned_bufs:
+            pb.free()
+        return result
+
+    lane_elapsed, _, _ = repeated(region_serial, Wm, K, D, None)
+    result["one_batch_per_lane"] = {"value": K / lane_elapsed, "ms_per_step": lane_elapsed / K * 1e3,
+                                    "note": "%d lanes, helios_sync on a lane before it gets its next batch" % D}
+    s6_elapsed, _, _ = repeated(region_serial, Wm, K, D, "zero-copy")
+    result["with_miss_service"] = {"value": K / s6_elapsed, "ms_per_step": s6_elapsed / K * 1e3,
+                                   "note": "S6 by helios_gather_miss (zero-copy reads of the stand-in) after every batch"}
     if args.missq_queues > 0 and tiers.n_rest > 0:
         for ln in lanes:
             ln.record_with_queue()
         torch.cuda.synchronize()
-        run_region(0, Wm, D, 0, "queue")
-        elapsed_q, _ = run_region(Wm, K, D, 0, "queue")
+        region_serial(0, Wm, D, "queue")
+        q_elapsed, _, _ = repeated(region_serial, Wm, K, D, "queue")
         for ln in lanes:
-            ln.plans.pop("queue").destroy()
-            ln.queue.destroy()
-            ln.queue = None
-
-    rb = sp.row_bytes
-
-    def large_list():
-        """The HBM-tier copy where it is bound by bandwidth: helios_gather of 1 M random IDs (fewer for rows
-        above 1 KB) that all hit an HBM tier of --large-list-gb, far larger than the last-level cache."""
-        n_tab = int(args.large_list_gb * 1e9) // rb
-        n_ids = 1_000_000 if rb <= 1024 else 500_000
-        if n_tab < 2 * n_ids:
-            return None
-        table = torch.empty((n_tab, rb), dtype=torch.uint8, device=dev)
-        table.fill_(5)
-        order_l = torch.arange(n_tab, device=dev, dtype=torch.int32)       # the IDs are random, so are the rows
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(args.seed)
-        ids = torch.randint(0, n_tab, (n_ids,), device=dev, dtype=torch.int32, generator=gen)
-        out = torch.empty((n_ids, rb), dtype=torch.uint8, device=dev)
-        mp = torch.empty(16, dtype=torch.int32, device=dev)
-        stats = torch.zeros(4, dtype=torch.int64).pin_memory()
-        ctx = helios.Helios(0, stream=torch.cuda.Stream(device=dev))
-        ctx.csr_load(torch.zeros(n_tab + 1, dtype=torch.int64, device=dev), torch.zeros(1, dtype=torch.int32, device=dev))
-        ctx.cache_build(order_l, n_tab, 0, rb, table, None, None)
-        ctx.set_timing(1)
-        best = 0.0
-        for _ in range(5):
-            ctx.gather(ids, out, mp, mp.clone(), mp.clone(), stats)
-            ctx.sync()
-            ms = ctx.gather_times()[0]
-            best = max(best, 2.0 * n_ids * rb / (ms * 1e-3) / 1e9) if ms > 0 else best
-        ctx.close()
-        return {"rows": n_ids, "table_GB": n_tab * rb / 1e9, "achieved": best, "frac": best / HBM_PEAK_GBS,
-                "note": "same kernel, best of 5, device clock; a list long enough to be bound by bandwidth"}
-
-    big = large_list() if args.large_list_gb > 0 else None
-
-    def rates(a):
-        hbm = 2.0 * a["hbm_rows"] * rb / (a["hbm_ms"] * 1e-3) / 1e9 if a["hbm_ms"] > 0 else 0.0     # read + write
-        host = 1.0 * a["host_rows"] * rb / (a["host_ms"] * 1e-3) / 1e9 if a["host_ms"] > 0 else 0.0  # bytes over the link
-        return hbm, host
-
-    hbm_gbs, host_gbs = rates(one_acc)              # kernel quality: nothing else runs beside the copies
-    ov_hbm_gbs, ov_host_gbs = rates(ov_acc)         # the same kernels with one batch on each lane
-    dominant_host = one_acc["host_ms"] > one_acc["hbm_ms"]
-    link_whole_run = 1.0 * acc["host_rows"] * rb / elapsed / 1e9
-
-    # HBM bytes per launch of the HBM-tier copy from the committed counter runs (two rocprofv3 --pmc runs,
-    # scaled by the calibration copy); only for the workload they were taken on
-    traffic = None
-    names = {1: "hbm_traffic_cfg1_medium.txt"}
-    tpath = os.path.join(ROOT, "profiles", names.get(args.config, "none"))
-    if os.path.exists(tpath) and args.hbm_frac is None:
-        for line in open(tpath):
-            if line.startswith("TRAFFIC_JSON:"):
-                try:
-                    traffic = json.loads(line[len("TRAFFIC_JSON:"):])
-                except Exception:
-                    traffic = None
-
-    result = {
-        "metric": "sampled mini-batches/sec; feature gather GB/s vs HBM and host-link peak",
-        "value": K / elapsed,
-        "unit": "mini-batches/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": elapsed / K * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int32 ids / byte rows (" + ("fp32" if sp.dtype == torch.float32 else "fp16") + " features)",
-        "data": "synthetic",
-        "config": {"workload": f"BASELINE.json configs[{args.config}] {sp.name}", "n_nodes": g.n_nodes,
-                   "n_edges": g.n_edges, "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
-                   "tier_rows": [tiers.n_hbm, tiers.n_host, tiers.n_rest], "seed": args.seed, "cache_order": cache_order,
-                   "step": ("helios_plan_launch (recorded helios_prepare_batch" if args.graph else "helios_prepare_batch (") +
-                           ": sample, dedup, lookup, HBM+host gather, miss list) + one wait per batch (helios_plan_wait / helios_sync), "
-                           "%d contexts on %d streams, %d mini-batches queued on each" % (D, D, P)},
-        "roofline": {"kernel": "gather_rows_kernel (HBM tier)", "bound": "hbm", "achieved": hbm_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": traffic,
-                     "avg_kernel_us": one_acc["hbm_ms"] / K * 1e3,
-                     "avg_event_us": ev_acc["hbm_ev_ms"] / min(K, 50) * 1e3,
-                     "region": "the K timed steps run with one mini-batch in flight (as a kernel trace sees them)",
-                     "timer": "device clock, earliest workgroup start to latest end; avg_event_us: HIP events on the kernel's stream",
-                     "rows_per_launch": one_acc["hbm_rows"] / K, "bytes_per_row": 2 * rb,
-                     "plain_copy_GBs_on_this_box": copy_gbs,
-                     "large_list": big,
-                     "while_overlapped": {"achieved": ov_hbm_gbs, "frac": ov_hbm_gbs / HBM_PEAK_GBS,
-                                          "avg_kernel_us": ov_acc["hbm_ms"] / K * 1e3,
-                                          "note": "same kernel with one mini-batch on each of the %d lanes, beside other batches' host-link copies" % D}},
-        "roofline_host_link": {"kernel": "gather_rows_kernel (host tier)", "bound": "host_link",
-                               "achieved": host_gbs, "peak": link_gbs, "unit": "GB/s",
-                               "frac": host_gbs / link_gbs if link_gbs > 0 else None,
-                               "peak_source": "given on the command line" if args.link_gbs else "pinned H2D copy measured in this run",
-                               "avg_kernel_us": one_acc["host_ms"] / K * 1e3,
-                               "avg_event_us": ev_acc["host_ev_ms"] / min(K, 50) * 1e3,
-                               "rows_per_launch": one_acc["host_rows"] / K, "bytes_per_row": rb,
-                               "while_overlapped": {"link_GBs_over_the_whole_region": link_whole_run,
-                                                    "frac": link_whole_run / link_gbs if link_gbs > 0 else None,
-                                                    "per_kernel_GBs": ov_host_gbs,
-                                                    "note": "host-tier bytes of all K steps / wall time of the timed region (value)"}},
-        "dominant_kernel": "host-tier gather" if dominant_host else "HBM-tier gather",
-        "with_miss_service": {"value": K / elapsed_s6, "ms_per_step": elapsed_s6 / K * 1e3},
-        "with_async_miss_queue": None if elapsed_q is None else {
-            "value": K / elapsed_q, "ms_per_step": elapsed_q / K * 1e3, "queues_per_lane": args.missq_queues,
+            ln.drop_queue()
+        result["with_async_miss_queue"] = {
+            "value": K / q_elapsed, "ms_per_step": q_elapsed / K * 1e3, "queues_per_lane": args.missq_queues,
             "service_threads_per_lane": args.missq_threads,
             "note": "S6 in the shape of the paper's IO stack: submission kernel, host threads serving the stand-in "
-                    "into a pinned staging buffer, completion kernel"},
-        "batches_in_flight": D * P,
-        "one_batch_per_lane": {"value": K / ov_elapsed, "ms_per_step": ov_elapsed / K * 1e3,
-                               "note": "%d lanes, helios_sync on a lane before it gets its next batch" % D},
-        "one_batch_in_flight": {"value": K / one_elapsed, "ms_per_step": one_elapsed / K * 1e3,
-                                "note": "the same K steps with helios_sync after every batch"},
-        "per_batch": {"raw_sampled_ids": acc["raw"] / K, "unique_ids": acc["unique"] / K,
-                      "hit_ratio_hbm": acc["hbm_rows"] / max(acc["unique"], 1),
-                      "hit_ratio_host": acc["host_rows"] / max(acc["unique"], 1),
-                      "miss_ratio": acc["miss"] / max(acc["unique"], 1)},
-    }
+                    "into a pinned staging buffer, completion kernel"}
+    if args.large_list_gb > 0:
+        result["roofline"]["large_list"] = large_list(torch, helios, dev, rb, args.large_list_gb, args.seed)
 
     # ---------------- CPU oracle on the same batches (reported baseline) + parity of one batch
     if not args.no_cpu:
@@ -568,34 +491,105 @@ def main() -> int:
         seeds_h = [sd.cpu().numpy() for sd in seeds]
 
         def oracle_leg(seconds):
-            done, t_cpu = 0, time.perf_counter()
+            done, t_cpu, steps = 0, time.perf_counter(), [0.0, 0.0, 0.0]
             while (time.perf_counter() - t_cpu) < seconds:
                 b = Wm + done % K
+                ta = time.perf_counter()
                 hops_o = oracle.sample(off_h, idx_h, seeds_h[b], sp.fanouts, rng_seeds[b])
+                tb = time.perf_counter()
                 cat = np.concatenate([seeds_h[b]] + [fl for _, _, fl in hops_o])
                 uq, _ = oracle.dedup(g.n_nodes, cat)
+                tc = time.perf_counter()
                 o = np.empty((uq.size, rb), np.uint8)
                 oracle.gather(uq, rank_h, tiers.n_hbm, tiers.n_host, tabs[0], tabs[1], o)
+                td = time.perf_counter()
+                steps = [steps[0] + tb - ta, steps[1] + tc - tb, steps[2] + td - tc]
                 done += 1
-            return done, time.perf_counter() - t_cpu
+            return done, time.perf_counter() - t_cpu, [s / max(done, 1) * 1e3 for s in steps]
 
         all_cores = oracle.num_threads()
-        done, cpu_elapsed = oracle_leg(args.cpu_seconds)
+        done, cpu_elapsed, step_ms = oracle_leg(args.cpu_seconds)
         oracle.set_num_threads(1)
-        done1, cpu_elapsed1 = oracle_leg(args.cpu_seconds / 3)
+        done1, cpu_elapsed1, _ = oracle_leg(args.cpu_seconds / 3)
         oracle.set_num_threads(all_cores)
         result["cpu_baseline"] = {"value": done / cpu_elapsed, "unit": "mini-batches/s", "cores": all_cores,
                                   "kind": "oracle",
                                   "sample": f"{done} batches (passes over the {K} timed batches; sample, dedup, lookup, "
                                             f"gather of both cached tiers, miss list), {cpu_elapsed:.1f} s",
+                                  "ms_per_step_by_part": {"sample": step_ms[0], "dedup": step_ms[1],
+                                                          "lookup_gather_miss_list": step_ms[2]},
                                   "one_thread": {"value": done1 / cpu_elapsed1, "cores": 1,
                                                  "sample": f"{done1} batches, {cpu_elapsed1:.1f} s"}}
+        del tabs, off_h, idx_h
     for ln in lanes:
-        for pl in ln.plans.values():
-            pl.destroy()
+        for bs in ln.sets:
+            for pl in bs.plans.values():
+                pl.destroy()
         ln.h.close()
     h.close()
-    print(json.dumps(result))
+    for pb in pinned_bufs:
+        pb.free()
+    return result
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload index in BASELINE.json configs (0-based)")
+    ap.add_argument("--also", type=int, default=2,
+                    help="a second workload whose headline figures go under \"also\" in the same line (-1: none)")
+    ap.add_argument("--hbm-frac", type=float, default=None, help="config 4 only: HBM-tier fraction of the sweep")
+    ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--repeats", type=int, default=5, help="runs of the K-step timed region; the median is reported")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time given to the CPU-oracle leg")
+    ap.add_argument("--depth", type=int, default=3,
+                    help="lanes: library contexts, each on its own stream, that take the mini-batches in turn")
+    ap.add_argument("--per-lane", type=int, default=2,
+                    help="mini-batches queued per lane in the timed region (buffer sets per context): one runs, "
+                         "the next waits behind it on the lane's stream")
+    ap.add_argument("--missq-queues", type=int, default=128,
+                    help="queues of the asynchronous miss queue region (0 skips the region)")
+    ap.add_argument("--missq-threads", type=int, default=4, help="service threads per miss queue (one queue per lane)")
+    ap.add_argument("--large-list-gb", type=float, default=20.0,
+                    help="table size of the bandwidth-bound run of the HBM-tier copy (1 M random rows; 0 skips it)")
+    ap.add_argument("--presample-batches", type=int, default=0,
+                    help="0: tiers in the in-degree order BASELINE.json names; N > 0: in the order of hotness counted over "
+                         "N pre-sampling batches (the paper's policy); -1: over one epoch of the train split")
+    ap.add_argument("--only", choices=["roofline"], default=None,
+                    help="roofline: set-up and the roofline region only (the command the kernel traces under profiles/ use)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--link-gbs", type=float, default=None,
+                    help="skip the host-link probe and use this rate (for runs under a counter profiler)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; the path shards by giving each GPU its own "
+              "mini-batches, which needs no code here. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    link_gbs = args.link_gbs if args.link_gbs else measure_host_link(torch)
+    log(f"host link (pinned H2D copy): {link_gbs:.1f} GB/s" + (" (given)" if args.link_gbs else ""))
+    K, Wm = args.steps, args.warmup
+
+    main_res = run_workload(args, args.config, args.hbm_frac, K, Wm, link_gbs, full=True)
+    line = {"metric": "sampled mini-batches/sec; feature gather GB/s vs HBM and host-link peak",
+            "value": main_res.get("value"), "unit": "mini-batches/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+            "ms_per_step": main_res.get("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": main_res["dtype"], "data": "synthetic"}
+    line.update(main_res)
+    if args.also >= 0 and args.also != args.config and args.only is None:
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        also = run_workload(args, args.also, None, K, Wm, link_gbs, full=False)
+        line["also"] = also
+    print(json.dumps(line))
     return 0
 
 

@@ -47,6 +47,7 @@ struct PartitionArgs {
     int32_t *miss_pos, *miss_id, *miss_slot;
     int64_t miss_cap;
     int64_t* stats_out;          // device-accessible int64[4], nullable
+    int64_t* learn;              // pinned int64[4], nullable: a copy of the stats for the host's grid sizing
     ScanState scan;
     int32_t* err;
 };
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(kBlock) void lookup_partition_kernel(PartitionArgs 
         const int64_t c2 = static_cast<int64_t>(s_excl[2]) + s_agg[2];
         a.lists.count[0] = c0; a.lists.count[1] = c1; a.lists.count[2] = c2;
         if (a.stats_out) { a.stats_out[0] = n; a.stats_out[1] = c0; a.stats_out[2] = c1; a.stats_out[3] = c2; }
+        if (a.learn) { a.learn[0] = n; a.learn[1] = c0; a.learn[2] = c1; a.learn[3] = c2; }
         if (c2 > a.miss_cap) raise(a.err, kErrCapacity);
     }
 }
@@ -144,10 +146,10 @@ hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n
 hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max,
                                    const int32_t* rank, int64_t n_nodes, int64_t n_hbm, int64_t n_host,
                                    const TierLists& lists, int32_t* miss_pos, int32_t* miss_id,
-                                   int32_t* miss_slot, int64_t miss_cap, int64_t* stats_out,
+                                   int32_t* miss_slot, int64_t miss_cap, int64_t* stats_out, int64_t* learn,
                                    const ScanState& scan, int32_t* err) {
     PartitionArgs a{ids, n, rank, n_nodes, n_hbm, n_host, lists, miss_pos, miss_id, miss_slot, miss_cap,
-                    stats_out, scan, err};
+                    stats_out, learn, scan, err};
     int64_t tiles = (n_max + kTileItems - 1) / kTileItems;
     if (tiles < 1) tiles = 1;
     hipLaunchKernelGGL(lookup_partition_kernel, dim3(static_cast<unsigned>(tiles)), dim3(kBlock), 0, stream, a);

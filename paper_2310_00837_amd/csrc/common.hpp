@@ -66,7 +66,7 @@ struct Role {
     __device__ __forceinline__ bool mine() const { return blockIdx.x - first < blocks; }   // unsigned wrap-around
     __device__ __forceinline__ uint32_t rb() const { return blockIdx.x - first; }
 };
-constexpr unsigned kMaxRoleBlocks = 8192;
+constexpr unsigned kMaxRoleBlocks = 32768;
 
 // Optional timing of a role: workgroup rb of nrb stores its first and last tick of the constant-rate
 // device clock at clock[rb] and clock[nrb + rb] (plain stores, no contention); a publish kernel

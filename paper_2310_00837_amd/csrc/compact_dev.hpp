@@ -90,6 +90,8 @@ struct LookupOut {
     int32_t *miss_pos, *miss_id, *miss_slot;
     int64_t miss_cap;
     int64_t* stats_out;          // device-accessible int64[4], nullable; written by the last stage
+    int64_t* learn;              // pinned int64[4], nullable: the library's own copy of the stats, from which the host
+                                 // sizes the grids of the batches that follow
 };
 // Totals a stage leaves behind in device memory (int64[kStageWords]).
 constexpr int kStageUnique = 0, kStageHbm = 1, kStageHost = 2;      // unique IDs, HBM hits, host hits so far
@@ -302,6 +304,7 @@ __device__ __forceinline__ void compact_role(const CompactArgs& a, uint32_t rb, 
             if (a.last) {
                 a.look.lists.count[0] = copy0; a.look.lists.count[1] = copy1; a.look.lists.count[2] = fits ? c2 : 0;
                 if (a.look.stats_out) { a.look.stats_out[0] = total; a.look.stats_out[1] = c0; a.look.stats_out[2] = c1; a.look.stats_out[3] = c2; }
+                if (a.look.learn) { a.look.learn[0] = total; a.look.learn[1] = c0; a.look.learn[2] = c1; a.look.learn[3] = c2; }
                 if (c2 > a.look.miss_cap) raise(a.err, kErrCapacity);
             }
         }

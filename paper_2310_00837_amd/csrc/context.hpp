@@ -43,7 +43,7 @@ struct helios_ctx {
     int timing = 0;                            // 0 off, 1 device clock per role, 2 (split copies only) HIP events on the copy kernels
     hipEvent_t t_hbm[2] = {nullptr, nullptr}, t_host[2] = {nullptr, nullptr};
     bool timed_events = false;                 // the last batch recorded the events above
-    uint64_t* clock = nullptr;                 // device: workgroup ticks of the timed roles of a batch
+    uint64_t* clock = nullptr;                 // device: workgroup ticks of the timed roles of a batch (allocated when timing is first asked for)
     uint64_t* clock_host = nullptr;            // pinned [kMaxStampRoles][2], written by the publish kernel
     helios::StampRole stamp_roles[helios::kMaxStampRoles];
     helios::StampTable stamp_table{};
@@ -76,6 +76,8 @@ struct helios_ctx {
     int32_t* err = nullptr;                    // pinned, GPU-mapped int32[2]: the context's device-side error word
     int32_t* err_now = nullptr;                // where kernels being launched report: err, or the word of the plan being recorded
     int64_t* cnt = nullptr;                    // device int64[kNumCounters]
+    int64_t* learn = nullptr;                  // pinned int64[4]: {unique, HBM hits, host hits, misses} of the last finished lookup;
+                                               // read without waiting, to size the copy grids of the calls that follow
 
     // scratch, sized for calls of up to cap_ids IDs
     int64_t cap_ids = 0;

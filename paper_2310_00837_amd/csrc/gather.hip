@@ -49,8 +49,8 @@ hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* ds
 }
 
 hipError_t launch_gather_rows(hipStream_t stream, const GatherArgs& a, int64_t n_max, bool far_source, bool standin,
-                              unsigned blocks_limit, hipEvent_t t_start, hipEvent_t t_stop, unsigned* blocks_out) {
-    const unsigned nb = copy_role_blocks(a.chunks, far_source, n_max, blocks_limit);
+                              unsigned blocks_limit, int64_t expected, hipEvent_t t_start, hipEvent_t t_stop, unsigned* blocks_out) {
+    const unsigned nb = copy_role_blocks(a.chunks, far_source, n_max, blocks_limit, expected);
 #define HELIOS_CALL_(L, CPL, R)                                                          \
     do {                                                                                 \
         if (!far_source) launch_one<L, CPL, R, 0>(stream, a, nb, t_start, t_stop);       \

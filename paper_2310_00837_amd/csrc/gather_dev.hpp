@@ -9,10 +9,14 @@
 //
 // A group of L lanes owns one row and moves it as 16-byte pieces, so a row is read and written as
 // whole contiguous lines; L is the smallest power of two that covers the row (at most a wave).
-// Each group takes R list entries per step and issues all their loads before the first store.  The
-// groups of the role share the list evenly (entry k belongs to group k mod groups) and the bounds
-// of the list are read on the device.  Source and destination are touched once: non-temporal
-// accesses keep them from displacing the graph and the cache map in L2.
+// Each group takes R consecutive list entries per step and issues all their loads before the first
+// store.  A workgroup takes a run of consecutive entries per step and the workgroups take the runs
+// in turn, so the rows being written at any moment are one dense window of the output that moves
+// forward as workgroups are dispatched (list positions ascend): measured on this part, many
+// short-lived workgroups on consecutive runs copy 8-10 % faster than a few thousand long-lived
+// ones that stride over the whole list (6.0 against 5.5 TB/s for 2 KB rows; a plain copy behaves
+// the same way).  The bounds of the list are read on the device.  Source and destination are
+// touched once: non-temporal accesses keep them from displacing the graph and the cache map in L2.
 #pragma once
 #include "common.hpp"
 
@@ -56,18 +60,17 @@ __device__ __forceinline__ void copy_rows(const GatherArgs& a, uint32_t rb, uint
     stamp_start(a.stamps, rb);
     const int l = threadIdx.x % L;
     const int g = threadIdx.x / L;
-    // Group j of the role takes the list entries j, j + groups, j + 2 * groups, ..., R of them per step: every
-    // group gets the same number of rows to within one, so all workgroups (for a far source: all the CUs
-    // whose requests fill the link) stay busy until the list ends.
-    const int64_t groups = static_cast<int64_t>(nrb) * kGroups;
+    // Workgroup rb takes the runs rb, rb + nrb, ... of kGroups * R consecutive list entries: every workgroup gets
+    // the same number of runs to within one, so all of them (for a far source: all the CUs whose requests fill
+    // the link) stay busy until the list ends.
     const int64_t first = a.begin ? *a.begin : 0;
     const int64_t n = a.n.get();
-    for (int64_t k0 = first + static_cast<int64_t>(rb) * kGroups + g; k0 < n; k0 += groups * R) {
+    for (int64_t k0 = first + (static_cast<int64_t>(rb) * kGroups + g) * R; k0 < n; k0 += static_cast<int64_t>(nrb) * kGroups * R) {
         chunk16 v[R][CPL];
         int64_t dst[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int64_t k = k0 + r * groups;
+            const int64_t k = k0 + r;
             dst[r] = -1;
             int64_t s, d;
             if (k < n && gather_entry(a, k, s, d)) {
@@ -113,20 +116,34 @@ __device__ __forceinline__ void copy_rows_long(const GatherArgs& a, uint32_t rb,
 }
 
 // The shape of the copy loop for a row of `chunks` pieces.  far: the source is behind the host link (more
-// rows in flight per group, because each takes microseconds).
+// rows in flight per group, because each takes microseconds); an HBM source is quickest with one row per group
+// and step (measured: 2 KB rows 166 / 170 us with one / two rows, 512 B rows 181 / 186 / 193 us with 1 / 2 / 4).
 #define HELIOS_COPY_SHAPE_SWITCH(chunks, far, CALL)                     \
     do {                                                                \
         const int c_ = (chunks);                                        \
-        if (c_ <= 4) { CALL(4, 1, 2); }                                 \
-        else if (c_ <= 8) { CALL(8, 1, 2); }                            \
-        else if (c_ <= 16) { CALL(16, 1, 2); }                          \
-        else if (c_ <= 32 && (far)) { CALL(32, 1, 4); }                 \
-        else if (c_ <= 32) { CALL(32, 1, 1); }                          \
-        else if (c_ <= 64) { CALL(64, 1, 2); }                          \
-        else if (c_ <= 128) { CALL(64, 2, 2); }                         \
-        else if (c_ <= 256) { CALL(64, 4, 1); }                         \
-        else { CALL(0, 0, 0); }                                         \
+        if (far) {                                                      \
+            if (c_ <= 4) { CALL(4, 1, 2); }                             \
+            else if (c_ <= 8) { CALL(8, 1, 2); }                        \
+            else if (c_ <= 16) { CALL(16, 1, 2); }                      \
+            else if (c_ <= 32) { CALL(32, 1, 4); }                      \
+            else if (c_ <= 64) { CALL(64, 1, 2); }                      \
+            else if (c_ <= 128) { CALL(64, 2, 2); }                     \
+            else if (c_ <= 256) { CALL(64, 4, 1); }                     \
+            else { CALL(0, 0, 0); }                                     \
+        } else {                                                        \
+            if (c_ <= 4) { CALL(4, 1, 1); }                             \
+            else if (c_ <= 8) { CALL(8, 1, 1); }                        \
+            else if (c_ <= 16) { CALL(16, 1, 1); }                      \
+            else if (c_ <= 32) { CALL(32, 1, 1); }                      \
+            else if (c_ <= 64) { CALL(64, 1, 1); }                      \
+            else if (c_ <= 128) { CALL(64, 2, 1); }                     \
+            else if (c_ <= 256) { CALL(64, 4, 1); }                     \
+            else { CALL(0, 0, 0); }                                     \
+        }                                                               \
     } while (0)
+
+// rows per step of the far shape for a row that the near shape copies with L lanes and CPL pieces per lane
+constexpr int far_rows_per_step(int L, int CPL) { return L == 0 ? 0 : L <= 16 ? 2 : L == 32 ? 4 : CPL >= 4 ? 1 : 2; }
 
 // The copy with the shape chosen on the device: for roles that ride on another kernel (a host-link
 // copy beside a sampling pass), where one instantiation has to serve every row size.  The loop is
@@ -139,19 +156,26 @@ __device__ __forceinline__ void copy_rows_any(const GatherArgs& a, uint32_t rb, 
 #undef HELIOS_CALL_
 }
 
-// workgroups of a copy role over a list of at most n_max rows
-inline unsigned copy_role_blocks(int32_t chunks, bool far, int64_t n_max, unsigned limit /* 0 = default */) {
-    // far source: limited per CU by the requests a CU keeps in flight, not by waves, so one workgroup on each
-    // of as many CUs as fill the link (more for short rows) and no more: every kernel launched on the GPU while
-    // the link is saturated starts some microseconds late, the later the more link waves are in flight.
-    // HBM source: 8192 workgroups (four rounds of what the chip holds) balance long lists best; lists that can
-    // hold at most a few hundred thousand rows are quicker with the 2048 that are resident at once.
-    unsigned max_blocks = far ? (chunks <= 16 ? 128u : chunks <= 32 ? 44u : 32u) : (n_max >= 500000 ? kMaxRoleBlocks : 2048u);
-    if (limit > 0) max_blocks = limit < kMaxRoleBlocks ? limit : kMaxRoleBlocks;
+// Workgroups of a copy role over a list of at most n_max rows.  expected (0 = unknown): how many rows the
+// list will probably hold (the count of the context's previous batch).
+inline unsigned copy_role_blocks(int32_t chunks, bool far, int64_t n_max, unsigned limit /* 0 = default */, int64_t expected) {
     int rows_per_step = 1;
 #define HELIOS_CALL_(L, CPL, R) rows_per_step = (L) == 0 ? kWavesPerBlock : (kBlock / ((L) == 0 ? 64 : (L))) * (R)
     HELIOS_COPY_SHAPE_SWITCH(chunks, far, HELIOS_CALL_);
 #undef HELIOS_CALL_
+    // far source: limited per CU by the requests a CU keeps in flight, not by waves, so one workgroup on each
+    // of as many CUs as fill the link (more for short rows) and no more: every kernel launched on the GPU while
+    // the link is saturated starts some microseconds late, the later the more link waves are in flight.
+    // HBM source: best is one step per workgroup (see the head of this file), i.e. as many workgroups as the
+    // list has runs, if the length of the list can be guessed (a workgroup that finds nothing to do costs
+    // 0.2 ns, so a grid for the worst case would cost more than it gains); else a fixed few thousand.
+    int64_t max_blocks = far ? (chunks <= 16 ? 128 : chunks <= 32 ? 44 : 32) : (n_max >= 500000 ? 8192 : 2048);
+    if (!far && expected > 0) {
+        max_blocks = (expected + expected / 16 + rows_per_step - 1) / rows_per_step;
+        if (max_blocks < 256) max_blocks = 256;
+    }
+    if (limit > 0) max_blocks = limit;
+    if (max_blocks > kMaxRoleBlocks) max_blocks = kMaxRoleBlocks;
     int64_t blocks = (n_max + rows_per_step - 1) / rows_per_step;
     if (blocks < 1) blocks = 1;
     if (blocks > max_blocks) blocks = max_blocks;

@@ -188,6 +188,8 @@ unsigned tiles_for(int64_t n_max) {
 }
 
 // ---- timing of roles
+constexpr uint64_t kStampWords = 2ull * kMaxRoleBlocks * 16;     // ticks of all timed roles of one batch (8 MiB)
+
 void reset_stamps(helios_ctx* c) {
     c->n_stamps = 0;
     c->stamp_words = 0;
@@ -196,7 +198,8 @@ void reset_stamps(helios_ctx* c) {
 
 // Room in the clock buffer for a role of `workgroups` workgroups, if roles are being timed.
 Stamps take_stamps(helios_ctx* c, int kind, int stage, unsigned workgroups) {
-    if (c->timing != 1 || c->n_stamps >= kMaxStampRoles || workgroups == 0 || workgroups > kMaxRoleBlocks) return Stamps{nullptr};
+    if (c->timing != 1 || !c->clock || c->n_stamps >= kMaxStampRoles || workgroups == 0 || workgroups > kMaxRoleBlocks) return Stamps{nullptr};
+    if (c->stamp_words + 2ull * workgroups > kStampWords) return Stamps{nullptr};
     const int q = c->n_stamps++;
     c->stamp_roles[q] = StampRole{kind, stage, workgroups};
     c->stamp_table.offset[q] = c->stamp_words;
@@ -246,20 +249,28 @@ GatherArgs tier_copy_args(helios_ctx* c, int tier, const int64_t* begin, Count e
                       begin, end, c->row_bytes / 16, static_cast<chunk16*>(out), -1, -1, c->err_now, stamps};
 }
 
+// The HBM hits of the context's last finished lookup: the best guess for the next batch's (0 = none yet).  The
+// word is written by the lookup's last workgroup and read here without waiting: it only sizes a grid.
+int64_t expected_hbm_rows(const helios_ctx* c) {
+    const int64_t v = *reinterpret_cast<const volatile int64_t*>(c->learn + 1);
+    return v > 0 ? v : 0;
+}
+
 // The two row copies as kernels of their own over the per-tier lists that a lookup has left behind
 // (helios_gather, and the whole-path call with split copies); n_max bounds the lists.
 int copy_tiers_split(helios_ctx* c, int64_t n_max, void* out) {
     const bool events = c->timing > 1 && !c->recording;
     if (c->n_hbm > 0 && n_max > 0) {
-        const unsigned nb = copy_role_blocks(c->row_bytes / 16, false, n_max, c->hbm_blocks);
+        const int64_t expected = expected_hbm_rows(c);
+        const unsigned nb = copy_role_blocks(c->row_bytes / 16, false, n_max, c->hbm_blocks, expected);
         const GatherArgs a = tier_copy_args(c, 0, nullptr, Count{c->cnt + kCntTier + 0, n_max}, out, take_stamps(c, HELIOS_ROLE_COPY_HBM, 0, nb));
-        HIP_TRY(c, launch_gather_rows(c->stream, a, n_max, false, false, c->hbm_blocks, events ? c->t_hbm[0] : nullptr,
+        HIP_TRY(c, launch_gather_rows(c->stream, a, n_max, false, false, c->hbm_blocks, expected, events ? c->t_hbm[0] : nullptr,
                                       events ? c->t_hbm[1] : nullptr, nullptr));
     }
     if (c->n_host > 0 && n_max > 0) {
-        const unsigned nb = copy_role_blocks(c->row_bytes / 16, true, n_max, c->host_blocks);
+        const unsigned nb = copy_role_blocks(c->row_bytes / 16, true, n_max, c->host_blocks, 0);
         const GatherArgs a = tier_copy_args(c, 1, nullptr, Count{c->cnt + kCntTier + 1, n_max}, out, take_stamps(c, HELIOS_ROLE_COPY_HOST, 0, nb));
-        HIP_TRY(c, launch_gather_rows(c->stream, a, n_max, true, false, c->host_blocks, events ? c->t_host[0] : nullptr,
+        HIP_TRY(c, launch_gather_rows(c->stream, a, n_max, true, false, c->host_blocks, 0, events ? c->t_host[0] : nullptr,
                                       events ? c->t_host[1] : nullptr, nullptr));
     }
     c->timed_events = events;
@@ -345,7 +356,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         if (b && h > 0 && !c->split_copies && c->n_host > 0 && u_max > 0) {
             const int stage = h - 1;
             const int64_t stage_max = std::min(u_max, stage == 0 ? n_seeds + p.flat_max[0] : p.flat_max[stage]);
-            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks);
+            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks, 0);
             link = tier_copy_args(c, 1, stage > 0 ? stage_words(c, stage - 1) + kStageHostCopy : nullptr,
                                   Count{stage_words(c, stage) + kStageHostCopy, u_max}, b->out,
                                   take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
@@ -398,7 +409,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
             look.n_unique_out = b->n_unique;
             look.look = LookupOut{c->rank, c->n_hbm, c->n_host,
                                   TierLists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier},
-                                  b->miss_pos, b->miss_id, b->miss_slot, b->miss_cap, reinterpret_cast<int64_t*>(b->stats)};
+                                  b->miss_pos, b->miss_id, b->miss_slot, b->miss_cap, reinterpret_cast<int64_t*>(b->stats), c->learn};
             look.batches_run = rec && h == 0 ? c->batches_run : nullptr;
             look.scan = scan_state(c, epoch, kScanRowsLook);
             look.err = err;
@@ -432,12 +443,12 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         GatherArgs hbm{}, link{};
         unsigned hbm_blocks = 0, link_blocks = 0, inv_blocks = 0, clear_blocks = 0;
         if (c->n_hbm > 0 && u_max > 0) {
-            hbm_blocks = copy_role_blocks(chunks, false, u_max, c->hbm_blocks);
+            hbm_blocks = copy_role_blocks(chunks, false, u_max, c->hbm_blocks, expected_hbm_rows(c));
             hbm = tier_copy_args(c, 0, nullptr, Count{c->cnt + kCntTier + 0, u_max}, b->out, take_stamps(c, HELIOS_ROLE_COPY_HBM, stage, hbm_blocks));
         }
         if (c->n_host > 0 && u_max > 0) {
             const int64_t stage_max = std::min(u_max, stage == 0 ? n_seeds + p.flat_max[0] : p.flat_max[stage]);
-            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks);
+            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks, 0);
             link = tier_copy_args(c, 1, stage > 0 ? stage_words(c, stage - 1) + kStageHostCopy : nullptr,
                                   Count{c->cnt + kCntTier + 1, u_max}, b->out, take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
         }
@@ -544,16 +555,17 @@ int helios_create(helios_ctx** out, int device, void* hip_stream) {
               hipMalloc(&c->batches_run, 64) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->vars_ring), sizeof(BatchVars) * kVarsRing,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
-              hipMalloc(&c->clock, sizeof(uint64_t) * 2 * kMaxRoleBlocks * kMaxStampRoles) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&c->learn), 64, hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess &&
               hipHostMalloc(reinterpret_cast<void**>(&c->clock_host), sizeof(uint64_t) * 2 * kMaxStampRoles,
                             hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess;
-    ok = ok && c->err && c->cnt && c->vars && c->scan_ticket && c->batches_run && c->vars_ring && c->clock && c->clock_host;
+    ok = ok && c->err && c->cnt && c->vars && c->scan_ticket && c->batches_run && c->vars_ring && c->learn && c->clock_host;
     ok = ok && noalloc_init(device) == HELIOS_OK;      // address of this device's static scratch (helios_dedup_noalloc)
     if (ok) {
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && khz > 0) c->clock_khz = khz;
         c->err[0] = c->err[1] = 0;
         c->err_now = c->err;
+        for (int k = 0; k < 4; ++k) c->learn[k] = 0;
         ok = hipMemsetAsync(c->cnt, 0, sizeof(int64_t) * kNumCounters, c->stream) == hipSuccess &&
              hipMemsetAsync(c->scan_ticket, 0, 128, c->stream) == hipSuccess &&
              hipMemsetAsync(c->batches_run, 0, 64, c->stream) == hipSuccess &&
@@ -586,6 +598,7 @@ int helios_destroy(helios_ctx* c) {
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
     if (c->err) (void)hipHostFree(c->err);
+    if (c->learn) (void)hipHostFree(c->learn);
     for (hipEvent_t e : {c->t_hbm[0], c->t_hbm[1], c->t_host[0], c->t_host[1]})
         if (e) (void)hipEventDestroy(e);
     delete c;
@@ -669,7 +682,7 @@ int helios_cache_fill(helios_ctx* c, const void* src_table, const int32_t* order
     DeviceGuard guard(c->device);
     const GatherArgs a{static_cast<const chunk16*>(src_table), nullptr, order + first_rank, nullptr, Count{nullptr, n_rows},
                        row_bytes / 16, static_cast<chunk16*>(dst), -1, -1, c->err, Stamps{nullptr}};
-    HIP_TRY(c, launch_gather_rows(c->stream, a, n_rows, false, false, 0, nullptr, nullptr, nullptr));
+    HIP_TRY(c, launch_gather_rows(c->stream, a, n_rows, false, false, 0, n_rows, nullptr, nullptr, nullptr));
     return HELIOS_OK;
 }
 
@@ -747,7 +760,7 @@ int helios_gather(helios_ctx* c, const int32_t* ids, int64_t n_ids, void* out, i
     if (rc) return rc;
     const TierLists lists{{c->list_pos[0], c->list_pos[1]}, {c->list_slot[0], c->list_slot[1]}, c->cnt + kCntTier};
     HIP_TRY(c, launch_lookup_partition(c->stream, ids, Count{nullptr, n_ids}, n_ids, c->rank, c->g.n_nodes, c->n_hbm, c->n_host,
-                                       lists, miss_pos, miss_id, miss_slot, miss_cap, reinterpret_cast<int64_t*>(stats),
+                                       lists, miss_pos, miss_id, miss_slot, miss_cap, reinterpret_cast<int64_t*>(stats), c->learn,
                                        scan_state(c, epoch, kScanRowsLook), c->err));
     rc = copy_tiers_split(c, n_ids, out);
     if (rc) return rc;
@@ -767,7 +780,7 @@ int helios_gather_miss(helios_ctx* c, const int32_t* miss_pos, const int32_t* mi
     // (with every node cached nothing can miss: any entry is then reported by the kernel as outside its table)
     const GatherArgs a{static_cast<const chunk16*>(c->standin_table), miss_pos, miss_slot, nullptr, Count{n_miss_dev, n_miss_max},
                        c->row_bytes / 16, static_cast<chunk16*>(out), standin_rows, out_rows, c->err, Stamps{nullptr}};
-    HIP_TRY(c, launch_gather_rows(c->stream, a, n_miss_max, true, true, c->host_blocks, nullptr, nullptr, nullptr));
+    HIP_TRY(c, launch_gather_rows(c->stream, a, n_miss_max, true, true, c->host_blocks, 0, nullptr, nullptr, nullptr));
     return HELIOS_OK;
 }
 
@@ -1070,6 +1083,10 @@ int helios_set_param(helios_ctx* c, int param, int64_t value) {
 
 int helios_set_timing(helios_ctx* c, int level) {
     if (!c) return HELIOS_EINVAL;
+    if (level == 1 && !c->clock) {              // room for the ticks of every workgroup of every timed role of a batch
+        DeviceGuard guard(c->device);
+        HIP_TRY(c, hipMalloc(&c->clock, sizeof(uint64_t) * kStampWords));
+    }
     c->timing = level < 0 ? 0 : level > 2 ? 2 : level;
     reset_stamps(c);
     return HELIOS_OK;

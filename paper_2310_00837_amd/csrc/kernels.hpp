@@ -67,15 +67,16 @@ hipError_t launch_rank_build(hipStream_t stream, const int32_t* order, int64_t n
 hipError_t launch_lookup_partition(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max,
                                    const int32_t* rank, int64_t n_nodes, int64_t n_hbm, int64_t n_host,
                                    const TierLists& lists, int32_t* miss_pos, int32_t* miss_id,
-                                   int32_t* miss_slot, int64_t miss_cap, int64_t* stats_out,
+                                   int32_t* miss_slot, int64_t miss_cap, int64_t* stats_out, int64_t* learn,
                                    const ScanState& scan, int32_t* err);
 
 // ---- gather.hip
 // The row copy as a kernel of its own.  far_source selects the launch shape for a source behind the host
 // link (few workgroups, one per CU).  With t_start / t_stop (nullable) the launch carries HIP events that
-// take the kernel's own begin and end, as a kernel trace reports them.  *blocks_out = workgroups launched.
+// take the kernel's own begin and end, as a kernel trace reports them.  expected: the probable length of the
+// list (0 = unknown; see copy_role_blocks).  *blocks_out = workgroups launched.
 hipError_t launch_gather_rows(hipStream_t stream, const GatherArgs& a, int64_t n_max, bool far_source, bool standin,
-                              unsigned blocks_limit /* 0 = default */, hipEvent_t t_start, hipEvent_t t_stop,
+                              unsigned blocks_limit /* 0 = default */, int64_t expected, hipEvent_t t_start, hipEvent_t t_stop,
                               unsigned* blocks_out);
 
 // ---- blocks.hip

@@ -134,9 +134,9 @@ hipError_t launch_finish(hipStream_t stream, const GatherArgs& hbm, unsigned hbm
     if (total == 0) return hipSuccess;
     const dim3 grid(total), block(kBlock);
     const int chunks = hbm_blocks > 0 ? hbm.chunks : link_blocks > 0 ? link.chunks : 1;
-    // the two copies move rows of the same size; only for rows of 272-512 bytes do their loops differ (rows per step)
+    // the two copies move rows of the same size; their loops differ in the rows a group takes per step
 #define HELIOS_CALL_(L, CPL, R)                                                                                            \
-    hipLaunchKernelGGL((batch_finish_kernel<L, CPL, R, (L) == 32 ? 4 : (R)>), grid, block, 0, stream, hbm, r_hbm, link, r_link, inv, \
+    hipLaunchKernelGGL((batch_finish_kernel<L, CPL, R, far_rows_per_step(L, CPL)>), grid, block, 0, stream, hbm, r_hbm, link, r_link, inv, \
                        r_inv, clear, r_clear, bt, vars)
     HELIOS_COPY_SHAPE_SWITCH(chunks, false, HELIOS_CALL_);
 #undef HELIOS_CALL_
