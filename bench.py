@@ -557,8 +557,10 @@ def main() -> int:
     ap.add_argument("--presample-batches", type=int, default=0,
                     help="0: tiers in the in-degree order BASELINE.json names; N > 0: in the order of hotness counted over "
                          "N pre-sampling batches (the paper's policy); -1: over one epoch of the train split")
-    ap.add_argument("--only", choices=["roofline"], default=None,
-                    help="roofline: set-up and the roofline region only (the command the kernel traces under profiles/ use)")
+    ap.add_argument("--only", choices=["roofline", "large-list"], default=None,
+                    help="roofline: set-up and the roofline region only (the command the kernel traces under profiles/ use); "
+                         "large-list: only the bandwidth-bound run of the HBM-tier copy with the workload's row size (no "
+                         "graph, no pinned tiers: the command the counter runs under profiles/ use)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--link-gbs", type=float, default=None,
                     help="skip the host-link probe and use this rate (for runs under a counter profiler)")
@@ -576,6 +578,15 @@ def main() -> int:
     link_gbs = args.link_gbs if args.link_gbs else measure_host_link(torch)
     log(f"host link (pinned H2D copy): {link_gbs:.1f} GB/s" + (" (given)" if args.link_gbs else ""))
     K, Wm = args.steps, args.warmup
+    if args.only == "large-list":
+        from paper_2310_00837_amd import helios, workload as W
+        h = helios.Helios(0)
+        copy_gbs = measure_plain_copy(torch, h)          # the yardstick kernel runs in the same process
+        h.close()
+        res = large_list(torch, helios, torch.device("cuda", 0), W.spec(args.config).row_bytes, args.large_list_gb, args.seed)
+        res["plain_copy_GBs_on_this_box"] = copy_gbs
+        print(json.dumps(res))
+        return 0
 
     main_res = run_workload(args, args.config, args.hbm_frac, K, Wm, link_gbs, full=True)
     line = {"metric": "sampled mini-batches/sec; feature gather GB/s vs HBM and host-link peak",

@@ -306,6 +306,17 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         if (b) c->batch_dirty[which] = slots_b;
     }
     const int64_t u_max = b ? std::min(p.cat_max, b->unique_cap) : 0;
+    // What the kernels' own guards rely on (they bound every index by these): a list never outgrows the buffer it
+    // is written to, and the scratch holds the longest list.  Cheap enough to check on every call.
+    for (int h = 0; h < n_hops; ++h) {
+        const bool fits = p.frontier_max[h] <= hops[h].frontier_cap && p.flat_max[h] <= hops[h].flat_cap &&
+                          p.flat_max[h] <= c->cap_ids && 2 * p.flat_max[h] <= static_cast<int64_t>(c->table_slots) &&
+                          (h == 0 || p.frontier_max[h] <= p.flat_max[h - 1]);
+        if (!fits) return fail(c, HELIOS_EINTERNAL, "launch bounds of hop %d do not fit its buffers", h);
+    }
+    if (p.cat_max > c->cap_ids || 2 * p.cat_max > static_cast<int64_t>(c->table_slots) || (b && u_max > b->unique_cap) ||
+        c->scan_stride < static_cast<uint32_t>(p.ids_max / kTileItems + 2))
+        return fail(c, HELIOS_EINTERNAL, "launch bounds of the batch do not fit the scratch");
 
     const bool fold = n_seeds <= kFoldMaxSeeds;
     if (!fold) {

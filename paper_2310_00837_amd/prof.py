@@ -4,8 +4,10 @@
     python -m paper_2310_00837_amd.prof trace  <dir> <prefix>     # per-kernel durations
     python -m paper_2310_00837_amd.prof pmc    <dir> <prefix> <COUNTER>   # per-kernel counter sums
 
-Kernels of this library are listed one line per (kernel, grid size), since the same row-copy
-kernel serves the HBM tier (large grid) and the host tier / stand-in (small grid).
+Kernels of this library are listed one line per kernel name.  The row-copy kernel's last template
+argument names its source (gather_rows_kernel<L, CPL, R, SRC>: SRC 0 = HBM tier or another device
+table, 1 = host tier, 2 = storage stand-in); its grid follows the length of the list, so the
+workgroup column gives the range seen.
 """
 import collections
 import csv
@@ -27,17 +29,21 @@ def trace(d: str, prefix: str) -> str:
     for r in rows:
         if not _ours(r["Kernel_Name"]):
             continue
-        key = (_short(r["Kernel_Name"]), int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1))
+        key = _short(r["Kernel_Name"])
+        wg = int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1)
         dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
-        a = agg.setdefault(key, [0, 0, 1 << 62, 0])
+        a = agg.setdefault(key, [0, 0, 1 << 62, 0, 1 << 62, 0])
         a[0] += 1
         a[1] += dur
         a[2] = min(a[2], dur)
         a[3] = max(a[3], dur)
+        a[4] = min(a[4], wg)
+        a[5] = max(a[5], wg)
     total = sum(a[1] for a in agg.values()) or 1
-    out = [f"{'kernel':36s} {'workgroups':>10s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'share':>6s}"]
-    for (nm, wg), a in agg.items():
-        out.append(f"{nm:36s} {wg:10d} {a[0]:6d} {a[1] / a[0] / 1e3:9.2f} {a[2] / 1e3:9.2f} {a[3] / 1e3:9.2f} "
+    out = [f"{'kernel':44s} {'workgroups':>13s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'share':>6s}"]
+    for nm, a in agg.items():
+        wgs = f"{a[4]}" if a[4] == a[5] else f"{a[4]}-{a[5]}"
+        out.append(f"{nm:44s} {wgs:>13s} {a[0]:6d} {a[1] / a[0] / 1e3:9.2f} {a[2] / 1e3:9.2f} {a[3] / 1e3:9.2f} "
                    f"{100.0 * a[1] / total:5.1f}%")
     return "\n".join(out)
 
@@ -51,13 +57,17 @@ def pmc(d: str, prefix: str, counter: str) -> str:
         name = r["Kernel_Name"]
         if not _ours(name):
             continue
-        key = (_short(name), int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1))
-        a = agg.setdefault(key, [0, 0.0])
+        key = _short(name)
+        wg = int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1)
+        a = agg.setdefault(key, [0, 0.0, 1 << 62, 0])
         a[0] += 1
         a[1] += float(r["Counter_Value"])
-    out = [f"{'kernel':36s} {'workgroups':>10s} {'dispatches':>10s} {counter + ' avg/dispatch':>26s}"]
-    for (nm, wg), a in agg.items():
-        out.append(f"{nm:36s} {wg:10d} {a[0]:10d} {a[1] / a[0]:26.1f}")
+        a[2] = min(a[2], wg)
+        a[3] = max(a[3], wg)
+    out = [f"{'kernel':44s} {'workgroups':>13s} {'dispatches':>10s} {counter + ' avg/dispatch':>26s}"]
+    for nm, a in agg.items():
+        wgs = f"{a[2]}" if a[2] == a[3] else f"{a[2]}-{a[3]}"
+        out.append(f"{nm:44s} {wgs:>13s} {a[0]:10d} {a[1] / a[0]:26.1f}")
     return "\n".join(out)
 
 

@@ -26,14 +26,14 @@ def test_profile_summaries(tmp_path):
     trace.write_text(
         '"Kind","Kernel_Name","Start_Timestamp","End_Timestamp","Workgroup_Size_X","Grid_Size_X"\n'
         '"KERNEL_DISPATCH","void helios::(anonymous namespace)::gather_rows_kernel<32, 1, 1>(helios::(anonymous namespace)::GatherArgs)",1000,5000,256,524288\n'
-        '"KERNEL_DISPATCH","void helios::(anonymous namespace)::gather_rows_kernel<32, 1, 1>(helios::(anonymous namespace)::GatherArgs)",9000,15000,256,524288\n'
+        '"KERNEL_DISPATCH","void helios::(anonymous namespace)::gather_rows_kernel<32, 1, 1>(helios::(anonymous namespace)::GatherArgs)",9000,15000,256,1048576\n'
         '"KERNEL_DISPATCH","void helios::(anonymous namespace)::gather_rows_kernel<32, 1, 4>(helios::(anonymous namespace)::GatherArgs)",20000,110000,256,11264\n'
         '"KERNEL_DISPATCH","(anonymous namespace)::missq_submit_kernel((anonymous namespace)::SubmitArgs)",0,7000,256,4096\n'
         '"KERNEL_DISPATCH","void at::native::some_torch_kernel()",0,1000000,256,256\n')
     lines = prof.trace(str(tmp_path), "x").splitlines()
     assert len(lines) == 4                                     # header + three kernels of this library
     hbm = [ln for ln in lines if ln.startswith("gather_rows_kernel<32, 1, 1>")][0].split()
-    assert hbm[-6:-1] == ["2048", "2", "5.00", "4.00", "6.00"]  # workgroups, calls, avg, min, max (us)
+    assert hbm[-6:-1] == ["2048-4096", "2", "5.00", "4.00", "6.00"]  # workgroups (range), calls, avg, min, max (us)
     assert any(ln.startswith("missq_submit_kernel") and " 16 " in ln for ln in lines)
     pmc = tmp_path / "x_counter_collection.csv"
     pmc.write_text(
