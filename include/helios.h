@@ -238,8 +238,8 @@ int helios_make_blocks(helios_ctx *ctx, const helios_hop_out *hops, int32_t n_ho
  * count as in helios_gather_miss; counts device int32[n_nodes], zeroed by the
  * caller before the epoch).  helios_hotness_order writes the nodes by counter
  * descending, ties by ascending ID, to order (device int32[n_nodes]): the
- * hotness_order argument of helios_cache_build.  It allocates and frees its
- * scratch and waits for the stream. */
+ * hotness_order argument of helios_cache_build.  Its scratch (about 13 bytes
+ * per node) is allocated on the first call and kept by the context. */
 int helios_hotness_add(helios_ctx *ctx, const int32_t *ids, int64_t n_max, const int64_t *n_dev,
                        int32_t *counts);
 int helios_hotness_order(helios_ctx *ctx, const int32_t *counts, int32_t *order);

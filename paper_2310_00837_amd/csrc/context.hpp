@@ -122,8 +122,6 @@ struct helios_ctx {
     // scratch of helios_hotness_order, kept between calls
     void* hot_temp = nullptr;
     size_t hot_temp_bytes = 0;
-    int32_t *hot_ids = nullptr, *hot_counts = nullptr;
-    int64_t hot_cap = 0;
 };
 
 namespace helios {

@@ -603,8 +603,6 @@ int helios_destroy(helios_ctx* c) {
     (void)hipFree(c->scan_ticket);
     (void)hipFree(c->batches_run);
     (void)hipFree(c->hot_temp);
-    (void)hipFree(c->hot_ids);
-    (void)hipFree(c->hot_counts);
     if (c->vars_ring) (void)hipHostFree(c->vars_ring);
     (void)hipFree(c->clock);
     if (c->clock_host) (void)hipHostFree(c->clock_host);
@@ -1026,23 +1024,16 @@ int helios_hotness_order(helios_ctx* c, const int32_t* counts, int32_t* order) {
     if (!counts || !order) return fail(c, HELIOS_EINVAL, "NULL pointer");
     DeviceGuard guard(c->device);
     // scratch of the sort: allocated on the first call for a graph of this size, kept until the context is destroyed
-    const size_t temp_bytes = hotness_order_temp_bytes(n);
-    if (n > c->hot_cap || temp_bytes > c->hot_temp_bytes) {
+    const size_t bytes = hotness_order_scratch_bytes(n);
+    if (bytes > c->hot_temp_bytes) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         (void)hipFree(c->hot_temp);
-        (void)hipFree(c->hot_ids);
-        (void)hipFree(c->hot_counts);
         c->hot_temp = nullptr;
-        c->hot_ids = c->hot_counts = nullptr;
-        c->hot_cap = 0;
         c->hot_temp_bytes = 0;
-        HIP_TRY(c, hipMalloc(&c->hot_temp, temp_bytes ? temp_bytes : 16));
-        HIP_TRY(c, hipMalloc(&c->hot_ids, sizeof(int32_t) * n));
-        HIP_TRY(c, hipMalloc(&c->hot_counts, sizeof(int32_t) * n));
-        c->hot_cap = n;
-        c->hot_temp_bytes = temp_bytes;
+        HIP_TRY(c, hipMalloc(&c->hot_temp, bytes));
+        c->hot_temp_bytes = bytes;
     }
-    HIP_TRY(c, launch_hotness_order(c->stream, counts, n, c->hot_ids, c->hot_counts, order, c->hot_temp, c->hot_temp_bytes));
+    HIP_TRY(c, launch_hotness_order(c->stream, counts, n, order, c->hot_temp, c->err));
     return HELIOS_OK;
 }
 

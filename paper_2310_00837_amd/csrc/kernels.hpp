@@ -88,10 +88,10 @@ hipError_t launch_local_ids(hipStream_t stream, const int32_t* ids, Count n, int
 // ---- hotness.hip
 hipError_t launch_hotness_add(hipStream_t stream, const int32_t* ids, Count n, int64_t n_max, int64_t n_nodes,
                               int32_t* counts, int32_t* err);
-size_t hotness_order_temp_bytes(int64_t n_nodes);
-// order = nodes by counts descending, ties by ascending ID; ids_in / counts_sorted: int32[n_nodes] scratch
-hipError_t launch_hotness_order(hipStream_t stream, const int32_t* counts, int64_t n_nodes, int32_t* ids_in,
-                                int32_t* counts_sorted, int32_t* order, void* temp, size_t temp_bytes);
+size_t hotness_order_scratch_bytes(int64_t n_nodes);
+// order = nodes by counts descending, ties by ascending ID; scratch: hotness_order_scratch_bytes(n_nodes) of device memory
+hipError_t launch_hotness_order(hipStream_t stream, const int32_t* counts, int64_t n_nodes, int32_t* order, void* scratch,
+                                int32_t* err);
 
 // dst[0, bytes) = src[0, bytes) with the same 16-byte non-temporal accesses as the row copy
 hipError_t launch_calibration_copy(hipStream_t stream, const void* src, void* dst, int64_t bytes);

@@ -168,8 +168,11 @@ def test_blocks_of_queued_plans(helios, oracle, small, cfg):
     h.close()
 
 
-def test_presampling_hotness_and_order(helios, oracle, small):
-    sp, g, feats = small(0)
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_presampling_hotness_and_order(helios, oracle, small, cfg):
+    """Sec. 3.2.2 "Cache Initialization": hotness counted over pre-sampling batches and the order sorted from it, on
+    the 10 k-node and on the 1 M-node workload, against the oracle; the tiers placed by that order serve a batch."""
+    sp, g, feats = small(cfg)
     n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
     off, idx = g.offsets.numpy(), g.indices.numpy()
     h = helios.Helios(0)
@@ -178,7 +181,7 @@ def test_presampling_hotness_and_order(helios, oracle, small):
     b = _batch_buffers(helios, h, sp, sp.batch)
     counts = torch.zeros(g.n_nodes, dtype=torch.int32, device="cuda")
     want_counts = np.zeros(g.n_nodes, np.int32)
-    n_batches = 7                                                # the train split of workload 0 has 7 full batches
+    n_batches = 7 if cfg == 0 else 12                            # the train split of workload 0 has 7 full batches
     for batch in range(n_batches):
         seeds = W.seed_batch(sp, g, batch)
         rs = W.batch_rng_seed(SEED, batch)
@@ -210,10 +213,11 @@ def test_presampling_hotness_and_order(helios, oracle, small):
     assert hit_presampled > 0
 
 
-def test_topology_in_pinned_host_memory(helios, oracle, small):
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_topology_in_pinned_host_memory(helios, oracle, small, cfg):
     """The graph may stay in CPU memory and be read by the sampling kernel through the mapped
     address (Sec. 3.2.1 keeps the whole topology in the CPU cache)."""
-    sp, g, feats = small(0)
+    sp, g, feats = small(cfg)
     n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
     h = helios.Helios(0)
     off_pin, idx_pin = g.offsets.clone().pin_memory(), g.indices.clone().pin_memory()
