@@ -70,6 +70,7 @@ int32_t* batch_iof(const helios_ctx* c, uint32_t t) { return c->batch_iof + stat
 // Scratch for calls with up to n IDs.  Growing waits for the stream first: the
 // old buffers may still be in use.  Every hash table starts out empty.
 int ensure_capacity(helios_ctx* c, int64_t n) {
+    if (n < 1) n = 1;                           // an empty call still gets its (smallest) scratch
     if (n <= c->cap_ids) return HELIOS_OK;
     if (c->recording) return fail(c, HELIOS_ESTATE, "scratch must be reserved before a batch is recorded");
     c->scratch_generation += 1;
