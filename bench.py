@@ -103,6 +103,30 @@ def large_list(torch, helios, dev, rb: int, table_gb: float, seed: int):
                     "events on the kernel"}
 
 
+def counted_traffic(rb: int, rows_per_launch: float):
+    """HBM bytes per launch of the HBM-tier copy from the committed counter runs (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+    scaled by the calibration copy): those runs are taken on a long list of rows of the same size (the profiler does not
+    survive the set-up of the large workloads), so the counted bytes per row are scaled to this launch's row count."""
+    name = {2048: "hbm_traffic_and_l2_gather_rows_large_list_2KB_rows.txt",
+            512: "hbm_traffic_and_l2_gather_rows_large_list_512B_rows.txt"}.get(rb)
+    path = os.path.join(ROOT, "profiles", name) if name else None
+    if not path or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("TRAFFIC_JSON:"):
+            try:
+                t = json.loads(line[len("TRAFFIC_JSON:"):])
+            except Exception:
+                return None
+            k = rows_per_launch / t["rows_per_launch"]
+            return {"unit": "bytes per launch of the HBM-tier row copy", "fetched": t["fetched"] * k, "written": t["written"] * k,
+                    "algorithmic_read": rows_per_launch * (rb + 8), "algorithmic_written": rows_per_launch * rb,
+                    "rows_per_launch": rows_per_launch,
+                    "source": "counted on %d rows of %d B with the same kernel (profiles/%s), scaled to this launch's rows"
+                              % (t["rows_per_launch"], rb, name)}
+    return None
+
+
 def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, full: bool):
     """Sets workload `cfg` up, runs the timed regions, returns the result dict (full: with every region and the
     CPU-oracle leg; else the headline figures only)."""
@@ -398,7 +422,7 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
     host_gbs = 1.0 * roof["host_rows"] * rb / (roof["host_event_ms"] * 1e-3) / 1e9 if roof["host_event_ms"] > 0 else 0.0
     result["roofline"] = {
         "kernel": "gather_rows_kernel<.., 0> (HBM-tier row copy)", "bound": "hbm", "achieved": hbm_gbs, "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None,
+        "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": counted_traffic(rb, roof["hbm_rows"]),
         "avg_kernel_us": roof["hbm_event_ms"] * 1e3, "in_kernel_span_us": roof["hbm_span_ms"] * 1e3,
         "rows_per_launch": roof["hbm_rows"], "bytes_per_row": 2 * rb,
         "timer": "HIP events carried by the kernel launch (the kernel's own begin and end, as rocprofv3 --kernel-trace "
