@@ -313,6 +313,54 @@ int helios_plan_wait(helios_plan *plan);
 int helios_plan_make_blocks(helios_plan *plan, const helios_block_out *blocks);
 int helios_plan_destroy(helios_plan *plan);
 
+/* A gang: the mini-batches of several contexts recorded into the same
+ * launches.  One mini-batch is a chain of short launches that latency, not
+ * throughput, bounds; the chains of independent mini-batches overlap best
+ * when they are the same launches (Sec. 3.3 pipelines independent
+ * mini-batches on streams; here up to HELIOS_MAX_GANG of them share every
+ * launch, each with workgroups of its own, and gangs in turn may run on
+ * different streams).  The members are contexts created on one and the same
+ * (non-NULL) stream, each with its graph, its cache (rows of one size) and
+ * its scratch; member m's batch goes to buffers[m] (the buffer arguments of
+ * helios_prepare_batch; hops points to n_hops entries) and its results and
+ * errors are those of helios_prepare_batch on that context, bit for bit.
+ * n_seeds (at most 2048), the fan-outs and n_hops are the same for all
+ * members.  Timing, split copies and an attached miss queue do not go with a
+ * gang (HELIOS_ESTATE).  Argument errors are reported through ctxs[0]
+ * (helios_last_error).
+ *
+ * helios_gang_launch: seeds[m] (device int32[n_seeds]) and rng_seeds[m] are
+ * member m's; one launch sequence on the shared stream prepares all batches.
+ * helios_gang_wait: waits for the gang's last launch; member_status
+ * (nullable, n_members entries) receives every member's own device-side
+ * error code, the return value is the first that is not HELIOS_OK.
+ * helios_gang_make_blocks: helios_plan_make_blocks for one member's batch.
+ * Between launches of a gang its contexts may be used for other calls; the
+ * rules of a recorded batch apply to every member (scratch, cache and graph
+ * unchanged since the recording; at most 255 launches without a wait).
+ * Destroy the gang before its contexts. */
+#define HELIOS_MAX_GANG 4
+typedef struct {
+    const helios_hop_out *hops;
+    int64_t *sizes;
+    int32_t *unique;
+    int64_t unique_cap;
+    int32_t *inverse;
+    int64_t *n_unique;
+    void *out;
+    int32_t *miss_pos, *miss_id, *miss_slot;
+    int64_t miss_cap;
+    helios_gather_stats *stats;
+} helios_batch_buffers;
+typedef struct helios_gang helios_gang;
+int helios_gang_create(helios_ctx *const *ctxs, int32_t n_members, int64_t n_seeds,
+                       const int32_t *fanouts, int32_t n_hops,
+                       const helios_batch_buffers *buffers, helios_gang **gang_out);
+int helios_gang_launch(helios_gang *gang, const int32_t *const *seeds, const uint64_t *rng_seeds);
+int helios_gang_wait(helios_gang *gang, int32_t *member_status);
+int helios_gang_make_blocks(helios_gang *gang, int32_t member, const helios_block_out *blocks);
+int helios_gang_destroy(helios_gang *gang);
+
 /* Asynchronous service of the miss list in the shape of the GPU-initiated IO
  * stack of Sec. 3.1, with host threads over the storage stand-in in the place
  * of the SSDs: a submission kernel (Sec. 3.1.1: one thread per miss builds a

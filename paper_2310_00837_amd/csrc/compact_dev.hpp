@@ -114,8 +114,10 @@ struct CompactArgs {
     bool last;                   // the last stage writes the outputs below
     int64_t* n_unique_dev;
     int64_t* n_unique_out;       // device-accessible, nullable
-    NextHopCount next;
-    LookupOut look;
+    union {                      // a pass is either the batch's (look) or the one between two hops (next), or neither
+        LookupOut look;
+        NextHopCount next;
+    };
     uint32_t* batches_run;       // nullable: the first compaction of a recorded batch counts the batch
     ScanState scan;
     int32_t* err;

@@ -26,6 +26,16 @@ constexpr int kScanRowsHop = 0;     // 2 rows: hop compaction, count pass
 constexpr int kScanRowsLook = 2;    // 3 rows: batch compaction with lookup, stand-alone lookup, stand-alone de-duplication
 constexpr int kScanRows = 5;
 
+// A launch of the batch pipeline that has been prepared but not issued: the launches of the members of a
+// gang are collected first and then issued together, step by step (see helios_gang_create).
+enum StepKind { kStepSample = 0, kStepCompact = 1, kStepFinish = 2 };
+struct PendingStep {
+    StepKind kind;
+    SampleJob sample;
+    CompactJob compact;
+    FinishJob finish;
+};
+
 // one timed role of the last batch (see helios_batch_ticks)
 struct StampRole {
     int32_t kind, stage;
@@ -109,6 +119,8 @@ struct helios_ctx {
     uint32_t rec_scans = 0;
     uint32_t rec_clear_slots = 0;              // slots of the next batch's table that the recording empties
     uint64_t scratch_generation = 0;
+
+    std::vector<helios::PendingStep>* defer = nullptr;   // set while a gang is recorded: where the pipeline's launches go
 
     // what the last batch left behind for helios_make_blocks
     bool blocks_ready = false;

@@ -9,6 +9,8 @@
 
 using namespace helios;
 
+static_assert(kMaxGang == HELIOS_MAX_GANG, "the header's limit is the kernels' limit");
+
 struct helios_plan {
     helios_ctx* ctx = nullptr;
     hipGraph_t graph = nullptr;
@@ -32,6 +34,19 @@ struct helios_plan {
     StampRole stamp_roles[kMaxStampRoles];
     StampTable stamp_table{};
     int n_stamps = 0;
+    helios_gang* gang = nullptr;       // the gang this plan is a member of: it owns the recording and the event
+};
+
+// Mini-batches of several contexts recorded into the same launches (see helios_gang_create).
+struct helios_gang {
+    int n = 0;
+    helios_plan* member[kMaxGang] = {nullptr, nullptr, nullptr, nullptr};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    hipEvent_t done = nullptr;
+    bool launched = false;
 };
 
 namespace {
@@ -278,6 +293,41 @@ int copy_tiers_split(helios_ctx* c, int64_t n_max, void* out) {
     return HELIOS_OK;
 }
 
+// The launches of the pipeline go out at once, or, while a gang is being recorded, onto the member's list.
+int emit_sample(helios_ctx* c, const SampleJob& j) {
+    if (c->defer) {
+        PendingStep s{};
+        s.kind = kStepSample;
+        s.sample = j;
+        c->defer->push_back(s);
+        return HELIOS_OK;
+    }
+    HIP_TRY(c, launch_sample(c->stream, &j, 1));
+    return HELIOS_OK;
+}
+int emit_compact(helios_ctx* c, const CompactJob& j) {
+    if (c->defer) {
+        PendingStep s{};
+        s.kind = kStepCompact;
+        s.compact = j;
+        c->defer->push_back(s);
+        return HELIOS_OK;
+    }
+    HIP_TRY(c, launch_compact(c->stream, &j, 1));
+    return HELIOS_OK;
+}
+int emit_finish(helios_ctx* c, const FinishJob& j) {
+    if (c->defer) {
+        PendingStep s{};
+        s.kind = kStepFinish;
+        s.finish = j;
+        c->defer->push_back(s);
+        return HELIOS_OK;
+    }
+    HIP_TRY(c, launch_finish(c->stream, &j, 1));
+    return HELIOS_OK;
+}
+
 // The sampling pipeline, and with `b` the whole path: see pipeline.hip for the launches and their roles.
 int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                  uint64_t rng_seed, const helios_hop_out* hops, int64_t* sizes, const HopPlan& p, const BatchOut* b) {
@@ -320,6 +370,8 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         return fail(c, HELIOS_EINTERNAL, "launch bounds of the batch do not fit the scratch");
 
     const bool fold = n_seeds <= kFoldMaxSeeds;
+    if (c->defer && (!fold || !b || c->split_copies || c->missq || c->timing != 0))
+        return fail(c, HELIOS_EINTERNAL, "this call cannot be part of a gang");       // (refused earlier, with the reason)
     if (!fold) {
         uint32_t epoch;
         int rc = next_epoch(c, &epoch);
@@ -373,7 +425,8 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
                                   Count{stage_words(c, stage) + kStageHostCopy, u_max}, b->out,
                                   take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
         }
-        HIP_TRY(c, launch_sample(c->stream, ha, hop_blocks, link, link_blocks));
+        int rs = emit_sample(c, SampleJob{ha, hop_blocks, link, link_blocks});
+        if (rs) return rs;
         prev_flat[h] = Count{c->cnt + kCntFlat + h, p.flat_max[h]};
 
         // ---- compaction: this hop's samples into the next frontier, and stage h of the batch's ID list
@@ -428,7 +481,8 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
             look_blocks = tiles_for(look.n_max);
             look.stamps = take_stamps(c, HELIOS_ROLE_COMPACT_LOOKUP, h, look_blocks);
         }
-        HIP_TRY(c, launch_compact(c->stream, hopc, hopc_blocks, look, look_blocks));
+        rc = emit_compact(c, CompactJob{hopc, hopc_blocks, look, look_blocks});
+        if (rc) return rc;
         nf = Count{c->cnt + kCntFrontier + h + 1, !last ? p.frontier_max[h + 1] : 0};
     }
     if (!b) {
@@ -474,7 +528,8 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
             clear = ClearJob{batch_table(c, next), clear_slots};      // a recording picks the table on the device
             clear_blocks = std::min(256u, (clear_slots + kBlock * 16 - 1) / (kBlock * 16));
         }
-        HIP_TRY(c, launch_finish(c->stream, hbm, hbm_blocks, link, link_blocks, inv, inv_blocks, clear, clear_blocks, bt, vars));
+        int rf = emit_finish(c, FinishJob{hbm, hbm_blocks, link, link_blocks, inv, inv_blocks, clear, clear_blocks, bt, vars});
+        if (rf) return rf;
     }
     int rc = publish_stamps(c);
     if (rc) return rc;
@@ -542,6 +597,154 @@ int make_blocks_impl(helios_ctx* c, uint32_t table, uint32_t slots, int64_t n_se
         HIP_TRY(c, launch_local_ids(c->stream, hops[h].flat, nfl, flat_max[h], s, blocks[h].col_local, err));
     }
     return HELIOS_OK;
+}
+
+// ---- recorded batches: the parts that a plan of its own and a member of a gang share
+helios_plan* new_plan(helios_ctx* c) {
+    helios_plan* pl = new helios_plan();
+    pl->ctx = c;
+    if (hipHostMalloc(reinterpret_cast<void**>(&pl->err), 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess || !pl->err) {
+        (void)hipGetLastError();
+        delete pl;
+        fail(c, HELIOS_EHIP, "no pinned memory for the plan's error word");
+        return nullptr;
+    }
+    pl->err[0] = pl->err[1] = 0;
+    return pl;
+}
+
+void free_plan(helios_plan* pl) {
+    if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
+    if (pl->graph) (void)hipGraphDestroy(pl->graph);
+    if (pl->done) (void)hipEventDestroy(pl->done);
+    if (pl->err) (void)hipHostFree(pl->err);
+    delete pl;
+}
+
+// what the recording that has just ended left in the context goes into the plan
+void fill_plan(helios_plan* pl, helios_ctx* c, const HopPlan& p, int64_t n_seeds, int32_t n_hops, const helios_hop_out* hops,
+               int64_t* sizes) {
+    pl->n_scans = c->rec_scans;
+    pl->scratch_generation = c->scratch_generation;
+    pl->cache_generation = c->cache_generation;
+    pl->graph_generation = c->graph_generation;
+    pl->n_seeds = n_seeds;
+    pl->n_hops = n_hops;
+    for (int h = 0; h < n_hops; ++h) {
+        pl->frontier_max[h] = p.frontier_max[h];
+        pl->flat_max[h] = p.flat_max[h];
+        pl->hops[h] = hops[h];
+    }
+    pl->sizes = sizes;
+    pl->slots = c->last_slots;
+    pl->clear_slots = c->rec_clear_slots;
+    pl->missq = c->missq;
+    pl->n_stamps = c->n_stamps;
+    pl->stamp_table = c->stamp_table;
+    for (int q = 0; q < c->n_stamps; ++q) pl->stamp_roles[q] = c->stamp_roles[q];
+    reset_stamps(c);
+}
+
+// Everything of a launch up to the launch itself: the checks, the tables that the recording expects to be empty,
+// the batch's variables in the next ring slot.  Nothing is committed: if the launch does not happen, nothing has.
+int plan_prelaunch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed, uint32_t* io_round_out) {
+    helios_ctx* c = pl->ctx;
+    if (pl->n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
+    if (pl->scratch_generation != c->scratch_generation)
+        return fail(c, HELIOS_ESTATE, "the context's scratch was regrown after the batch was recorded; record it again");
+    if (pl->graph_generation != c->graph_generation || pl->cache_generation != c->cache_generation || !c->has_cache)
+        return fail(c, HELIOS_ESTATE, "helios_csr_load / helios_cache_build was called after the batch was recorded; record it again");
+    if (pl->missq != c->missq)
+        return fail(c, HELIOS_ESTATE, "the miss queue attached to the context is not the one the batch was recorded with");
+    uint32_t io_round = 0;
+    if (pl->missq) {
+        int rc = missq_next_round(c, pl->missq, &io_round);      // opened once the launch has succeeded
+        if (rc) return rc;
+    }
+    if (c->epoch + pl->n_scans >= (1u << 30) - 64) {
+        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * kScanRows * c->scan_stride, c->stream));
+        c->epoch = 0;
+    }
+    if (c->vars_unsynced + 1 >= kVarsRing) {     // the ring slot about to be reused may still be in flight
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        c->vars_unsynced = 0;
+    }
+    // The recording assumes that its own batch table and both hop tables are empty, and it empties clear_slots slots
+    // of the next batch's table.  What that leaves out is emptied here, by launches of their own (rare: only when
+    // batches of different sizes, or direct and recorded calls, alternate on a context).
+    const uint32_t which = static_cast<uint32_t>(c->batch_seq % kBatchTables), next = (which + 1) % kBatchTables;
+    int rc = clean_for_call(c, static_cast<int>(which));
+    if (rc) return rc;
+    if (c->batch_dirty[next] > pl->clear_slots) {
+        HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, next), c->batch_dirty[next]}));
+        c->batch_dirty[next] = 0;
+    }
+    BatchVars* slot = c->vars_ring + (c->vars_next % kVarsRing);
+    slot->rng_seed = rng_seed;
+    slot->seeds = seeds;
+    slot->epoch_base = c->epoch;
+    slot->io_round = io_round;
+    slot->table = which;
+    slot->reserved = 0;
+    __atomic_thread_fence(__ATOMIC_RELEASE);     // the slot is written before the launch is rung in
+    *io_round_out = io_round;
+    return HELIOS_OK;
+}
+
+// The launch has happened: only a batch that was launched takes its ring slot (the device counts the batches it
+// runs, and the two counts select the slot), its tables, its miss-queue round.
+void plan_postlaunch(helios_plan* pl, uint32_t io_round) {
+    helios_ctx* c = pl->ctx;
+    const uint32_t which = static_cast<uint32_t>(c->batch_seq % kBatchTables), next = (which + 1) % kBatchTables;
+    c->vars_next += 1;
+    c->vars_unsynced += 1;
+    c->epoch += pl->n_scans;
+    if (pl->missq) missq_commit_round(pl->missq, io_round);
+    c->batch_dirty[which] = pl->slots;
+    c->batch_dirty[next] = 0;
+    c->batch_seq += 1;
+    pl->batch_seq = c->batch_seq;
+    c->launch_seq += 1;
+    pl->launch_seq = c->launch_seq;
+    c->blocks_ready = true;
+    c->last_table = which;
+    c->last_slots = pl->slots;
+    c->last_n_seeds = pl->n_seeds;
+    c->last_n_hops = pl->n_hops;
+    for (int h = 0; h < pl->n_hops; ++h) {
+        c->last_frontier_max[h] = pl->frontier_max[h];
+        c->last_flat_max[h] = pl->flat_max[h];
+    }
+    c->n_stamps = pl->n_stamps;
+    c->stamp_table = pl->stamp_table;
+    for (int q = 0; q < pl->n_stamps; ++q) c->stamp_roles[q] = pl->stamp_roles[q];
+    c->timed_events = false;
+}
+
+// after the event behind the plan's last launch has been waited for
+int plan_retire(helios_plan* pl) {
+    helios_ctx* c = pl->ctx;
+    // everything launched on the context up to this plan's launch has finished
+    const uint64_t later = c->launch_seq - pl->launch_seq;
+    if (later < c->vars_unsynced) c->vars_unsynced = static_cast<uint32_t>(later);
+    return check_error_word(c, pl->err);                 // the errors of this plan's batches, not of others queued behind them
+}
+
+int plan_make_blocks(helios_plan* pl, const helios_block_out* blocks) {
+    helios_ctx* c = pl->ctx;
+    if (!blocks) return fail(c, HELIOS_EINVAL, "blocks is NULL");
+    if (pl->launch_seq == 0) return fail(c, HELIOS_ESTATE, "the plan has not been launched");
+    if (pl->scratch_generation != c->scratch_generation) return fail(c, HELIOS_ESTATE, "the context's scratch was regrown since");
+    // the plan's batch was number batch_seq - 1 of the context; its table is kept until the second batch after it
+    // is launched (that one empties it for the third)
+    const uint32_t table = static_cast<uint32_t>((pl->batch_seq - 1) % kBatchTables);
+    if (c->batch_seq - pl->batch_seq > 1 || c->batch_dirty[table] < pl->slots)
+        return fail(c, HELIOS_ESTATE, "two or more batches were launched on the context since this plan's: its table is gone");
+    if (!pl->sizes && c->batch_seq != pl->batch_seq)
+        return fail(c, HELIOS_ESTATE, "a plan recorded without a size array can only make blocks right after its launch");
+    DeviceGuard guard(c->device);
+    return make_blocks_impl(c, table, pl->slots, pl->n_seeds, pl->n_hops, pl->frontier_max, pl->flat_max, pl->sizes, pl->hops,
+                            blocks, pl->err);
 }
 
 }  // namespace
@@ -820,14 +1023,8 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
     rc = ensure_capacity(c, p.ids_max);          // allocate before recording starts
     if (rc) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    helios_plan* pl = new helios_plan();
-    pl->ctx = c;
-    if (hipHostMalloc(reinterpret_cast<void**>(&pl->err), 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess || !pl->err) {
-        (void)hipGetLastError();
-        delete pl;
-        return fail(c, HELIOS_EHIP, "helios_plan_create: no pinned memory for the plan's error word");
-    }
-    pl->err[0] = pl->err[1] = 0;
+    helios_plan* pl = new_plan(c);
+    if (!pl) return HELIOS_EHIP;
     c->recording = true;
     c->rec_scans = 0;
     c->err_now = pl->err;
@@ -843,35 +1040,14 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
     c->recording = false;
     c->err_now = c->err;
     c->blocks_ready = was_ready;                 // nothing has run
-    pl->n_scans = c->rec_scans;
     if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&pl->exec, pl->graph, nullptr, nullptr, 0);
     if (e == hipSuccess && rc == HELIOS_OK) e = hipEventCreateWithFlags(&pl->done, hipEventDisableTiming);
     if (e != hipSuccess || rc != HELIOS_OK) {
-        if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
-        if (pl->graph) (void)hipGraphDestroy(pl->graph);
-        (void)hipHostFree(pl->err);
-        delete pl;
+        free_plan(pl);
         if (rc != HELIOS_OK) return rc;
         return fail(c, HELIOS_EHIP, "recording the batch failed: %s", hipGetErrorString(e));
     }
-    pl->scratch_generation = c->scratch_generation;
-    pl->cache_generation = c->cache_generation;
-    pl->graph_generation = c->graph_generation;
-    pl->n_seeds = n_seeds;
-    pl->n_hops = n_hops;
-    for (int h = 0; h < n_hops; ++h) {
-        pl->frontier_max[h] = p.frontier_max[h];
-        pl->flat_max[h] = p.flat_max[h];
-        pl->hops[h] = hops[h];
-    }
-    pl->sizes = sizes;
-    pl->slots = c->last_slots;
-    pl->clear_slots = c->rec_clear_slots;
-    pl->missq = c->missq;
-    pl->n_stamps = c->n_stamps;
-    pl->stamp_table = c->stamp_table;
-    for (int q = 0; q < c->n_stamps; ++q) pl->stamp_roles[q] = c->stamp_roles[q];
-    reset_stamps(c);
+    fill_plan(pl, c, p, n_seeds, n_hops, hops, sizes);
     c->n_children += 1;
     c->plans.push_back(pl);
     *plan_out = pl;
@@ -879,91 +1055,30 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
 }
 
 int helios_plan_launch(helios_plan* pl, const int32_t* seeds, uint64_t rng_seed) {
-    if (!pl || !pl->ctx) return HELIOS_EINVAL;
+    if (!pl || !pl->ctx || pl->gang) return HELIOS_EINVAL;
     helios_ctx* c = pl->ctx;
-    if (pl->n_seeds > 0 && !seeds) return fail(c, HELIOS_EINVAL, "seeds is NULL");
-    if (pl->scratch_generation != c->scratch_generation)
-        return fail(c, HELIOS_ESTATE, "the context's scratch was regrown after the batch was recorded; record it again");
-    if (pl->graph_generation != c->graph_generation || pl->cache_generation != c->cache_generation || !c->has_cache)
-        return fail(c, HELIOS_ESTATE, "helios_csr_load / helios_cache_build was called after the batch was recorded; record it again");
-    if (pl->missq != c->missq)
-        return fail(c, HELIOS_ESTATE, "the miss queue attached to the context is not the one the batch was recorded with");
     DeviceGuard guard(c->device);
     uint32_t io_round = 0;
-    if (pl->missq) {
-        int rc = missq_next_round(c, pl->missq, &io_round);      // opened below, once the launch has succeeded
-        if (rc) return rc;
-    }
-    if (c->epoch + pl->n_scans >= (1u << 30) - 64) {
-        HIP_TRY(c, hipMemsetAsync(c->scan_status, 0, sizeof(unsigned long long) * kScanRows * c->scan_stride, c->stream));
-        c->epoch = 0;
-    }
-    if (c->vars_unsynced + 1 >= kVarsRing) {     // the ring slot about to be reused may still be in flight
-        HIP_TRY(c, hipStreamSynchronize(c->stream));
-        c->vars_unsynced = 0;
-    }
-    // The recording assumes that its own batch table and both hop tables are empty, and it empties clear_slots slots
-    // of the next batch's table.  What that leaves out is emptied here, by launches of their own (rare: only when
-    // batches of different sizes, or direct and recorded calls, alternate on a context).
-    const uint32_t which = static_cast<uint32_t>(c->batch_seq % kBatchTables), next = (which + 1) % kBatchTables;
-    int rc = clean_for_call(c, static_cast<int>(which));
+    int rc = plan_prelaunch(pl, seeds, rng_seed, &io_round);
     if (rc) return rc;
-    if (c->batch_dirty[next] > pl->clear_slots) {
-        HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, next), c->batch_dirty[next]}));
-        c->batch_dirty[next] = 0;
-    }
-    BatchVars* slot = c->vars_ring + (c->vars_next % kVarsRing);
-    slot->rng_seed = rng_seed;
-    slot->seeds = seeds;
-    slot->epoch_base = c->epoch;
-    slot->io_round = io_round;
-    slot->table = which;
-    slot->reserved = 0;
-    __atomic_thread_fence(__ATOMIC_RELEASE);     // the slot is written before the launch is rung in
     HIP_TRY(c, hipGraphLaunch(pl->exec, c->stream));
-    // only a batch that was launched takes its slot: the device counts the batches it runs, and the two
-    // counts select the slot
-    c->vars_next += 1;
-    c->vars_unsynced += 1;
-    c->epoch += pl->n_scans;
-    if (pl->missq) missq_commit_round(pl->missq, io_round);
-    c->batch_dirty[which] = pl->slots;
-    c->batch_dirty[next] = 0;
-    c->batch_seq += 1;
-    pl->batch_seq = c->batch_seq;
+    plan_postlaunch(pl, io_round);
     HIP_TRY(c, hipEventRecord(pl->done, c->stream));
-    c->launch_seq += 1;
-    pl->launch_seq = c->launch_seq;
-    c->blocks_ready = true;
-    c->last_table = which;
-    c->last_slots = pl->slots;
-    c->last_n_seeds = pl->n_seeds;
-    c->last_n_hops = pl->n_hops;
-    for (int h = 0; h < pl->n_hops; ++h) {
-        c->last_frontier_max[h] = pl->frontier_max[h];
-        c->last_flat_max[h] = pl->flat_max[h];
-    }
-    c->n_stamps = pl->n_stamps;
-    c->stamp_table = pl->stamp_table;
-    for (int q = 0; q < pl->n_stamps; ++q) c->stamp_roles[q] = pl->stamp_roles[q];
-    c->timed_events = false;
     return HELIOS_OK;
 }
 
 int helios_plan_wait(helios_plan* pl) {
-    if (!pl || !pl->ctx) return HELIOS_EINVAL;
+    if (!pl || !pl->ctx || pl->gang) return HELIOS_EINVAL;
     helios_ctx* c = pl->ctx;
     if (pl->launch_seq == 0) return HELIOS_OK;           // never launched
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipEventSynchronize(pl->done));
-    // everything launched on the context up to this plan's launch has finished
-    const uint64_t later = c->launch_seq - pl->launch_seq;
-    if (later < c->vars_unsynced) c->vars_unsynced = static_cast<uint32_t>(later);
-    return check_error_word(c, pl->err);                 // the errors of this plan's batches, not of others queued behind them
+    return plan_retire(pl);
 }
 
 int helios_plan_destroy(helios_plan* pl) {
     if (!pl) return HELIOS_EINVAL;
+    if (pl->gang) return HELIOS_EINVAL;                  // a gang's members go with the gang
     if (pl->ctx) {
         helios_ctx* c = pl->ctx;
         DeviceGuard guard(c->device);
@@ -971,11 +1086,187 @@ int helios_plan_destroy(helios_plan* pl) {
         c->n_children -= 1;
         c->plans.erase(std::remove(c->plans.begin(), c->plans.end(), pl), c->plans.end());
     }
-    if (pl->exec) (void)hipGraphExecDestroy(pl->exec);
-    if (pl->graph) (void)hipGraphDestroy(pl->graph);
-    if (pl->done) (void)hipEventDestroy(pl->done);
-    if (pl->err) (void)hipHostFree(pl->err);
-    delete pl;
+    free_plan(pl);
+    return HELIOS_OK;
+}
+
+int helios_gang_create(helios_ctx* const* ctxs, int32_t n_members, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                       const helios_batch_buffers* buffers, helios_gang** gang_out) {
+    if (!ctxs || !gang_out || n_members < 1 || !ctxs[0]) return HELIOS_EINVAL;
+    *gang_out = nullptr;
+    helios_ctx* c0 = ctxs[0];
+    if (n_members > kMaxGang) return fail(c0, HELIOS_EINVAL, "a gang has at most %d members", kMaxGang);
+    if (!buffers) return fail(c0, HELIOS_EINVAL, "buffers is NULL");
+    if (!c0->stream) return fail(c0, HELIOS_EINVAL, "a gang cannot be recorded on the default (NULL) stream");
+    if (n_seeds > kFoldMaxSeeds) return fail(c0, HELIOS_EINVAL, "a batch of a gang has at most %d seeds", kFoldMaxSeeds);
+    for (int m = 0; m < n_members; ++m) {
+        helios_ctx* c = ctxs[m];
+        if (!c) return fail(c0, HELIOS_EINVAL, "member %d is NULL", m);
+        for (int k = 0; k < m; ++k)
+            if (ctxs[k] == c) return fail(c0, HELIOS_EINVAL, "members %d and %d are the same context", k, m);
+        if (c->stream != c0->stream || c->device != c0->device)
+            return fail(c0, HELIOS_EINVAL, "member %d is not on the stream of member 0: a gang's contexts share one stream", m);
+        if (!c->has_graph || !c->has_cache) return fail(c0, HELIOS_ESTATE, "member %d has no graph or no cache", m);
+        if (c->row_bytes != c0->row_bytes) return fail(c0, HELIOS_EINVAL, "member %d has rows of another size", m);
+        if (c->timing != 0 || c->split_copies || c->missq)
+            return fail(c0, HELIOS_ESTATE, "member %d: timing, split copies and an attached miss queue do not go with a gang", m);
+        if (c->recording) return fail(c0, HELIOS_ESTATE, "member %d is being recorded", m);
+    }
+    DeviceGuard guard(c0->device);
+    HopPlan p[kMaxGang];
+    for (int m = 0; m < n_members; ++m) {
+        helios_ctx* c = ctxs[m];
+        int rc = plan_hops(c, n_seeds, fanouts, n_hops, buffers[m].hops, &p[m]);
+        if (rc == HELIOS_OK) rc = ensure_capacity(c, p[m].ids_max);          // allocate before recording starts
+        if (rc) return c == c0 ? rc : fail(c0, rc, "member %d: %s", m, c->errmsg);
+    }
+    HIP_TRY(c0, hipStreamSynchronize(c0->stream));
+    helios_gang* g = new helios_gang();
+    g->n = n_members;
+    g->device = c0->device;
+    g->stream = c0->stream;
+    int rc = HELIOS_OK;
+    for (int m = 0; m < n_members && rc == HELIOS_OK; ++m) {
+        g->member[m] = new_plan(ctxs[m]);
+        if (!g->member[m]) rc = fail(c0, HELIOS_EHIP, "no pinned memory for a member's error word");
+    }
+    std::vector<PendingStep> steps[kMaxGang];
+    bool was_ready[kMaxGang] = {false, false, false, false};
+    hipError_t e = hipSuccess;
+    if (rc == HELIOS_OK) {
+        for (int m = 0; m < n_members; ++m) {
+            helios_ctx* c = ctxs[m];
+            c->recording = true;
+            c->rec_scans = 0;
+            c->err_now = g->member[m]->err;
+            c->defer = &steps[m];
+            was_ready[m] = c->blocks_ready;
+        }
+        e = hipStreamBeginCapture(c0->stream, hipStreamCaptureModeThreadLocal);
+        if (e == hipSuccess) {
+            // every member prepares its launches (the seeds pointer and rng_seed are placeholders: recorded kernels
+            // read both from the batch's variables) ...
+            for (int m = 0; m < n_members && rc == HELIOS_OK; ++m) {
+                helios_ctx* c = ctxs[m];
+                const helios_batch_buffers& bb = buffers[m];
+                rc = prepare_batch_impl(c, reinterpret_cast<const int32_t*>(c->vars), n_seeds, fanouts, n_hops, 0, bb.hops, bb.sizes,
+                                        bb.unique, bb.unique_cap, bb.inverse, bb.n_unique, bb.out, bb.miss_pos, bb.miss_id,
+                                        bb.miss_slot, bb.miss_cap, bb.stats);
+                if (rc && c != c0) rc = fail(c0, rc, "member %d: %s", m, c->errmsg);
+            }
+            // ... and step by step the launches of all members go out as one
+            for (int m = 1; m < n_members && rc == HELIOS_OK; ++m) {
+                bool same = steps[m].size() == steps[0].size();
+                for (size_t k = 0; same && k < steps[0].size(); ++k) same = steps[m][k].kind == steps[0][k].kind;
+                if (!same) rc = fail(c0, HELIOS_EINTERNAL, "the members of a gang do not take the same steps");
+            }
+            for (size_t k = 0; k < steps[0].size() && rc == HELIOS_OK && e == hipSuccess; ++k) {
+                if (steps[0][k].kind == kStepSample) {
+                    SampleJob jobs[kMaxGang];
+                    for (int m = 0; m < n_members; ++m) jobs[m] = steps[m][k].sample;
+                    e = launch_sample(c0->stream, jobs, n_members);
+                } else if (steps[0][k].kind == kStepCompact) {
+                    CompactJob jobs[kMaxGang];
+                    for (int m = 0; m < n_members; ++m) jobs[m] = steps[m][k].compact;
+                    e = launch_compact(c0->stream, jobs, n_members);
+                } else {
+                    FinishJob jobs[kMaxGang];
+                    for (int m = 0; m < n_members; ++m) jobs[m] = steps[m][k].finish;
+                    e = launch_finish(c0->stream, jobs, n_members);
+                }
+            }
+            hipError_t e2 = hipStreamEndCapture(c0->stream, &g->graph);
+            if (rc == HELIOS_OK && e == hipSuccess && e2 != hipSuccess) e = e2;
+        }
+        for (int m = 0; m < n_members; ++m) {
+            helios_ctx* c = ctxs[m];
+            c->recording = false;
+            c->err_now = c->err;
+            c->defer = nullptr;
+            c->blocks_ready = was_ready[m];          // nothing has run
+        }
+    }
+    if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+    if (e == hipSuccess && rc == HELIOS_OK) e = hipEventCreateWithFlags(&g->done, hipEventDisableTiming);
+    if (e != hipSuccess || rc != HELIOS_OK) {
+        for (int m = 0; m < n_members; ++m)
+            if (g->member[m]) free_plan(g->member[m]);
+        if (g->exec) (void)hipGraphExecDestroy(g->exec);
+        if (g->graph) (void)hipGraphDestroy(g->graph);
+        if (g->done) (void)hipEventDestroy(g->done);
+        delete g;
+        (void)hipGetLastError();
+        if (rc != HELIOS_OK) return rc;
+        return fail(c0, HELIOS_EHIP, "recording the gang failed: %s", hipGetErrorString(e));
+    }
+    for (int m = 0; m < n_members; ++m) {
+        helios_ctx* c = ctxs[m];
+        helios_plan* pl = g->member[m];
+        fill_plan(pl, c, p[m], n_seeds, n_hops, buffers[m].hops, buffers[m].sizes);
+        pl->gang = g;
+        c->n_children += 1;
+        c->plans.push_back(pl);
+    }
+    *gang_out = g;
+    return HELIOS_OK;
+}
+
+int helios_gang_launch(helios_gang* g, const int32_t* const* seeds, const uint64_t* rng_seeds) {
+    if (!g || g->n < 1) return HELIOS_EINVAL;
+    helios_ctx* c0 = g->member[0]->ctx;
+    if (!seeds || !rng_seeds) return fail(c0, HELIOS_EINVAL, "seeds / rng_seeds is NULL");
+    DeviceGuard guard(g->device);
+    uint32_t io_round[kMaxGang] = {0, 0, 0, 0};
+    for (int m = 0; m < g->n; ++m) {
+        helios_plan* pl = g->member[m];
+        int rc = plan_prelaunch(pl, seeds[m], rng_seeds[m], &io_round[m]);
+        if (rc) return pl->ctx == c0 ? rc : fail(c0, rc, "member %d: %s", m, pl->ctx->errmsg);
+    }
+    HIP_TRY(c0, hipGraphLaunch(g->exec, g->stream));
+    for (int m = 0; m < g->n; ++m) plan_postlaunch(g->member[m], io_round[m]);
+    g->launched = true;
+    HIP_TRY(c0, hipEventRecord(g->done, g->stream));
+    return HELIOS_OK;
+}
+
+int helios_gang_wait(helios_gang* g, int32_t* member_status) {
+    if (!g || g->n < 1) return HELIOS_EINVAL;
+    helios_ctx* c0 = g->member[0]->ctx;
+    for (int m = 0; member_status && m < g->n; ++m) member_status[m] = HELIOS_OK;
+    if (!g->launched) return HELIOS_OK;
+    DeviceGuard guard(g->device);
+    HIP_TRY(c0, hipEventSynchronize(g->done));
+    int first = HELIOS_OK;
+    for (int m = 0; m < g->n; ++m) {
+        const int rc = plan_retire(g->member[m]);
+        if (member_status) member_status[m] = rc;
+        if (rc != HELIOS_OK && first == HELIOS_OK) first = g->member[m]->ctx == c0 ? rc : fail(c0, rc, "member %d: %s", m, g->member[m]->ctx->errmsg);
+    }
+    return first;
+}
+
+int helios_gang_make_blocks(helios_gang* g, int32_t member, const helios_block_out* blocks) {
+    if (!g || member < 0 || member >= g->n) return HELIOS_EINVAL;
+    return plan_make_blocks(g->member[member], blocks);
+}
+
+int helios_gang_destroy(helios_gang* g) {
+    if (!g) return HELIOS_EINVAL;
+    {
+        DeviceGuard guard(g->device);
+        (void)hipStreamSynchronize(g->stream);
+    }
+    for (int m = 0; m < g->n; ++m) {
+        helios_plan* pl = g->member[m];
+        helios_ctx* c = pl->ctx;
+        c->n_children -= 1;
+        c->plans.erase(std::remove(c->plans.begin(), c->plans.end(), pl), c->plans.end());
+        free_plan(pl);
+    }
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    if (g->done) (void)hipEventDestroy(g->done);
+    delete g;
     return HELIOS_OK;
 }
 
@@ -990,20 +1281,7 @@ int helios_make_blocks(helios_ctx* c, const helios_hop_out* hops, int32_t n_hops
 
 int helios_plan_make_blocks(helios_plan* pl, const helios_block_out* blocks) {
     if (!pl || !pl->ctx) return HELIOS_EINVAL;
-    helios_ctx* c = pl->ctx;
-    if (!blocks) return fail(c, HELIOS_EINVAL, "blocks is NULL");
-    if (pl->launch_seq == 0) return fail(c, HELIOS_ESTATE, "the plan has not been launched");
-    if (pl->scratch_generation != c->scratch_generation) return fail(c, HELIOS_ESTATE, "the context's scratch was regrown since");
-    // the plan's batch was number batch_seq - 1 of the context; its table is kept until the second batch after it
-    // is launched (that one empties it for the third)
-    const uint32_t table = static_cast<uint32_t>((pl->batch_seq - 1) % kBatchTables);
-    if (c->batch_seq - pl->batch_seq > 1 || c->batch_dirty[table] < pl->slots)
-        return fail(c, HELIOS_ESTATE, "two or more batches were launched on the context since this plan's: its table is gone");
-    if (!pl->sizes && c->batch_seq != pl->batch_seq)
-        return fail(c, HELIOS_ESTATE, "a plan recorded without a size array can only make blocks right after its launch");
-    DeviceGuard guard(c->device);
-    return make_blocks_impl(c, table, pl->slots, pl->n_seeds, pl->n_hops, pl->frontier_max, pl->flat_max, pl->sizes, pl->hops,
-                            blocks, pl->err);
+    return plan_make_blocks(pl, blocks);
 }
 
 int helios_hotness_add(helios_ctx* c, const int32_t* ids, int64_t n_max, const int64_t* n_dev, int32_t* counts) {

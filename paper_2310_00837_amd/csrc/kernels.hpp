@@ -27,20 +27,77 @@ hipError_t launch_frontier_count(hipStream_t stream, const CsrView& g, const int
                                  int64_t flat_cap, int64_t* n_flat_dev, int64_t* size_out, const ScanState& scan, int32_t* err);
 
 // ---- pipeline.hip: the launches of the sampling / whole-path pipeline; each carries one or more roles
+// Every launch takes the jobs of n mini-batches (1 <= n <= kMaxGang), one per member of a gang; the
+// members' roles share the launch.
+constexpr int kMaxGang = 4;
 // Sampling pass of one hop (see sample_dev.hpp), and beside it, if link_blocks > 0, a row copy from a
-// source behind the host link (the cached rows that the stage before has just listed).
-hipError_t launch_sample(hipStream_t stream, const HopArgs& hop, unsigned hop_blocks, const GatherArgs& link, unsigned link_blocks);
+// source behind the host link (the cached rows that the stage before has just listed).  The fan-outs
+// of all members select the same group width.
+struct SampleJob {
+    HopArgs hop;
+    unsigned hop_blocks;
+    GatherArgs link;
+    unsigned link_blocks;
+};
+hipError_t launch_sample(hipStream_t stream, const SampleJob* jobs, int n);
 // Compaction pass(es) after a hop: the hop's samples into the next frontier (hop_blocks > 0) and the
 // stage of the batch's ID list that the hop has completed, with its cache lookup (look_blocks > 0).
-hipError_t launch_compact(hipStream_t stream, const CompactArgs& hop, unsigned hop_blocks, const CompactArgs& look,
-                          unsigned look_blocks);
+struct CompactJob {
+    CompactArgs hop;
+    unsigned hop_blocks;
+    CompactArgs look;
+    unsigned look_blocks;
+};
+hipError_t launch_compact(hipStream_t stream, const CompactJob* jobs, int n);
 // The end of a batch in one launch: host-tier copy of the last stage, HBM-tier copy of all stages, the
 // inverse map, and the emptying of the table that the next batch of the context uses.  Any of the four
 // may be absent (0 workgroups).  With vars (a recorded batch) the table to empty is the one after the batch's
-// own among bt's, whatever clear.table says.
-hipError_t launch_finish(hipStream_t stream, const GatherArgs& hbm, unsigned hbm_blocks, const GatherArgs& link,
-                         unsigned link_blocks, const InverseArgs& inv, unsigned inv_blocks, const ClearJob& clear,
-                         unsigned clear_blocks, const BatchTables& bt, const BatchVars* vars);
+// own among bt's, whatever clear.table says.  The rows of all members have one size.
+struct FinishJob {
+    GatherArgs hbm;
+    unsigned hbm_blocks;
+    GatherArgs link;
+    unsigned link_blocks;
+    InverseArgs inv;
+    unsigned inv_blocks;
+    ClearJob clear;
+    unsigned clear_blocks;
+    BatchTables bt;
+    const BatchVars* vars;
+};
+hipError_t launch_finish(hipStream_t stream, const FinishJob* jobs, int n);
+// what the kernels receive: the members' arguments and workgroup ranges side by side
+struct SampleMember {
+    HopArgs hop;
+    GatherArgs link;
+    Role r_hop, r_link;
+};
+struct SampleGang {
+    SampleMember m[kMaxGang];
+    int n;
+};
+struct CompactMember {
+    CompactArgs hop, look;
+    Role r_hop, r_look;
+};
+struct CompactGang {
+    CompactMember m[kMaxGang];
+    int n;
+};
+struct FinishMember {
+    GatherArgs hbm, link;
+    InverseArgs inv;
+    ClearJob clear;
+    BatchTables bt;
+    const BatchVars* vars;
+    Role r_hbm, r_link, r_inv, r_clear;
+};
+struct FinishGang {
+    FinishMember m[kMaxGang];
+    int n;
+};
+static_assert(sizeof(SampleGang) <= 4096 && sizeof(CompactGang) <= 4096 && sizeof(FinishGang) <= 4096,
+              "kernel arguments are limited to 4 KB");
 hipError_t launch_clear(hipStream_t stream, const ClearJob& job);
 // reduces the stamps of n_roles roles (role q: workgroups[q] workgroups, stamps at clock + offset[q]) to
 // {earliest start, latest end} pairs in pinned host memory

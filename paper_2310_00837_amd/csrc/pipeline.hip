@@ -23,47 +23,69 @@ namespace helios {
 
 namespace {
 
+// Every launch below takes the roles of up to kMaxGang mini-batches (a "gang": batches of different
+// contexts that share a stream and go through their steps together), so that the chain of short,
+// latency-bound launches is paid once per gang and not once per batch.  A workgroup looks up which
+// member's role it belongs to; the members' arguments sit side by side in the kernel arguments.
+// The link roles of all members come first in every launch: they start first.
 template <int G>
-__global__ __launch_bounds__(kBlock) void batch_sample_kernel(HopArgs hop, Role r_hop, GatherArgs link, Role r_link) {
-    if (r_link.mine()) {                         // the link's workgroups come first: they start first
-        copy_rows_any(link, r_link.rb(), r_link.blocks, true);
-        return;
+__global__ __launch_bounds__(kBlock) void batch_sample_kernel(SampleGang g) {
+#pragma unroll 1
+    for (int m = 0; m < g.n; ++m) {
+        const SampleMember& a = g.m[m];
+        if (a.r_link.mine()) {
+            copy_rows_any(a.link, a.r_link.rb(), a.r_link.blocks, true);
+            return;
+        }
+        if (a.r_hop.mine()) {
+            sample_role<G>(a.hop, a.r_hop.rb(), a.r_hop.blocks);
+            return;
+        }
     }
-    if (r_hop.mine()) sample_role<G>(hop, r_hop.rb(), r_hop.blocks);
 }
 
-__global__ __launch_bounds__(kBlock) void batch_compact_kernel(CompactArgs hop, Role r_hop, CompactArgs look, Role r_look) {
-    if (r_look.mine()) {
-        compact_role<kCompactLookup>(look, r_look.rb(), r_look.blocks);
-        return;
+__global__ __launch_bounds__(kBlock) void batch_compact_kernel(CompactGang g) {
+#pragma unroll 1
+    for (int m = 0; m < g.n; ++m) {
+        const CompactMember& a = g.m[m];
+        if (a.r_look.mine()) {
+            compact_role<kCompactLookup>(a.look, a.r_look.rb(), a.r_look.blocks);
+            return;
+        }
+        if (a.r_hop.mine()) {
+            compact_role<kCompactNextHop>(a.hop, a.r_hop.rb(), a.r_hop.blocks);
+            return;
+        }
     }
-    if (r_hop.mine()) compact_role<kCompactNextHop>(hop, r_hop.rb(), r_hop.blocks);
 }
 
 // L, CPL, R: the shape of the HBM-tier copy loop for the row size; RF: rows per step of the host-tier copy
 template <int L, int CPL, int R, int RF>
-__global__ __launch_bounds__(kBlock) void batch_finish_kernel(GatherArgs hbm, Role r_hbm, GatherArgs link, Role r_link,
-                                                              InverseArgs inv, Role r_inv, ClearJob clear, Role r_clear,
-                                                              BatchTables bt, const BatchVars* vars) {
-    if (r_link.mine()) {
-        if constexpr (L == 0) copy_rows_long(link, r_link.rb(), r_link.blocks);
-        else copy_rows<L == 0 ? 64 : L, CPL == 0 ? 1 : CPL, RF == 0 ? 1 : RF>(link, r_link.rb(), r_link.blocks);
-        return;
-    }
-    if (r_hbm.mine()) {
-        if constexpr (L == 0) copy_rows_long(hbm, r_hbm.rb(), r_hbm.blocks);
-        else copy_rows<L == 0 ? 64 : L, CPL == 0 ? 1 : CPL, R == 0 ? 1 : R>(hbm, r_hbm.rb(), r_hbm.blocks);
-        return;
-    }
-    if (r_inv.mine()) {
-        inverse_role(inv, r_inv.rb(), r_inv.blocks);
-        return;
-    }
-    if (r_clear.mine()) {
-        // the table of the context's next batch; a recorded batch learns only on the device which one that is
-        unsigned long long* table = vars ? bt.table((vars->table + 1) % kBatchTables) : clear.table;
-        for (uint32_t w = r_clear.rb() * kBlock + threadIdx.x; table && w < clear.n_slots; w += r_clear.blocks * kBlock)
-            table[w] = kEmptySlot;
+__global__ __launch_bounds__(kBlock) void batch_finish_kernel(FinishGang g) {
+#pragma unroll 1
+    for (int m = 0; m < g.n; ++m) {
+        const FinishMember& a = g.m[m];
+        if (a.r_link.mine()) {
+            if constexpr (L == 0) copy_rows_long(a.link, a.r_link.rb(), a.r_link.blocks);
+            else copy_rows<L == 0 ? 64 : L, CPL == 0 ? 1 : CPL, RF == 0 ? 1 : RF>(a.link, a.r_link.rb(), a.r_link.blocks);
+            return;
+        }
+        if (a.r_hbm.mine()) {
+            if constexpr (L == 0) copy_rows_long(a.hbm, a.r_hbm.rb(), a.r_hbm.blocks);
+            else copy_rows<L == 0 ? 64 : L, CPL == 0 ? 1 : CPL, R == 0 ? 1 : R>(a.hbm, a.r_hbm.rb(), a.r_hbm.blocks);
+            return;
+        }
+        if (a.r_inv.mine()) {
+            inverse_role(a.inv, a.r_inv.rb(), a.r_inv.blocks);
+            return;
+        }
+        if (a.r_clear.mine()) {
+            // the table of the context's next batch; a recorded batch learns only on the device which one that is
+            unsigned long long* table = a.vars ? a.bt.table((a.vars->table + 1) % kBatchTables) : a.clear.table;
+            for (uint32_t w = a.r_clear.rb() * kBlock + threadIdx.x; table && w < a.clear.n_slots; w += a.r_clear.blocks * kBlock)
+                table[w] = kEmptySlot;
+            return;
+        }
     }
 }
 
@@ -107,37 +129,92 @@ __global__ __launch_bounds__(kPublishThreads) void clock_publish_kernel(const un
 
 }  // namespace
 
-hipError_t launch_sample(hipStream_t stream, const HopArgs& hop, unsigned hop_blocks, const GatherArgs& link, unsigned link_blocks) {
-    const Role r_link{0, link_blocks}, r_hop{link_blocks, hop_blocks};
-    const dim3 grid(link_blocks + hop_blocks), block(kBlock);
-    const int lanes = group_lanes(hop.fanout);
-    if (lanes == 8) hipLaunchKernelGGL(batch_sample_kernel<8>, grid, block, 0, stream, hop, r_hop, link, r_link);
-    else if (lanes == 16) hipLaunchKernelGGL(batch_sample_kernel<16>, grid, block, 0, stream, hop, r_hop, link, r_link);
-    else if (lanes == 32) hipLaunchKernelGGL(batch_sample_kernel<32>, grid, block, 0, stream, hop, r_hop, link, r_link);
-    else hipLaunchKernelGGL(batch_sample_kernel<64>, grid, block, 0, stream, hop, r_hop, link, r_link);
+// Workgroup ranges: the link roles of all members first, then the members' other roles.
+hipError_t launch_sample(hipStream_t stream, const SampleJob* jobs, int n) {
+    if (n < 1 || n > kMaxGang) return hipErrorInvalidValue;
+    SampleGang g{};
+    g.n = n;
+    unsigned at = 0;
+    for (int m = 0; m < n; ++m) {
+        g.m[m].hop = jobs[m].hop;
+        g.m[m].link = jobs[m].link;
+        g.m[m].r_link = Role{at, jobs[m].link_blocks};
+        at += jobs[m].link_blocks;
+    }
+    for (int m = 0; m < n; ++m) {
+        g.m[m].r_hop = Role{at, jobs[m].hop_blocks};
+        at += jobs[m].hop_blocks;
+        if (group_lanes(jobs[m].hop.fanout) != group_lanes(jobs[0].hop.fanout)) return hipErrorInvalidValue;
+    }
+    if (at == 0) return hipSuccess;
+    const dim3 grid(at), block(kBlock);
+    const int lanes = group_lanes(jobs[0].hop.fanout);
+    if (lanes == 8) hipLaunchKernelGGL(batch_sample_kernel<8>, grid, block, 0, stream, g);
+    else if (lanes == 16) hipLaunchKernelGGL(batch_sample_kernel<16>, grid, block, 0, stream, g);
+    else if (lanes == 32) hipLaunchKernelGGL(batch_sample_kernel<32>, grid, block, 0, stream, g);
+    else hipLaunchKernelGGL(batch_sample_kernel<64>, grid, block, 0, stream, g);
     return hipGetLastError();
 }
 
-hipError_t launch_compact(hipStream_t stream, const CompactArgs& hop, unsigned hop_blocks, const CompactArgs& look,
-                          unsigned look_blocks) {
-    const Role r_look{0, look_blocks}, r_hop{look_blocks, hop_blocks};
-    hipLaunchKernelGGL(batch_compact_kernel, dim3(look_blocks + hop_blocks), dim3(kBlock), 0, stream, hop, r_hop, look, r_look);
+hipError_t launch_compact(hipStream_t stream, const CompactJob* jobs, int n) {
+    if (n < 1 || n > kMaxGang) return hipErrorInvalidValue;
+    CompactGang g{};
+    g.n = n;
+    unsigned at = 0;
+    for (int m = 0; m < n; ++m) {
+        g.m[m].hop = jobs[m].hop;
+        g.m[m].look = jobs[m].look;
+        g.m[m].r_look = Role{at, jobs[m].look_blocks};
+        at += jobs[m].look_blocks;
+    }
+    for (int m = 0; m < n; ++m) {
+        g.m[m].r_hop = Role{at, jobs[m].hop_blocks};
+        at += jobs[m].hop_blocks;
+    }
+    if (at == 0) return hipSuccess;
+    hipLaunchKernelGGL(batch_compact_kernel, dim3(at), dim3(kBlock), 0, stream, g);
     return hipGetLastError();
 }
 
-hipError_t launch_finish(hipStream_t stream, const GatherArgs& hbm, unsigned hbm_blocks, const GatherArgs& link,
-                         unsigned link_blocks, const InverseArgs& inv, unsigned inv_blocks, const ClearJob& clear,
-                         unsigned clear_blocks, const BatchTables& bt, const BatchVars* vars) {
-    const Role r_link{0, link_blocks}, r_hbm{link_blocks, hbm_blocks}, r_inv{link_blocks + hbm_blocks, inv_blocks},
-        r_clear{link_blocks + hbm_blocks + inv_blocks, clear_blocks};
-    const unsigned total = link_blocks + hbm_blocks + inv_blocks + clear_blocks;
-    if (total == 0) return hipSuccess;
-    const dim3 grid(total), block(kBlock);
-    const int chunks = hbm_blocks > 0 ? hbm.chunks : link_blocks > 0 ? link.chunks : 1;
+hipError_t launch_finish(hipStream_t stream, const FinishJob* jobs, int n) {
+    if (n < 1 || n > kMaxGang) return hipErrorInvalidValue;
+    FinishGang g{};
+    g.n = n;
+    unsigned at = 0;
+    int chunks = 0;
+    for (int m = 0; m < n; ++m) {
+        FinishMember& a = g.m[m];
+        a.hbm = jobs[m].hbm;
+        a.link = jobs[m].link;
+        a.inv = jobs[m].inv;
+        a.clear = jobs[m].clear;
+        a.bt = jobs[m].bt;
+        a.vars = jobs[m].vars;
+        a.r_link = Role{at, jobs[m].link_blocks};
+        at += jobs[m].link_blocks;
+        // the copies of all members move rows of one size (the loops are compiled for it)
+        const int mine = jobs[m].hbm_blocks > 0 ? jobs[m].hbm.chunks : jobs[m].link_blocks > 0 ? jobs[m].link.chunks : 0;
+        if (mine > 0 && chunks > 0 && mine != chunks) return hipErrorInvalidValue;
+        if (mine > 0) chunks = mine;
+    }
+    for (int m = 0; m < n; ++m) {
+        FinishMember& a = g.m[m];
+        a.r_hbm = Role{at, jobs[m].hbm_blocks};
+        at += jobs[m].hbm_blocks;
+    }
+    for (int m = 0; m < n; ++m) {
+        FinishMember& a = g.m[m];
+        a.r_inv = Role{at, jobs[m].inv_blocks};
+        at += jobs[m].inv_blocks;
+        a.r_clear = Role{at, jobs[m].clear_blocks};
+        at += jobs[m].clear_blocks;
+    }
+    if (at == 0) return hipSuccess;
+    if (chunks == 0) chunks = 1;
+    const dim3 grid(at), block(kBlock);
     // the two copies move rows of the same size; their loops differ in the rows a group takes per step
-#define HELIOS_CALL_(L, CPL, R)                                                                                            \
-    hipLaunchKernelGGL((batch_finish_kernel<L, CPL, R, far_rows_per_step(L, CPL)>), grid, block, 0, stream, hbm, r_hbm, link, r_link, inv, \
-                       r_inv, clear, r_clear, bt, vars)
+#define HELIOS_CALL_(L, CPL, R) \
+    hipLaunchKernelGGL((batch_finish_kernel<L, CPL, R, far_rows_per_step(L, CPL)>), grid, block, 0, stream, g)
     HELIOS_COPY_SHAPE_SWITCH(chunks, false, HELIOS_CALL_);
 #undef HELIOS_CALL_
     return hipGetLastError();

@@ -30,7 +30,8 @@ _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELI
 EXPORTS = ["helios_create", "helios_destroy", "helios_last_error", "helios_reserve", "helios_sync",
            "helios_csr_load", "helios_cache_build", "helios_cache_fill", "helios_sample", "helios_dedup", "helios_dedup_noalloc",
            "helios_gather", "helios_gather_miss", "helios_prepare_batch", "helios_host_alloc", "helios_host_free", "helios_calibration_copy", "helios_make_blocks",
-           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_wait", "helios_plan_make_blocks", "helios_plan_destroy", "helios_set_param", "helios_set_timing",
+           "helios_hotness_add", "helios_hotness_order", "helios_plan_create", "helios_plan_launch", "helios_plan_wait", "helios_plan_make_blocks", "helios_plan_destroy",
+           "helios_gang_create", "helios_gang_launch", "helios_gang_wait", "helios_gang_make_blocks", "helios_gang_destroy", "helios_set_param", "helios_set_timing",
            "helios_gather_times", "helios_batch_ticks", "helios_missq_create", "helios_missq_submit", "helios_missq_complete",
            "helios_missq_attach", "helios_missq_faulted", "helios_missq_counters", "helios_missq_destroy"]
 
@@ -42,6 +43,15 @@ class HopOut(C.Structure):
 
 class BlockOut(C.Structure):
     _fields_ = [("row_local", C.c_void_p), ("col_local", C.c_void_p)]
+
+
+class BatchBuffersC(C.Structure):
+    _fields_ = [("hops", C.POINTER(HopOut)), ("sizes", C.c_void_p), ("unique", C.c_void_p), ("unique_cap", C.c_int64),
+                ("inverse", C.c_void_p), ("n_unique", C.c_void_p), ("out", C.c_void_p), ("miss_pos", C.c_void_p),
+                ("miss_id", C.c_void_p), ("miss_slot", C.c_void_p), ("miss_cap", C.c_int64), ("stats", C.c_void_p)]
+
+
+MAX_GANG = 4
 
 
 class RoleTicks(C.Structure):
@@ -91,6 +101,11 @@ def load_library() -> C.CDLL:
     lib.helios_plan_wait.argtypes = [vp]
     lib.helios_plan_make_blocks.argtypes = [vp, C.POINTER(BlockOut)]
     lib.helios_plan_destroy.argtypes = [vp]
+    lib.helios_gang_create.argtypes = [C.POINTER(vp), i32, i64, C.POINTER(i32), i32, C.POINTER(BatchBuffersC), C.POINTER(vp)]
+    lib.helios_gang_launch.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64)]
+    lib.helios_gang_wait.argtypes = [vp, C.POINTER(i32)]
+    lib.helios_gang_make_blocks.argtypes = [vp, i32, C.POINTER(BlockOut)]
+    lib.helios_gang_destroy.argtypes = [vp]
     lib.helios_host_alloc.argtypes = [i64]
     lib.helios_host_alloc.restype = vp
     lib.helios_host_free.argtypes = [vp]
@@ -223,6 +238,95 @@ class Plan:
         if self._p is not None and self._p.value:
             _lib.helios_plan_destroy(self._p)
             self._p = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+@dataclass
+class BatchBuffers:
+    """The caller-owned outputs of one whole-path batch (the buffer arguments of helios_prepare_batch)."""
+    hops: Sequence["HopBuffers"]
+    sizes: torch.Tensor
+    unique: torch.Tensor
+    inverse: Optional[torch.Tensor]
+    n_unique: torch.Tensor
+    out: torch.Tensor
+    miss_pos: torch.Tensor
+    miss_id: torch.Tensor
+    miss_slot: torch.Tensor
+    stats: torch.Tensor
+
+
+class Gang:
+    """The mini-batches of several contexts recorded into the same launches (see helios_gang_create).
+    launch(seeds, rng_seeds) enqueues one mini-batch per member on the contexts' shared stream."""
+
+    def __init__(self, ctxs: Sequence["Helios"], n_seeds: int, fanouts: Sequence[int], buffers: Sequence[BatchBuffers]):
+        assert len(ctxs) == len(buffers) and len(ctxs) >= 1
+        self._ctxs, self.n_seeds, self._keep = list(ctxs), n_seeds, list(buffers)
+        self._g = C.c_void_p()
+        n = len(ctxs)
+        handles = (C.c_void_p * n)(*[c._h for c in ctxs])
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        arr = (BatchBuffersC * n)()
+        self._hop_arrays = []
+        for m, (c, b) in enumerate(zip(ctxs, buffers)):
+            assert len(b.hops) == len(fanouts)
+            _dev(b.unique, torch.int32, "unique")
+            _dev_accessible(b.sizes, torch.int64, "sizes"), _dev_accessible(b.n_unique, torch.int64, "n_unique")
+            _dev_accessible(b.stats, torch.int64, "stats")
+            if b.inverse is not None:
+                _dev(b.inverse, torch.int32, "inverse")
+                assert b.inverse.numel() >= n_seeds + sum(h.flat.numel() for h in b.hops)
+            if not b.out.is_cuda or b.out.numel() * b.out.element_size() < b.unique.numel() * c.row_bytes:
+                raise TypeError("out must be a GPU tensor with room for unique_cap rows")
+            for t in (b.miss_pos, b.miss_id, b.miss_slot):
+                _dev(t, torch.int32, "miss list")
+            hop_arr = c._hop_array(b.hops)
+            self._hop_arrays.append(hop_arr)
+            arr[m] = BatchBuffersC(hop_arr, _ptr(b.sizes), _ptr(b.unique), b.unique.numel(), _ptr(b.inverse), _ptr(b.n_unique),
+                                   _ptr(b.out), _ptr(b.miss_pos), _ptr(b.miss_id), _ptr(b.miss_slot),
+                                   min(b.miss_pos.numel(), b.miss_id.numel(), b.miss_slot.numel()), _ptr(b.stats))
+        ctxs[0]._check(_lib.helios_gang_create(handles, n, n_seeds, fan, len(fanouts), arr, C.byref(self._g)))
+        for c in ctxs:
+            c._children.append(self)
+
+    def launch(self, seeds: Sequence[torch.Tensor], rng_seeds: Sequence[int]) -> None:
+        n = len(self._ctxs)
+        assert len(seeds) == n and len(rng_seeds) == n
+        for t in seeds:
+            _dev(t, torch.int32, "seeds")
+            assert t.numel() == self.n_seeds
+        ptrs = (C.c_void_p * n)(*[t.data_ptr() for t in seeds])
+        rs = (C.c_uint64 * n)(*[int(r) for r in rng_seeds])
+        self._ctxs[0]._check(_lib.helios_gang_launch(self._g, ptrs, rs))
+
+    def wait(self, raise_on_error: bool = True) -> List[int]:
+        """Waits for the gang's last launch; returns every member's own device-side error code."""
+        st = (C.c_int32 * len(self._ctxs))()
+        rc = _lib.helios_gang_wait(self._g, st)
+        if rc != OK and raise_on_error:
+            self._ctxs[0]._check(rc)
+        return list(st)
+
+    def make_blocks(self, member: int, row_local: Sequence[torch.Tensor], col_local: Sequence[torch.Tensor]) -> None:
+        hops = self._keep[member].hops
+        arr = (BlockOut * len(hops))()
+        for i, hb in enumerate(hops):
+            _dev(row_local[i], torch.int32, "row_local"), _dev(col_local[i], torch.int32, "col_local")
+            assert row_local[i].numel() >= min(hb.frontier.numel(), hb.indptr.numel() - 1)
+            assert col_local[i].numel() >= hb.flat.numel()
+            arr[i] = BlockOut(row_local[i].data_ptr(), col_local[i].data_ptr())
+        self._ctxs[member]._check(_lib.helios_gang_make_blocks(self._g, member, arr))
+
+    def destroy(self) -> None:
+        if self._g is not None and self._g.value:
+            _lib.helios_gang_destroy(self._g)
+            self._g = None
 
     def __del__(self):
         try:

@@ -168,6 +168,83 @@ def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, t
     return results
 
 
+def gangs_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, tabs_dev, batch, fanouts, jobs,
+                    members: int = 3, n_gangs: int = 2, tune=None):
+    """bench.py's gang configuration: n_gangs streams, on each a gang of `members` contexts with one buffer set
+    per member; the jobs go out `members` at a time, to the gangs in turn, and a gang is waited for
+    (helios_gang_wait) before it gets its next batches.  Misses are not served (result key "out_before_miss").
+    jobs: list of (seeds on the GPU, rng_seed), a multiple of `members`.  Returns one result dict per job."""
+    import torch as T
+    assert len(jobs) % members == 0
+    dev = offsets.device
+    gangs = []
+    K = len(fanouts)
+    for _ in range(n_gangs):
+        st = T.cuda.Stream(device=dev)
+        ctxs, sets = [], []
+        for _ in range(members):
+            ctx = helios.Helios(dev.index or 0, stream=st)
+            ctx.csr_load(offsets, indices)
+            ctx.cache_build(order, n_hbm, n_host, row_bytes, *tabs_dev)
+            if tune is not None:
+                tune(ctx)
+            hops = helios.alloc_hops(batch, fanouts, dev)
+            cap = batch + sum(hb.flat.numel() for hb in hops)
+            ctx.reserve(cap)
+            ctx.sync()
+            ctxs.append(ctx)
+            sets.append(helios.BatchBuffers(
+                hops=hops, sizes=T.zeros(2 * K, dtype=T.int64).pin_memory(), unique=T.empty(cap, dtype=T.int32, device=dev),
+                inverse=T.empty(cap, dtype=T.int32, device=dev), n_unique=T.zeros(1, dtype=T.int64).pin_memory(),
+                out=T.full((cap, row_bytes), SENTINEL, dtype=T.uint8, device=dev),
+                miss_pos=T.empty(cap, dtype=T.int32, device=dev), miss_id=T.empty(cap, dtype=T.int32, device=dev),
+                miss_slot=T.empty(cap, dtype=T.int32, device=dev), stats=T.zeros(4, dtype=T.int64).pin_memory()))
+        T.cuda.synchronize()
+        gangs.append(dict(stream=st, ctxs=ctxs, sets=sets, gang=helios.Gang(ctxs, batch, fanouts, sets), jobs=None))
+    T.cuda.synchronize()
+
+    def collect(gd):
+        st = gd["gang"].wait()
+        assert all(code == 0 for code in st), st
+        res = []
+        for bs in gd["sets"]:
+            sizes, U, nm = bs.sizes, int(bs.n_unique[0]), int(bs.stats[3])
+            r = {"hops": []}
+            for k in range(K):
+                nf, nfl = int(sizes[2 * k]), int(sizes[2 * k + 1])
+                hb = bs.hops[k]
+                r["hops"].append((hb.frontier[:nf].cpu().numpy(), hb.indptr[:nf + 1].cpu().numpy(), hb.flat[:nfl].cpu().numpy()))
+            n_cat = batch + sum(int(sizes[2 * k + 1]) for k in range(K))
+            r.update(unique=bs.unique[:U].cpu().numpy(), inverse=bs.inverse[:n_cat].cpu().numpy(),
+                     stats=bs.stats.numpy().copy(), miss_pos=bs.miss_pos[:nm].cpu().numpy(),
+                     miss_id=bs.miss_id[:nm].cpu().numpy(), miss_slot=bs.miss_slot[:nm].cpu().numpy(),
+                     out_before_miss=bs.out[:U].cpu().numpy())
+            res.append(r)
+        return res
+
+    results = [None] * len(jobs)
+    for r in range(len(jobs) // members):
+        gd = gangs[r % n_gangs]
+        if gd["jobs"] is not None:
+            first = gd["jobs"]
+            results[first:first + members] = collect(gd)
+            with T.cuda.stream(gd["stream"]):
+                for bs in gd["sets"]:
+                    bs.out.fill_(SENTINEL)
+        mine = jobs[r * members:(r + 1) * members]
+        gd["gang"].launch([j[0] for j in mine], [j[1] for j in mine])
+        gd["jobs"] = r * members
+    for gd in gangs:
+        if gd["jobs"] is not None:
+            first = gd["jobs"]
+            results[first:first + members] = collect(gd)
+    for gd in gangs:
+        gd["gang"].destroy()
+        for ctx in gd["ctxs"]:
+            ctx.close()
+    return results
+
+
 def oracle_path(oracle, off, idx, seeds, fanouts, rng_seed, rank, n_hbm, n_host, hbm_tab, host_tab, standin_tab,
                 row_bytes):
     hops = oracle.sample(off, idx, seeds, fanouts, rng_seed)
