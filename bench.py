@@ -1,10 +1,12 @@
 """Benchmark of the Helios mini-batch preparation path on one MI355X.
 
 A step is one pass of the whole path (k-hop sampling, de-duplication, cache lookup, gather of
-both cached tiers, miss list: a recorded helios_prepare_batch + one wait for that batch) over one
-batch of seeds of a synthetic workload whose graph, feature tables and seeds are resident before
-the timed region (graph, cache map and HBM tier in HBM; host tier and storage stand-in in pinned
-host memory, where the method keeps them).  Prints ONE JSON line.
+both cached tiers, miss list: a recorded helios_prepare_batch) over one batch of seeds of a
+synthetic workload whose graph, feature tables and seeds are resident before the timed region
+(graph, cache map and HBM tier in HBM; host tier and storage stand-in in pinned host memory,
+where the method keeps them).  In the timed region the batches run in gangs: the mini-batches
+of four contexts share every launch (helios_gang_*), three such gangs in flight; the same
+K steps by separate recordings on three streams are reported under "lanes".  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--hbm-frac P]
 
@@ -407,6 +409,68 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
                 "batch_span_us": batch_span / count,
                 "note": "device clock, one mini-batch in flight, recorded batch; times from the batch's first workgroup"}
 
+    class GangOnStream:
+        """A gang of `members` contexts on one stream, one buffer set per member: the batches of the members go
+        through the same launches.  Every member runs one directly launched batch first (see Lane.record)."""
+
+        def __init__(self, members: int, cap: int, host_blocks: int):
+            self.stream = torch.cuda.Stream(device=dev)
+            self.ctxs, self.sets = [], []
+            for _ in range(members):
+                ctx = helios.Helios(0, stream=self.stream)
+                ctx.csr_load(offsets, indices)
+                ctx.cache_build(order, tiers.n_hbm, tiers.n_host, rb, tiers.hbm, tiers.host, tiers.standin)
+                if host_blocks > 0:
+                    ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, host_blocks)
+                ctx.reserve(cap)
+                bs = Buffers(cap)
+                ctx.prepare_batch(seeds[0], sp.fanouts, rng_seeds[0], *bs.args())
+                ctx.sync()
+                self.ctxs.append(ctx)
+                self.sets.append(bs)
+            self.gang = helios.Gang(self.ctxs, B, sp.fanouts, [
+                helios.BatchBuffers(hops=bs.hops, sizes=bs.sizes, unique=bs.unique, inverse=bs.inverse, n_unique=bs.n_unique,
+                                    out=bs.out, miss_pos=bs.mp, miss_id=bs.mi, miss_slot=bs.ms, stats=bs.stats)
+                for bs in self.sets])
+            self.live = 0                      # batches of the gang's last launch that count
+
+        def close(self) -> None:
+            self.gang.destroy()
+            for ctx in self.ctxs:
+                ctx.close()
+
+    gangs = []
+
+    def region_gangs(first: int, count: int):
+        """`count` steps by gangs: the batches go out M at a time, to the gangs in turn (each on its own stream); a gang
+        is waited for (helios_gang_wait) before it gets its next batches.  If M does not divide count, the last launch is
+        filled up with batches that are run but not counted.  Returns (seconds, sums)."""
+        acc = new_acc()
+        M = len(gangs[0].ctxs)
+        rounds = (count + M - 1) // M
+        for gd in gangs:
+            gd.live = 0
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for r in range(rounds):
+            gd = gangs[r % len(gangs)]
+            if gd.live:
+                gd.gang.wait()
+                for bs in gd.sets[:gd.live]:
+                    tally(acc, bs)
+            ks = [min(r * M + m, count - 1) for m in range(M)]
+            gd.gang.launch([seeds[first + k] for k in ks], [rng_seeds[first + k] for k in ks])
+            gd.live = min(M, count - r * M)
+        for r in range(max(0, rounds - len(gangs)), rounds):
+            gd = gangs[r % len(gangs)]
+            if gd.live:
+                gd.gang.wait()
+                for bs in gd.sets[:gd.live]:
+                    tally(acc, bs)
+                gd.live = 0
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_begin, acc
+
     result = {"dtype": "int32 ids / byte rows (" + ("fp32" if sp.dtype == torch.float32 else "fp16") + " features)",
               "config": {"workload": f"BASELINE.json configs[{cfg}] {sp.name}", "n_nodes": g.n_nodes, "n_edges": g.n_edges,
                          "batch": B, "fanouts": sp.fanouts, "row_bytes": rb,
@@ -445,11 +509,36 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
         h.close()
         return result
 
-    # ---------------- the timed region: W warm-up steps, then K whole steps (S1-S5), D x P mini-batches in flight
+    # ---------------- the timed region: W warm-up steps, then K whole steps (S1-S5)
+    # by lanes: D contexts on D streams, P mini-batches queued on each
     region_queued(0, Wm)
     elapsed, acc, all_runs = repeated(region_queued, Wm, K)
-    result.update(value=K / elapsed, ms_per_step=elapsed / K * 1e3, runs_ms_per_step=[s / K * 1e3 for s in all_runs],
-                  batches_in_flight=D * P)
+    lanes_res = {"value": K / elapsed, "ms_per_step": elapsed / K * 1e3, "runs_ms_per_step": [s / K * 1e3 for s in all_runs],
+                 "batches_in_flight": D * P, "host_link_use": 1.0 * acc["host_rows"] * rb / elapsed / 1e9 / link_gbs if link_gbs > 0 else None,
+                 "note": "the K steps by helios_plan_launch + helios_plan_wait per batch: %d contexts on %d streams, %d "
+                         "mini-batches queued on each" % (D, D, P)}
+    # by gangs (the headline): the mini-batches of M contexts share every launch, G such gangs on a stream each
+    n_members = min(args.gang_members, helios.MAX_GANG) if B <= 2048 else 0
+    if n_members > 0:
+        for _ in range(max(1, args.gangs)):
+            gangs.append(GangOnStream(n_members, lanes[0].cap, args.gang_host_blocks))
+        torch.cuda.synchronize()
+        region_gangs(0, Wm)
+        elapsed, acc, all_runs = repeated(region_gangs, Wm, K)
+        for gd in gangs:
+            gd.close()
+        n_gangs = len(gangs)
+        gangs.clear()
+        result["config"]["step"] = (
+            "one mini-batch of a recorded gang (helios_gang_launch: sample, dedup, lookup, HBM+host gather, miss list of %d "
+            "mini-batches in the same launches; helios_gang_wait), %d gangs of %d contexts, each gang on its own stream with "
+            "one launch sequence queued; median of %d runs of the K steps" % (n_members, n_gangs, n_members, args.repeats))
+        result["lanes"] = lanes_res
+        result.update(value=K / elapsed, ms_per_step=elapsed / K * 1e3, runs_ms_per_step=[s / K * 1e3 for s in all_runs],
+                      batches_in_flight=n_members * n_gangs)
+    else:
+        result.update(value=lanes_res["value"], ms_per_step=lanes_res["ms_per_step"], runs_ms_per_step=lanes_res["runs_ms_per_step"],
+                      batches_in_flight=D * P)
     link_whole_run = 1.0 * acc["host_rows"] * rb / elapsed / 1e9
     result["roofline_host_link"]["in_the_timed_region"] = {
         "link_GBs": link_whole_run, "frac": link_whole_run / link_gbs if link_gbs > 0 else None,
@@ -573,6 +662,12 @@ def main() -> int:
     ap.add_argument("--per-lane", type=int, default=2,
                     help="mini-batches queued per lane in the timed region (buffer sets per context): one runs, "
                          "the next waits behind it on the lane's stream")
+    ap.add_argument("--gang-members", type=int, default=4,
+                    help="members of a gang in the timed region (contexts whose mini-batches share every launch); 0: the timed "
+                         "region is the one by lanes (--depth, --per-lane)")
+    ap.add_argument("--gangs", type=int, default=3, help="gangs in flight in the timed region, each on its own stream")
+    ap.add_argument("--gang-host-blocks", type=int, default=0,
+                    help="workgroups of a gang member's host-tier copy (0: the library's default, a member's share of what fills the link)")
     ap.add_argument("--missq-queues", type=int, default=128,
                     help="queues of the asynchronous miss queue region (0 skips the region)")
     ap.add_argument("--missq-threads", type=int, default=4, help="service threads per miss queue (one queue per lane)")

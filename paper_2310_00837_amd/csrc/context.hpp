@@ -121,6 +121,7 @@ struct helios_ctx {
     uint64_t scratch_generation = 0;
 
     std::vector<helios::PendingStep>* defer = nullptr;   // set while a gang is recorded: where the pipeline's launches go
+    int link_share = 1;                        // batches whose host-tier copies share the link in every launch (a gang's members)
 
     // what the last batch left behind for helios_make_blocks
     bool blocks_ready = false;

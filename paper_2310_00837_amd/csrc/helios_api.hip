@@ -265,6 +265,18 @@ GatherArgs tier_copy_args(helios_ctx* c, int tier, const int64_t* begin, Count e
                       begin, end, c->row_bytes / 16, static_cast<chunk16*>(out), -1, -1, c->err_now, stamps};
 }
 
+// Workgroups of a host-tier copy role over a list of at most n_max rows.  The members of a gang copy at the same
+// time: they share what one copy alone would take to fill the link (at least 8 workgroups each).
+unsigned link_role_blocks(const helios_ctx* c, int64_t n_max) {
+    const int32_t chunks = c->row_bytes / 16;
+    unsigned limit = c->host_blocks;
+    if (limit == 0 && c->link_share > 1) {
+        const unsigned alone = copy_role_blocks(chunks, true, int64_t{1} << 40, 0, 0);
+        limit = std::max(8u, (alone + c->link_share - 1) / c->link_share);
+    }
+    return copy_role_blocks(chunks, true, n_max, limit, 0);
+}
+
 // The HBM hits of the context's last finished lookup: the best guess for the next batch's (0 = none yet).  The
 // word is written by the lookup's last workgroup and read here without waiting: it only sizes a grid.
 int64_t expected_hbm_rows(const helios_ctx* c) {
@@ -420,7 +432,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         if (b && h > 0 && !c->split_copies && c->n_host > 0 && u_max > 0) {
             const int stage = h - 1;
             const int64_t stage_max = std::min(u_max, stage == 0 ? n_seeds + p.flat_max[0] : p.flat_max[stage]);
-            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks, 0);
+            link_blocks = link_role_blocks(c, stage_max);
             link = tier_copy_args(c, 1, stage > 0 ? stage_words(c, stage - 1) + kStageHostCopy : nullptr,
                                   Count{stage_words(c, stage) + kStageHostCopy, u_max}, b->out,
                                   take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
@@ -514,7 +526,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         }
         if (c->n_host > 0 && u_max > 0) {
             const int64_t stage_max = std::min(u_max, stage == 0 ? n_seeds + p.flat_max[0] : p.flat_max[stage]);
-            link_blocks = copy_role_blocks(chunks, true, stage_max, c->host_blocks, 0);
+            link_blocks = link_role_blocks(c, stage_max);
             link = tier_copy_args(c, 1, stage > 0 ? stage_words(c, stage - 1) + kStageHostCopy : nullptr,
                                   Count{c->cnt + kCntTier + 1, u_max}, b->out, take_stamps(c, HELIOS_ROLE_COPY_HOST, stage, link_blocks));
         }
@@ -1140,6 +1152,7 @@ int helios_gang_create(helios_ctx* const* ctxs, int32_t n_members, int64_t n_see
             c->rec_scans = 0;
             c->err_now = g->member[m]->err;
             c->defer = &steps[m];
+            c->link_share = n_members;
             was_ready[m] = c->blocks_ready;
         }
         e = hipStreamBeginCapture(c0->stream, hipStreamCaptureModeThreadLocal);
@@ -1183,6 +1196,7 @@ int helios_gang_create(helios_ctx* const* ctxs, int32_t n_members, int64_t n_see
             c->recording = false;
             c->err_now = c->err;
             c->defer = nullptr;
+            c->link_share = 1;
             c->blocks_ready = was_ready[m];          // nothing has run
         }
     }

@@ -12,7 +12,7 @@ import pytest
 import torch
 
 from paper_2310_00837_amd import workload as W
-from pathlib_helios import assert_same, gpu_path, lanes_in_flight, oracle_path, to_bytes
+from pathlib_helios import assert_same, gangs_in_flight, gpu_path, lanes_in_flight, oracle_path, to_bytes
 
 pytestmark = pytest.mark.gpu
 SEED = 1234
@@ -69,6 +69,18 @@ def _check_batches(h, helios, oracle, sp, g, host_csr, rank_h, n_hbm, n_host, ta
         del want["out"]
         assert_same(res, want)
     say(f"  {sp.name}: {len(jobs)} recorded batches, one per lane, and {2 * len(jobs)}, two per lane: bit-exact")
+    # and as bench.py's timed region launches them: gangs of four contexts, three gangs in flight
+    gang_jobs, gang_order = list(jobs), list(order_of_jobs)
+    while len(gang_jobs) % 4:
+        gang_jobs.append(jobs[0])
+        gang_order.append(order_of_jobs[0])
+    got = gangs_in_flight(helios, g.offsets, g.indices, g.order, n_hbm, n_host, sp.row_bytes, tabs_dev, sp.batch,
+                          sp.fanouts, gang_jobs + gang_jobs, members=4, n_gangs=3)
+    for b, res in zip(gang_order + gang_order, got):
+        want = dict(wants[b])
+        del want["out"]
+        assert_same(res, want)
+    say(f"  {sp.name}: {2 * len(gang_jobs)} batches in gangs of four, three gangs in flight: bit-exact")
 
 
 def test_workloads_2_and_4_full_size(helios, oracle):
