@@ -112,6 +112,25 @@ def test_workloads_2_and_4_full_size(helios, oracle):
                     full_host[n_hbm + n_host:] if n_rest else None)
         tabs_host = (host_bytes[:n_hbm], host_bytes[n_hbm:n_hbm + n_host], host_bytes[n_hbm + n_host:])
         _check_batches(h, helios, oracle, sp, g, (off_h, idx_h), rank_h, n_hbm, n_host, tabs_dev, tabs_host, batches)
+    # The hotness order at this size (Sec. 3.2.2 "Cache Initialization" sorts every vertex of the graph): with the
+    # in-degrees as counters the result is the workload's own cache order, which the generator computes with
+    # torch's stable sort; and the properties that define the order hold (a permutation, counters descending,
+    # equal counters by ascending ID).
+    counts = torch.zeros(g.n_nodes, dtype=torch.int64, device=dev)
+    for s0 in range(0, g.indices.numel(), 1 << 28):
+        counts += torch.bincount(g.indices[s0:s0 + (1 << 28)].to(torch.int64), minlength=g.n_nodes)
+    counts = counts.to(torch.int32)
+    order = torch.empty(g.n_nodes, dtype=torch.int32, device=dev)
+    h.hotness_order(counts, order)
+    h.sync()
+    assert torch.equal(order, g.order.to(dev))
+    by_order = counts[order.long()]
+    assert bool((by_order[:-1] >= by_order[1:]).all())
+    ties = by_order[:-1] == by_order[1:]
+    assert bool((order[:-1][ties] < order[1:][ties]).all())
+    assert bool((torch.bincount(order.long(), minlength=g.n_nodes) == 1).all())
+    say(f"hotness order of {g.n_nodes} nodes ({int(ties.sum())} ties between neighbours): equal to the stable sort")
+    del counts, order, by_order, ties
     h.close()
     del full_dev, full_host, host_bytes, tabs_dev, tabs_host
     full_host_buf.free()
