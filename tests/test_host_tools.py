@@ -35,6 +35,14 @@ def test_profile_summaries(tmp_path):
     hbm = [ln for ln in lines if ln.startswith("gather_rows_kernel<32, 1, 1>")][0].split()
     assert hbm[-6:-1] == ["2048-4096", "2", "5.00", "4.00", "6.00"]  # workgroups (range), calls, avg, min, max (us)
     assert any(ln.startswith("missq_submit_kernel") and " 16 " in ln for ln in lines)
+    # one line per kernel and grid size: grids seen fewer than five times share a line
+    rows = ['"KERNEL_DISPATCH","void helios::(anonymous namespace)::batch_compact_kernel(helios::CompactGang)",%d,%d,256,%d\n'
+            % (100 * k, 100 * k + (40 if k < 6 else 90), 256 * (51 if k < 6 else 204 if k < 12 else 7 + k)) for k in range(14)]
+    trace.write_text('"Kind","Kernel_Name","Start_Timestamp","End_Timestamp","Workgroup_Size_X","Grid_Size_X"\n' + "".join(rows))
+    by_grid = [ln.split() for ln in prof.trace(str(tmp_path), "x", by_grid=True).splitlines()[1:]]
+    assert [ln[-6:-4] for ln in by_grid] == [["51", "6"], ["204", "6"], ["19-20", "2"]]
+    assert by_grid[2][1:3] == ["(other", "grids)"] and by_grid[0][-4] == "0.04" and by_grid[1][-4] == "0.09"
+    assert len(prof.trace(str(tmp_path), "x").splitlines()) == 2
     pmc = tmp_path / "x_counter_collection.csv"
     pmc.write_text(
         '"Kernel_Name","Counter_Name","Counter_Value","Grid_Size","Workgroup_Size"\n'
