@@ -28,7 +28,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-ROLE_NAMES = {1: "sample", 2: "compact_hop", 3: "compact_lookup", 4: "copy_host", 5: "copy_hbm", 6: "inverse"}
+ROLE_NAMES = {1: "sample", 2: "compact_hop", 3: "compact_lookup", 4: "copy_host", 5: "copy_hbm", 6: "inverse", 7: "copy_standin"}
 
 
 def log(msg: str) -> None:
@@ -413,7 +413,7 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
         """A gang of `members` contexts on one stream, one buffer set per member: the batches of the members go
         through the same launches.  Every member runs one directly launched batch first (see Lane.record)."""
 
-        def __init__(self, members: int, cap: int, host_blocks: int):
+        def __init__(self, members: int, cap: int, host_blocks: int, serve_misses: bool = False):
             self.stream = torch.cuda.Stream(device=dev)
             self.ctxs, self.sets = [], []
             for _ in range(members):
@@ -422,6 +422,8 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
                 ctx.cache_build(order, tiers.n_hbm, tiers.n_host, rb, tiers.hbm, tiers.host, tiers.standin)
                 if host_blocks > 0:
                     ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, host_blocks)
+                if serve_misses:
+                    ctx.set_param(helios.PARAM_SERVE_MISSES, 1)
                 ctx.reserve(cap)
                 bs = Buffers(cap)
                 ctx.prepare_batch(seeds[0], sp.fanouts, rng_seeds[0], *bs.args())
@@ -569,6 +571,19 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
     s6_elapsed, _, _ = repeated(region_serial, Wm, K, D, "zero-copy")
     result["with_miss_service"] = {"value": K / s6_elapsed, "ms_per_step": s6_elapsed / K * 1e3,
                                    "note": "S6 by helios_gather_miss (zero-copy reads of the stand-in) after every batch"}
+    if n_members > 0 and tiers.n_rest > 0:
+        for _ in range(max(1, args.gangs)):
+            gangs.append(GangOnStream(n_members, lanes[0].cap, args.gang_host_blocks, serve_misses=True))
+        torch.cuda.synchronize()
+        region_gangs(0, Wm)
+        gs_elapsed, _, _ = repeated(region_gangs, Wm, K)
+        for gd in gangs:
+            gd.close()
+        gangs.clear()
+        result["with_miss_service"]["by_gangs"] = {
+            "value": K / gs_elapsed, "ms_per_step": gs_elapsed / K * 1e3,
+            "note": "the timed region with HELIOS_PARAM_SERVE_MISSES: every batch copies the rows of its own miss list from "
+                    "the stand-in as a role of its last launch (S1-S6 in the launches of S1-S5)"}
     if args.missq_queues > 0 and tiers.n_rest > 0:
         for ln in lanes:
             ln.record_with_queue()

@@ -59,8 +59,8 @@ typedef enum {
 
 /* Context on `device`, working on `hip_stream` (a hipStream_t, borrowed;
  * NULL = the default stream).  helios_destroy waits for the stream and frees
- * the library's own memory only; while plans or miss queues of the context
- * are alive it returns HELIOS_ESTATE and destroys nothing. */
+ * the library's own memory only; while plans, gangs or miss queues of the
+ * context are alive it returns HELIOS_ESTATE and destroys nothing. */
 int helios_create(helios_ctx **out, int device, void *hip_stream);
 int helios_destroy(helios_ctx *ctx);
 const char *helios_last_error(const helios_ctx *ctx);
@@ -255,13 +255,20 @@ int helios_calibration_copy(helios_ctx *ctx, const void *src, void *dst, int64_t
  * *_GATHER_BLOCKS: workgroups that copy the HBM tier / the host tier and
  * stand-in (0 = built-in default; the host-link copies need few workgroups to
  * fill the link, and fewer of them leave more of the GPU to the work that runs
- * beside them, cf. Sec. 3.3 "Operator Resources Allocation").  SPLIT_COPIES:
+ * beside them, cf. Sec. 3.3 "Operator Resources Allocation"; by default the
+ * members of a gang share what one batch alone would take).  SPLIT_COPIES:
  * zero (the default): helios_prepare_batch overlaps its steps inside its
  * launches (Sec. 3.3, intra-mini-batch pipeline): the host-tier rows that one
  * hop has brought in are copied while the next hop is sampled, and the last
  * ones beside the HBM-tier copy.  Non-zero: the two tier copies run after the
  * last hop as kernels of their own, one after the other (for measuring each
  * copy by itself).
+ * SERVE_MISSES: non-zero: helios_prepare_batch (and recordings and gangs made
+ * while it is set) also serves the batch's miss list from the storage
+ * stand-in, out[miss_pos[k],:] = standin_table[miss_slot[k],:], as
+ * helios_gather_miss would right after it (S6 by zero-copy reads, beside the
+ * last host-tier copy); the miss list is still written.  Needs the stand-in
+ * table; not together with an attached miss queue (HELIOS_ESTATE).
  * MISSQ_TIMEOUT_US: how long a wave of helios_missq_complete's kernel waits
  * without seeing a new completion before it gives up (default 2 000 000);
  * MISSQ_WAVES: waves of that kernel (0 = default 256; at least one per 64
@@ -271,7 +278,8 @@ typedef enum {
     HELIOS_PARAM_HOST_GATHER_BLOCKS = 2,
     HELIOS_PARAM_SPLIT_COPIES = 3,
     HELIOS_PARAM_MISSQ_TIMEOUT_US = 4,
-    HELIOS_PARAM_MISSQ_WAVES = 5
+    HELIOS_PARAM_MISSQ_WAVES = 5,
+    HELIOS_PARAM_SERVE_MISSES = 6
 } helios_param;
 int helios_set_param(helios_ctx *ctx, int param, int64_t value);
 
@@ -434,7 +442,8 @@ typedef enum {
     HELIOS_ROLE_COMPACT_LOOKUP = 3,  /* a stage of the batch's ID list, cache lookup */
     HELIOS_ROLE_COPY_HOST = 4,       /* host-tier rows of a stage                    */
     HELIOS_ROLE_COPY_HBM = 5,        /* HBM-tier rows                                */
-    HELIOS_ROLE_INVERSE = 6
+    HELIOS_ROLE_INVERSE = 6,
+    HELIOS_ROLE_COPY_STANDIN = 7     /* rows of the miss list, from the stand-in     */
 } helios_role;
 typedef struct {
     int32_t kind, stage;

@@ -61,6 +61,7 @@ struct helios_ctx {
     uint32_t stamp_words = 0;                  // words of `clock` taken by them
     double clock_khz = 100000.0;
     unsigned hbm_blocks = 0, host_blocks = 0;  // 0 = the launcher's default
+    bool serve_misses = false;                 // the whole-path call also copies the rows of its miss list from the stand-in
     bool split_copies = false;                 // the whole-path call keeps its row copies in kernels of their own (see helios_set_param)
     char errmsg[256] = {0};
 

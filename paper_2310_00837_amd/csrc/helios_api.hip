@@ -503,6 +503,15 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
     }
 
     // ---- the end of the batch: the rest of the row copies, the inverse map, the next batch's table
+    const int64_t standin_rows = c->g.n_nodes - c->n_hbm - c->n_host;
+    const int64_t served_max = c->serve_misses && standin_rows > 0 ? std::min(b->miss_cap, u_max) : 0;
+    if (c->serve_misses && c->missq) return fail(c, HELIOS_ESTATE, "HELIOS_PARAM_SERVE_MISSES and an attached miss queue exclude each other");
+    if (served_max > 0 && !c->standin_table) return fail(c, HELIOS_ESTATE, "no stand-in table was given to helios_cache_build");
+    // the batch's own miss list, served from the stand-in; its entries are checked like a caller's (a node whose rank the
+    // cache map does not know has slot -1)
+    const GatherArgs miss_args{static_cast<const chunk16*>(c->standin_table), b->miss_pos, b->miss_slot, nullptr,
+                               Count{c->cnt + kCntTier + 2, served_max}, chunks, static_cast<chunk16*>(b->out), standin_rows,
+                               b->unique_cap, err, Stamps{nullptr}};
     if (c->missq) {                 // the misses are on their way while the cached tiers are copied
         const int64_t m_max = std::min(b->miss_cap, u_max);
         int rc = missq_submit_from_batch(c, b->miss_pos, b->miss_slot, Count{c->cnt + kCntTier + 2, m_max}, m_max, b->unique_cap);
@@ -513,13 +522,20 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
     if (c->split_copies) {
         int rc = copy_tiers_split(c, u_max, b->out);
         if (rc) return rc;
+        if (served_max > 0)
+            HIP_TRY(c, launch_gather_rows(c->stream, miss_args, served_max, true, true, c->host_blocks, 0, nullptr, nullptr, nullptr));
         if (b->inverse) HIP_TRY(c, launch_dedup_inverse(c->stream, inv, p.cat_max));
         // (a recording with split copies leaves the emptying of the next table to helios_plan_launch)
         if (!rec && clear_slots) HIP_TRY(c, launch_clear(c->stream, ClearJob{batch_table(c, next), clear_slots}));
     } else {
         const int stage = n_hops - 1;
-        GatherArgs hbm{}, link{};
-        unsigned hbm_blocks = 0, link_blocks = 0, inv_blocks = 0, clear_blocks = 0;
+        GatherArgs hbm{}, link{}, miss{};
+        unsigned hbm_blocks = 0, link_blocks = 0, miss_blocks = 0, inv_blocks = 0, clear_blocks = 0;
+        if (served_max > 0) {
+            miss = miss_args;
+            miss_blocks = link_role_blocks(c, served_max);
+            miss.stamps = take_stamps(c, HELIOS_ROLE_COPY_STANDIN, stage, miss_blocks);
+        }
         if (c->n_hbm > 0 && u_max > 0) {
             hbm_blocks = copy_role_blocks(chunks, false, u_max, c->hbm_blocks, expected_hbm_rows(c));
             hbm = tier_copy_args(c, 0, nullptr, Count{c->cnt + kCntTier + 0, u_max}, b->out, take_stamps(c, HELIOS_ROLE_COPY_HBM, stage, hbm_blocks));
@@ -540,7 +556,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
             clear = ClearJob{batch_table(c, next), clear_slots};      // a recording picks the table on the device
             clear_blocks = std::min(256u, (clear_slots + kBlock * 16 - 1) / (kBlock * 16));
         }
-        int rf = emit_finish(c, FinishJob{hbm, hbm_blocks, link, link_blocks, inv, inv_blocks, clear, clear_blocks, bt, vars});
+        int rf = emit_finish(c, FinishJob{hbm, hbm_blocks, link, link_blocks, miss, miss_blocks, inv, inv_blocks, clear, clear_blocks, bt, vars});
         if (rf) return rf;
     }
     int rc = publish_stamps(c);
@@ -1364,6 +1380,9 @@ int helios_set_param(helios_ctx* c, int param, int64_t value) {
             return HELIOS_OK;
         case HELIOS_PARAM_SPLIT_COPIES:
             c->split_copies = value != 0;
+            return HELIOS_OK;
+        case HELIOS_PARAM_SERVE_MISSES:
+            c->serve_misses = value != 0;
             return HELIOS_OK;
         case HELIOS_PARAM_MISSQ_TIMEOUT_US:
             c->missq_timeout_us = value < 1 ? 1 : value > 60000000 ? 60000000 : value;

@@ -49,15 +49,18 @@ struct CompactJob {
     unsigned look_blocks;
 };
 hipError_t launch_compact(hipStream_t stream, const CompactJob* jobs, int n);
-// The end of a batch in one launch: host-tier copy of the last stage, HBM-tier copy of all stages, the
-// inverse map, and the emptying of the table that the next batch of the context uses.  Any of the four
-// may be absent (0 workgroups).  With vars (a recorded batch) the table to empty is the one after the batch's
+// The end of a batch in one launch: host-tier copy of the last stage, the rows of the miss list from the
+// storage stand-in (if the batch serves its own misses), HBM-tier copy of all stages, the inverse map,
+// and the emptying of the table that the next batch of the context uses.  Any of the five may be absent
+// (0 workgroups).  With vars (a recorded batch) the table to empty is the one after the batch's
 // own among bt's, whatever clear.table says.  The rows of all members have one size.
 struct FinishJob {
     GatherArgs hbm;
     unsigned hbm_blocks;
     GatherArgs link;
     unsigned link_blocks;
+    GatherArgs miss;
+    unsigned miss_blocks;
     InverseArgs inv;
     unsigned inv_blocks;
     ClearJob clear;
@@ -85,12 +88,12 @@ struct CompactGang {
     int n;
 };
 struct FinishMember {
-    GatherArgs hbm, link;
+    GatherArgs hbm, link, miss;
     InverseArgs inv;
     ClearJob clear;
     BatchTables bt;
     const BatchVars* vars;
-    Role r_hbm, r_link, r_inv, r_clear;
+    Role r_hbm, r_link, r_miss, r_inv, r_clear;
 };
 struct FinishGang {
     FinishMember m[kMaxGang];

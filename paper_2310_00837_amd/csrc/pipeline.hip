@@ -14,6 +14,7 @@
 //   sample     hop 1                             |  host-tier copy of stage 0
 //   compact    flat_1 -> stage 1 (the last) of unique, tier lists, miss list, stats
 //   finish     host-tier copy of stage 1  |  HBM-tier copy of all stages  |  inverse  |  emptying of the next batch's table
+//              (|  the rows of the miss list from the storage stand-in, if the batch serves its own misses)
 //
 // Five launches; the host link is busy from the second compaction of hop 0 on, except while a
 // compaction runs.
@@ -68,6 +69,11 @@ __global__ __launch_bounds__(kBlock) void batch_finish_kernel(FinishGang g) {
         if (a.r_link.mine()) {
             if constexpr (L == 0) copy_rows_long(a.link, a.r_link.rb(), a.r_link.blocks);
             else copy_rows<L == 0 ? 64 : L, CPL == 0 ? 1 : CPL, RF == 0 ? 1 : RF>(a.link, a.r_link.rb(), a.r_link.blocks);
+            return;
+        }
+        if (a.r_miss.mine()) {
+            if constexpr (L == 0) copy_rows_long(a.miss, a.r_miss.rb(), a.r_miss.blocks);
+            else copy_rows<L == 0 ? 64 : L, CPL == 0 ? 1 : CPL, RF == 0 ? 1 : RF>(a.miss, a.r_miss.rb(), a.r_miss.blocks);
             return;
         }
         if (a.r_hbm.mine()) {
@@ -190,10 +196,14 @@ hipError_t launch_finish(hipStream_t stream, const FinishJob* jobs, int n) {
         a.clear = jobs[m].clear;
         a.bt = jobs[m].bt;
         a.vars = jobs[m].vars;
+        a.miss = jobs[m].miss;
         a.r_link = Role{at, jobs[m].link_blocks};
         at += jobs[m].link_blocks;
+        a.r_miss = Role{at, jobs[m].miss_blocks};
+        at += jobs[m].miss_blocks;
         // the copies of all members move rows of one size (the loops are compiled for it)
-        const int mine = jobs[m].hbm_blocks > 0 ? jobs[m].hbm.chunks : jobs[m].link_blocks > 0 ? jobs[m].link.chunks : 0;
+        const int mine = jobs[m].hbm_blocks > 0 ? jobs[m].hbm.chunks : jobs[m].link_blocks > 0 ? jobs[m].link.chunks
+                         : jobs[m].miss_blocks > 0 ? jobs[m].miss.chunks : 0;
         if (mine > 0 && chunks > 0 && mine != chunks) return hipErrorInvalidValue;
         if (mine > 0) chunks = mine;
     }

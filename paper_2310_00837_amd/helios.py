@@ -22,7 +22,7 @@ OK, EINVAL, ECAPACITY, EHIP, ESTATE, EDATA, EINTERNAL = 0, -1, -2, -3, -4, -5, -
 MAX_HOPS, MAX_FANOUT = 8, 1024
 DEDUP_NOALLOC_MAX_IDS = 262144
 PARAM_HBM_GATHER_BLOCKS, PARAM_HOST_GATHER_BLOCKS, PARAM_SPLIT_COPIES = 1, 2, 3
-PARAM_MISSQ_TIMEOUT_US, PARAM_MISSQ_WAVES = 4, 5
+PARAM_MISSQ_TIMEOUT_US, PARAM_MISSQ_WAVES, PARAM_SERVE_MISSES = 4, 5, 6
 _NAMES = {0: "HELIOS_OK", -1: "HELIOS_EINVAL", -2: "HELIOS_ECAPACITY", -3: "HELIOS_EHIP", -4: "HELIOS_ESTATE",
           -5: "HELIOS_EDATA", -6: "HELIOS_EINTERNAL"}
 
@@ -59,7 +59,7 @@ class RoleTicks(C.Structure):
                 ("end", C.c_uint64)]
 
 
-ROLE_SAMPLE, ROLE_COMPACT_HOP, ROLE_COMPACT_LOOKUP, ROLE_COPY_HOST, ROLE_COPY_HBM, ROLE_INVERSE = 1, 2, 3, 4, 5, 6
+ROLE_SAMPLE, ROLE_COMPACT_HOP, ROLE_COMPACT_LOOKUP, ROLE_COPY_HOST, ROLE_COPY_HBM, ROLE_INVERSE, ROLE_COPY_STANDIN = 1, 2, 3, 4, 5, 6, 7
 
 
 class HeliosError(RuntimeError):

@@ -226,3 +226,84 @@ def test_gang_argument_errors(helios, small):
     on_default.close()
     for h in every:
         h.close()
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_batches_that_serve_their_own_misses(helios, oracle, small, cfg):
+    """HELIOS_PARAM_SERVE_MISSES: the whole-path call also copies the rows of its miss list from the stand-in (S6), as
+    a role of its last launch.  Directly launched, with split copies, recorded, and in a gang, `out` must be what the
+    oracle has after its miss service, and the miss list is still there."""
+    sp, g, feats = small(cfg)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    rank, tabs = _oracle_side(oracle, sp, g, feats)
+    off, idx = g.offsets.numpy(), g.indices.numpy()
+    st = torch.cuda.Stream()
+    off_d, idx_d = g.offsets.cuda(), g.indices.cuda()
+    ctxs, cache = [], None
+    for m in range(3):
+        h = helios.Helios(0, stream=st)
+        h.csr_load(off_d, idx_d)
+        if cache is None:
+            cache = GpuCache(h, feats, g.order, n_hbm, n_host)
+        else:
+            h.cache_build(cache.order, n_hbm, n_host, sp.row_bytes, cache.hbm, cache.host, cache.standin)
+        h.set_param(helios.PARAM_SERVE_MISSES, 1)
+        ctxs.append(h)
+    seeds = [W.seed_batch(sp, g, b).cuda() for b in range(4)]
+    wants = [oracle_path(oracle, off, idx, seeds[b].cpu().numpy(), sp.fanouts, 40 + b, rank, n_hbm, n_host, *tabs, sp.row_bytes)
+             for b in range(4)]
+    assert all(int(w["stats"][3]) > 0 for w in wants)              # there are misses to serve
+
+    def served(res, want):
+        got = dict(res)
+        got["out"] = got.pop("out_before_miss")                    # what the call left in `out` already has the missed rows
+        want = dict(want)
+        del want["out_before_miss"]
+        assert_same(got, want)
+
+    # directly launched, roles and split copies
+    served(gpu_path(ctxs[0], helios, seeds[0], sp.fanouts, 40, fused=True, serve_misses=False), wants[0])
+    ctxs[0].set_param(helios.PARAM_SPLIT_COPIES, 1)
+    served(gpu_path(ctxs[0], helios, seeds[1], sp.fanouts, 41, fused=True, serve_misses=False), wants[1])
+    ctxs[0].set_param(helios.PARAM_SPLIT_COPIES, 0)
+    # recorded
+    bs = _buffers(helios, ctxs[0], sp)
+    ctxs[0].reserve(bs.inverse.numel())
+    plan = ctxs[0].plan_create(sp.batch, sp.fanouts, bs.hops, bs.sizes, bs.unique, bs.inverse, bs.n_unique, bs.out, bs.miss_pos,
+                               bs.miss_id, bs.miss_slot, bs.stats)
+    for b in (2, 3):
+        bs.out.fill_(SENTINEL)
+        torch.cuda.synchronize()
+        plan.launch(seeds[b], 40 + b)
+        plan.wait()
+        served(_result(bs, sp), wants[b])
+    plan.destroy()
+    # in a gang
+    sets = [_buffers(helios, h, sp) for h in ctxs]
+    for h, b_ in zip(ctxs, sets):
+        h.reserve(b_.inverse.numel())
+        h.sync()
+    gang = helios.Gang(ctxs, sp.batch, sp.fanouts, sets)
+    for rnd in range(2):
+        for b_ in sets:
+            b_.out.fill_(SENTINEL)
+        torch.cuda.synchronize()
+        pick = [(rnd + m) % 4 for m in range(3)]
+        gang.launch([seeds[b] for b in pick], [40 + b for b in pick])
+        assert gang.wait() == [0, 0, 0]
+        for m, b in enumerate(pick):
+            served(_result(sets[m], sp), wants[b])
+    gang.destroy()
+    # not together with an attached miss queue; not without a stand-in table
+    q = helios.MissQueue(ctxs[1], 4, 4096, 1)
+    q.attach()
+    with pytest.raises(helios.HeliosError) as e:
+        gpu_path(ctxs[1], helios, seeds[0], sp.fanouts, 40, fused=True, serve_misses=False)
+    assert e.value.code == helios.ESTATE
+    q.destroy()
+    ctxs[2].cache_build(cache.order, n_hbm, n_host, sp.row_bytes, cache.hbm, cache.host, None)
+    with pytest.raises(helios.HeliosError) as e:
+        gpu_path(ctxs[2], helios, seeds[0], sp.fanouts, 40, fused=True, serve_misses=False)
+    assert e.value.code == helios.ESTATE
+    for h in ctxs:
+        h.close()
