@@ -307,3 +307,50 @@ def test_batches_that_serve_their_own_misses(helios, oracle, small, cfg):
     assert e.value.code == helios.ESTATE
     for h in ctxs:
         h.close()
+
+
+def test_gang_of_small_and_odd_batches(helios, oracle, small):
+    """Three hops, a handful of seeds with repeats, a fan-out above the group width of the others, an empty hop: the
+    members of a gang take the same steps whatever their data, and each still equals the oracle."""
+    sp, g, feats = small(0)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    rank, tabs = _oracle_side(oracle, sp, g, feats)
+    off, idx = g.offsets.numpy(), g.indices.numpy()
+    st = torch.cuda.Stream()
+    off_d, idx_d = g.offsets.cuda(), g.indices.cuda()
+    ctxs, cache = [], None
+    for m in range(2):
+        h = helios.Helios(0, stream=st)
+        h.csr_load(off_d, idx_d)
+        if cache is None:
+            cache = GpuCache(h, feats, g.order, n_hbm, n_host)
+        else:
+            h.cache_build(cache.order, n_hbm, n_host, sp.row_bytes, cache.hbm, cache.host, cache.standin)
+        ctxs.append(h)
+    hub = int(g.order[0])
+    for n_seeds, fanouts in ((5, [3, 70, 2]), (1, [4, 0, 3]), (7, [2, 2, 2])):
+        class Shape:
+            batch = n_seeds
+            row_bytes = sp.row_bytes
+        Shape.fanouts = fanouts
+        sets = [_buffers(helios, h, Shape) for h in ctxs]
+        for h, bs in zip(ctxs, sets):
+            h.reserve(bs.inverse.numel())
+            h.sync()
+        gang = helios.Gang(ctxs, n_seeds, fanouts, sets)
+        for rnd in range(2):
+            seed_lists = [torch.tensor(([hub, 17, hub, 4242, 17, 9, 9999] * 2)[m + rnd:m + rnd + n_seeds], dtype=torch.int32).cuda()
+                          for m in range(2)]
+            rs = [900 + 10 * rnd + m for m in range(2)]
+            for bs in sets:
+                bs.out.fill_(SENTINEL)
+            torch.cuda.synchronize()
+            gang.launch(seed_lists, rs)
+            assert gang.wait() == [0, 0]
+            for m in range(2):
+                want = oracle_path(oracle, off, idx, seed_lists[m].cpu().numpy(), fanouts, rs[m], rank, n_hbm, n_host, *tabs, sp.row_bytes)
+                del want["out"]
+                assert_same(_result(sets[m], Shape), want)
+        gang.destroy()
+    for h in ctxs:
+        h.close()
