@@ -33,6 +33,19 @@ def test_host_side_argument_errors_need_no_device():
     assert lib.helios_last_error(None) == b"no context"
     assert lib.helios_host_alloc(0) is None
     assert lib.helios_host_free(None) == helios.OK
+    # plans and gangs: NULL handles and NULL member lists
+    assert lib.helios_plan_launch(None, None, 0) == helios.EINVAL
+    assert lib.helios_plan_wait(None) == helios.EINVAL
+    assert lib.helios_plan_destroy(None) == helios.EINVAL
+    out = ctypes.c_void_p()
+    assert lib.helios_gang_create(None, 2, 8, None, 1, None, ctypes.byref(out)) == helios.EINVAL and not out.value
+    none_ctx = (ctypes.c_void_p * 2)(None, None)
+    assert lib.helios_gang_create(none_ctx, 2, 8, None, 1, None, ctypes.byref(out)) == helios.EINVAL
+    assert lib.helios_gang_launch(None, None, None) == helios.EINVAL
+    assert lib.helios_gang_wait(None, None) == helios.EINVAL
+    assert lib.helios_gang_make_blocks(None, 0, None) == helios.EINVAL
+    assert lib.helios_gang_destroy(None) == helios.EINVAL
+    assert helios.MAX_GANG == 4
 
 
 def test_product_package_does_not_import_the_oracle():
