@@ -413,7 +413,7 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
         """A gang of `members` contexts on one stream, one buffer set per member: the batches of the members go
         through the same launches.  Every member runs one directly launched batch first (see Lane.record)."""
 
-        def __init__(self, members: int, cap: int, host_blocks: int, serve_misses: bool = False):
+        def __init__(self, members: int, cap: int, host_blocks: int, serve_misses: bool = False, timed: bool = False):
             self.stream = torch.cuda.Stream(device=dev)
             self.ctxs, self.sets = [], []
             for _ in range(members):
@@ -424,6 +424,8 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
                     ctx.set_param(helios.PARAM_HOST_GATHER_BLOCKS, host_blocks)
                 if serve_misses:
                     ctx.set_param(helios.PARAM_SERVE_MISSES, 1)
+                if timed:
+                    ctx.set_timing(1)
                 ctx.reserve(cap)
                 bs = Buffers(cap)
                 ctx.prepare_batch(seeds[0], sp.fanouts, rng_seeds[0], *bs.args())
@@ -472,6 +474,32 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
                 gd.live = 0
         torch.cuda.synchronize()
         return time.perf_counter() - t_begin, acc
+
+    def region_gang_roles(count: int, members: int):
+        """One gang in flight, its roles timed by the device clock (timing level 1 is part of the recording): per role
+        the average span in one member and the span over all members (first start to last end), and the whole gang."""
+        gd = GangOnStream(members, lanes[0].cap, args.gang_host_blocks, timed=True)
+        per_member, over_gang, whole = {}, {}, 0.0
+        for k in range(count):
+            ks = [(Wm + k * members + m) % n_batches for m in range(members)]
+            gd.gang.launch([seeds[b] for b in ks], [rng_seeds[b] for b in ks])
+            gd.gang.wait()
+            per_us, live = 1.0, []
+            for ctx in gd.ctxs:
+                roles, per_us = ctx.batch_ticks()
+                live.append({f"{ROLE_NAMES.get(kind, kind)}_{stage}": (a, z) for kind, stage, wgs, a, z in roles if z > a})
+            keys = sorted(set(k_ for lv in live for k_ in lv))
+            t_first = min(a for lv in live for a, _ in lv.values())
+            whole += (max(z for lv in live for _, z in lv.values()) - t_first) / per_us
+            for key in keys:
+                spans = [lv[key] for lv in live if key in lv]
+                per_member.setdefault(key, []).append(sum(z - a for a, z in spans) / len(spans) / per_us)
+                over_gang.setdefault(key, []).append((max(z for _, z in spans) - min(a for a, _ in spans)) / per_us)
+        gd.close()
+        return {"members": members, "avg_us_per_role_in_one_member": {k_: sum(v) / len(v) for k_, v in per_member.items()},
+                "avg_us_per_role_over_the_gang": {k_: sum(v) / len(v) for k_, v in over_gang.items()},
+                "gang_span_us": whole / count,
+                "note": "device clock, one gang in flight (its members' mini-batches in the same launches)"}
 
     result = {"dtype": "int32 ids / byte rows (" + ("fp32" if sp.dtype == torch.float32 else "fp16") + " features)",
               "config": {"workload": f"BASELINE.json configs[{cfg}] {sp.name}", "n_nodes": g.n_nodes, "n_edges": g.n_edges,
@@ -536,6 +564,7 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
             "mini-batches in the same launches; helios_gang_wait), %d gangs of %d contexts, each gang on its own stream with "
             "one launch sequence queued; median of %d runs of the K steps" % (n_members, n_gangs, n_members, args.repeats))
         result["lanes"] = lanes_res
+        result["gang_roles"] = region_gang_roles(min(K, 25), n_members)
         result.update(value=K / elapsed, ms_per_step=elapsed / K * 1e3, runs_ms_per_step=[s / K * 1e3 for s in all_runs],
                       batches_in_flight=n_members * n_gangs)
     else:

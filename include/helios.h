@@ -333,8 +333,9 @@ int helios_plan_destroy(helios_plan *plan);
  * helios_prepare_batch; hops points to n_hops entries) and its results and
  * errors are those of helios_prepare_batch on that context, bit for bit.
  * n_seeds (at most 2048), the fan-outs and n_hops are the same for all
- * members.  Timing, split copies and an attached miss queue do not go with a
- * gang (HELIOS_ESTATE).  Argument errors are reported through ctxs[0]
+ * members.  Event timing (level 2), split copies and an attached miss queue do
+ * not go with a gang (HELIOS_ESTATE); timing level 1 at creation is part of the
+ * recording, and helios_batch_ticks then gives a member's roles.  Argument errors are reported through ctxs[0]
  * (helios_last_error).
  *
  * helios_gang_launch: seeds[m] (device int32[n_seeds]) and rng_seeds[m] are

@@ -382,7 +382,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         return fail(c, HELIOS_EINTERNAL, "launch bounds of the batch do not fit the scratch");
 
     const bool fold = n_seeds <= kFoldMaxSeeds;
-    if (c->defer && (!fold || !b || c->split_copies || c->missq || c->timing != 0))
+    if (c->defer && (!fold || !b || c->split_copies || c->missq || c->timing > 1))
         return fail(c, HELIOS_EINTERNAL, "this call cannot be part of a gang");       // (refused earlier, with the reason)
     if (!fold) {
         uint32_t epoch;
@@ -559,7 +559,7 @@ int run_pipeline(helios_ctx* c, const int32_t* seeds, int64_t n_seeds, const int
         int rf = emit_finish(c, FinishJob{hbm, hbm_blocks, link, link_blocks, miss, miss_blocks, inv, inv_blocks, clear, clear_blocks, bt, vars});
         if (rf) return rf;
     }
-    int rc = publish_stamps(c);
+    int rc = c->defer ? HELIOS_OK : publish_stamps(c);      // (a gang publishes after its launches have gone out)
     if (rc) return rc;
     if (!rec) {
         for (int t = 0; t < 2; ++t) c->hop_dirty[t] = 0;
@@ -1136,8 +1136,8 @@ int helios_gang_create(helios_ctx* const* ctxs, int32_t n_members, int64_t n_see
             return fail(c0, HELIOS_EINVAL, "member %d is not on the stream of member 0: a gang's contexts share one stream", m);
         if (!c->has_graph || !c->has_cache) return fail(c0, HELIOS_ESTATE, "member %d has no graph or no cache", m);
         if (c->row_bytes != c0->row_bytes) return fail(c0, HELIOS_EINVAL, "member %d has rows of another size", m);
-        if (c->timing != 0 || c->split_copies || c->missq)
-            return fail(c0, HELIOS_ESTATE, "member %d: timing, split copies and an attached miss queue do not go with a gang", m);
+        if (c->timing > 1 || c->split_copies || c->missq)
+            return fail(c0, HELIOS_ESTATE, "member %d: event timing, split copies and an attached miss queue do not go with a gang", m);
         if (c->recording) return fail(c0, HELIOS_ESTATE, "member %d is being recorded", m);
     }
     DeviceGuard guard(c0->device);
@@ -1204,6 +1204,8 @@ int helios_gang_create(helios_ctx* const* ctxs, int32_t n_members, int64_t n_see
                     e = launch_finish(c0->stream, jobs, n_members);
                 }
             }
+            // members whose roles are timed (timing level 1 at creation) publish their ticks behind the last launch
+            for (int m = 0; m < n_members && rc == HELIOS_OK && e == hipSuccess; ++m) rc = publish_stamps(ctxs[m]);
             hipError_t e2 = hipStreamEndCapture(c0->stream, &g->graph);
             if (rc == HELIOS_OK && e == hipSuccess && e2 != hipSuccess) e = e2;
         }

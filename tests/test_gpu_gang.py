@@ -207,7 +207,7 @@ def test_gang_argument_errors(helios, small):
     others[0].set_param(helios.PARAM_SPLIT_COPIES, 1)
     refused(helios.ESTATE, [a, others[0]])
     others[0].set_param(helios.PARAM_SPLIT_COPIES, 0)
-    others[1].set_timing(1)
+    others[1].set_timing(2)                                 # event timing cannot be recorded
     refused(helios.ESTATE, [a, others[1]])
     others[1].set_timing(0)
     q = helios.MissQueue(others[2], 4, 1024, 1)
@@ -352,5 +352,58 @@ def test_gang_of_small_and_odd_batches(helios, oracle, small):
                 del want["out"]
                 assert_same(_result(sets[m], Shape), want)
         gang.destroy()
+    for h in ctxs:
+        h.close()
+
+
+def test_roles_of_a_gang_are_timed_per_member(helios, oracle, small):
+    """Timing level 1 is part of a gang's recording: every member gets the ticks of its own roles, the results stay
+    those of the oracle, and the members' roles of one launch run at the same time."""
+    sp, g, feats = small(1)
+    n_hbm, n_host, _ = sp.tier_rows(g.n_nodes)
+    rank, tabs = _oracle_side(oracle, sp, g, feats)
+    off, idx = g.offsets.numpy(), g.indices.numpy()
+    st = torch.cuda.Stream()
+    off_d, idx_d = g.offsets.cuda(), g.indices.cuda()
+    ctxs, cache = [], None
+    for m in range(3):
+        h = helios.Helios(0, stream=st)
+        h.csr_load(off_d, idx_d)
+        if cache is None:
+            cache = GpuCache(h, feats, g.order, n_hbm, n_host)
+        else:
+            h.cache_build(cache.order, n_hbm, n_host, sp.row_bytes, cache.hbm, cache.host, cache.standin)
+        h.set_timing(1)
+        ctxs.append(h)
+    sets = [_buffers(helios, h, sp) for h in ctxs]
+    for h, bs in zip(ctxs, sets):
+        h.reserve(bs.inverse.numel())
+        h.sync()
+    gang = helios.Gang(ctxs, sp.batch, sp.fanouts, sets)
+    for rnd in range(2):
+        seeds = [W.seed_batch(sp, g, 3 * rnd + m).cuda() for m in range(3)]
+        rs = [W.batch_rng_seed(SEED, 3 * rnd + m) for m in range(3)]
+        for bs in sets:
+            bs.out.fill_(SENTINEL)
+        torch.cuda.synchronize()
+        gang.launch(seeds, rs)
+        assert gang.wait() == [0, 0, 0]
+        for m in range(3):
+            want = oracle_path(oracle, off, idx, seeds[m].cpu().numpy(), sp.fanouts, rs[m], rank, n_hbm, n_host, *tabs, sp.row_bytes)
+            del want["out"]
+            assert_same(_result(sets[m], sp), want)
+        per_member = []
+        for h in ctxs:
+            roles, per_us = h.batch_ticks()
+            live = {(kind, stage): (a, z) for kind, stage, wgs, a, z in roles if z > a}
+            assert per_us > 0
+            for key in ((helios.ROLE_SAMPLE, 0), (helios.ROLE_SAMPLE, 1), (helios.ROLE_COMPACT_LOOKUP, 0), (helios.ROLE_COMPACT_LOOKUP, 1),
+                        (helios.ROLE_COPY_HBM, 1), (helios.ROLE_COPY_HOST, 0), (helios.ROLE_COPY_HOST, 1), (helios.ROLE_INVERSE, 1)):
+                assert key in live, (key, sorted(live))
+            per_member.append(live)
+        # the last host-tier copies of the three members share a launch: each starts before the others end
+        spans = [pm[(helios.ROLE_COPY_HOST, 1)] for pm in per_member]
+        assert max(a for a, _ in spans) < min(z for _, z in spans)
+    gang.destroy()
     for h in ctxs:
         h.close()
