@@ -351,6 +351,17 @@ def test_gang_of_small_and_odd_batches(helios, oracle, small):
                 want = oracle_path(oracle, off, idx, seed_lists[m].cpu().numpy(), fanouts, rs[m], rank, n_hbm, n_host, *tabs, sp.row_bytes)
                 del want["out"]
                 assert_same(_result(sets[m], Shape), want)
+        if n_seeds == 7:
+            # more launches than the ring of per-batch variables has slots, queued without a wait in between
+            for k in range(300):
+                gang.launch(seed_lists, [5000 + k, 6000 + k])
+            assert gang.wait() == [0, 0]
+            for m in range(2):
+                want = oracle_path(oracle, off, idx, seed_lists[m].cpu().numpy(), fanouts, [5299, 6299][m], rank, n_hbm, n_host, *tabs,
+                                   sp.row_bytes)
+                got = _result(sets[m], Shape)
+                for key in ("unique", "inverse", "stats", "miss_pos", "miss_id", "miss_slot"):
+                    assert np.array_equal(got[key], want[key]), key
         gang.destroy()
     for h in ctxs:
         h.close()
