@@ -35,6 +35,15 @@ def log(msg: str) -> None:
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
+def optional(what: str, fn):
+    """A secondary region of the benchmark: if it raises, the line still carries the headline figures."""
+    try:
+        return fn()
+    except Exception as e:                      # noqa: BLE001 (reported in the line)
+        log(f"{what} failed: {e!r}")
+        return {"error": repr(e)}
+
+
 def measure_host_link(torch, gib: float = 1.0) -> float:
     """Pinned host -> device copy rate in GB/s (best of 5), the denominator of the host-tier gather."""
     n = int(gib * (1 << 30))
@@ -564,7 +573,15 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
             "mini-batches in the same launches; helios_gang_wait), %d gangs of %d contexts, each gang on its own stream with "
             "one launch sequence queued; median of %d runs of the K steps" % (n_members, n_gangs, n_members, args.repeats))
         result["lanes"] = lanes_res
-        result["gang_roles"] = region_gang_roles(min(K, 25), n_members)
+        result["gang_roles"] = optional("gang_roles", lambda: region_gang_roles(min(K, 25), n_members))
+        hbm_role_us = max([v for k_, v in result["gang_roles"].get("avg_us_per_role_in_one_member", {}).items()
+                           if k_.startswith("copy_hbm")] or [0.0])
+        if hbm_role_us > 0:
+            in_gang = 2.0 * (acc["hbm_rows"] / K) * rb / (hbm_role_us * 1e-6) / 1e9
+            result["roofline"]["inside_a_gang"] = {
+                "achieved": in_gang, "frac": in_gang / HBM_PEAK_GBS, "avg_role_us": hbm_role_us,
+                "note": "the HBM-tier copy as a role of a gang's last launch (the timed region's form), beside the host-tier "
+                        "copies: rows per batch x bytes per row / span of one member's role by the device clock"}
         result.update(value=K / elapsed, ms_per_step=elapsed / K * 1e3, runs_ms_per_step=[s / K * 1e3 for s in all_runs],
                       batches_in_flight=n_members * n_gangs)
     else:
@@ -594,13 +611,17 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
             pb.free()
         return result
 
-    lane_elapsed, _, _ = repeated(region_serial, Wm, K, D, None)
-    result["one_batch_per_lane"] = {"value": K / lane_elapsed, "ms_per_step": lane_elapsed / K * 1e3,
-                                    "note": "%d lanes, helios_sync on a lane before it gets its next batch" % D}
-    s6_elapsed, _, _ = repeated(region_serial, Wm, K, D, "zero-copy")
-    result["with_miss_service"] = {"value": K / s6_elapsed, "ms_per_step": s6_elapsed / K * 1e3,
-                                   "note": "S6 by helios_gather_miss (zero-copy reads of the stand-in) after every batch"}
-    if n_members > 0 and tiers.n_rest > 0:
+    def per_lane_region():
+        lane_elapsed, _, _ = repeated(region_serial, Wm, K, D, None)
+        return {"value": K / lane_elapsed, "ms_per_step": lane_elapsed / K * 1e3,
+                "note": "%d lanes, helios_sync on a lane before it gets its next batch" % D}
+
+    def miss_service_region():
+        s6_elapsed, _, _ = repeated(region_serial, Wm, K, D, "zero-copy")
+        return {"value": K / s6_elapsed, "ms_per_step": s6_elapsed / K * 1e3,
+                "note": "S6 by helios_gather_miss (zero-copy reads of the stand-in) after every batch"}
+
+    def miss_service_by_gangs():
         for _ in range(max(1, args.gangs)):
             gangs.append(GangOnStream(n_members, lanes[0].cap, args.gang_host_blocks, serve_misses=True))
         torch.cuda.synchronize()
@@ -609,11 +630,11 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
         for gd in gangs:
             gd.close()
         gangs.clear()
-        result["with_miss_service"]["by_gangs"] = {
-            "value": K / gs_elapsed, "ms_per_step": gs_elapsed / K * 1e3,
-            "note": "the timed region with HELIOS_PARAM_SERVE_MISSES: every batch copies the rows of its own miss list from "
-                    "the stand-in as a role of its last launch (S1-S6 in the launches of S1-S5)"}
-    if args.missq_queues > 0 and tiers.n_rest > 0:
+        return {"value": K / gs_elapsed, "ms_per_step": gs_elapsed / K * 1e3,
+                "note": "the timed region with HELIOS_PARAM_SERVE_MISSES: every batch copies the rows of its own miss list from "
+                        "the stand-in as a role of its last launch (S1-S6 in the launches of S1-S5)"}
+
+    def miss_queue_region():
         for ln in lanes:
             ln.record_with_queue()
         torch.cuda.synchronize()
@@ -621,13 +642,19 @@ def run_workload(args, cfg: int, hbm_frac, K: int, Wm: int, link_gbs: float, ful
         q_elapsed, _, _ = repeated(region_serial, Wm, K, D, "queue")
         for ln in lanes:
             ln.drop_queue()
-        result["with_async_miss_queue"] = {
-            "value": K / q_elapsed, "ms_per_step": q_elapsed / K * 1e3, "queues_per_lane": args.missq_queues,
-            "service_threads_per_lane": args.missq_threads,
-            "note": "S6 in the shape of the paper's IO stack: submission kernel, host threads serving the stand-in "
-                    "into a pinned staging buffer, completion kernel"}
+        return {"value": K / q_elapsed, "ms_per_step": q_elapsed / K * 1e3, "queues_per_lane": args.missq_queues,
+                "service_threads_per_lane": args.missq_threads,
+                "note": "S6 in the shape of the paper's IO stack: submission kernel, host threads serving the stand-in "
+                        "into a pinned staging buffer, completion kernel"}
+
+    result["one_batch_per_lane"] = optional("one_batch_per_lane", per_lane_region)
+    result["with_miss_service"] = optional("with_miss_service", miss_service_region)
+    if n_members > 0 and tiers.n_rest > 0:
+        result["with_miss_service"]["by_gangs"] = optional("with_miss_service.by_gangs", miss_service_by_gangs)
+    if args.missq_queues > 0 and tiers.n_rest > 0:
+        result["with_async_miss_queue"] = optional("with_async_miss_queue", miss_queue_region)
     if args.large_list_gb > 0:
-        result["roofline"]["large_list"] = large_list(torch, helios, dev, rb, args.large_list_gb, args.seed)
+        result["roofline"]["large_list"] = optional("large_list", lambda: large_list(torch, helios, dev, rb, args.large_list_gb, args.seed))
 
     # ---------------- CPU oracle on the same batches (reported baseline) + parity of one batch
     if not args.no_cpu:
@@ -761,8 +788,7 @@ def main() -> int:
         import gc
         gc.collect()
         torch.cuda.empty_cache()
-        also = run_workload(args, args.also, None, K, Wm, link_gbs, full=False)
-        line["also"] = also
+        line["also"] = optional("also", lambda: run_workload(args, args.also, None, K, Wm, link_gbs, full=False))
     print(json.dumps(line))
     return 0
 
