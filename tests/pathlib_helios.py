@@ -169,10 +169,11 @@ def lanes_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, t
 
 
 def gangs_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, tabs_dev, batch, fanouts, jobs,
-                    members: int = 3, n_gangs: int = 2, tune=None):
+                    members: int = 3, n_gangs: int = 2, tune=None, served: bool = False):
     """bench.py's gang configuration: n_gangs streams, on each a gang of `members` contexts with one buffer set
     per member; the jobs go out `members` at a time, to the gangs in turn, and a gang is waited for
-    (helios_gang_wait) before it gets its next batches.  Misses are not served (result key "out_before_miss").
+    (helios_gang_wait) before it gets its next batches.  Misses are not served (result key "out_before_miss"), unless
+    served: then every batch serves its own (HELIOS_PARAM_SERVE_MISSES; result key "out").
     jobs: list of (seeds on the GPU, rng_seed), a multiple of `members`.  Returns one result dict per job."""
     import torch as T
     assert len(jobs) % members == 0
@@ -188,6 +189,8 @@ def gangs_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, t
             ctx.cache_build(order, n_hbm, n_host, row_bytes, *tabs_dev)
             if tune is not None:
                 tune(ctx)
+            if served:
+                ctx.set_param(helios.PARAM_SERVE_MISSES, 1)
             hops = helios.alloc_hops(batch, fanouts, dev)
             cap = batch + sum(hb.flat.numel() for hb in hops)
             ctx.reserve(cap)
@@ -217,8 +220,8 @@ def gangs_in_flight(helios, offsets, indices, order, n_hbm, n_host, row_bytes, t
             n_cat = batch + sum(int(sizes[2 * k + 1]) for k in range(K))
             r.update(unique=bs.unique[:U].cpu().numpy(), inverse=bs.inverse[:n_cat].cpu().numpy(),
                      stats=bs.stats.numpy().copy(), miss_pos=bs.miss_pos[:nm].cpu().numpy(),
-                     miss_id=bs.miss_id[:nm].cpu().numpy(), miss_slot=bs.miss_slot[:nm].cpu().numpy(),
-                     out_before_miss=bs.out[:U].cpu().numpy())
+                     miss_id=bs.miss_id[:nm].cpu().numpy(), miss_slot=bs.miss_slot[:nm].cpu().numpy())
+            r["out" if served else "out_before_miss"] = bs.out[:U].cpu().numpy()
             res.append(r)
         return res
 

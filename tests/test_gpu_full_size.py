@@ -81,6 +81,15 @@ def _check_batches(h, helios, oracle, sp, g, host_csr, rank_h, n_hbm, n_host, ta
         del want["out"]
         assert_same(res, want)
     say(f"  {sp.name}: {2 * len(gang_jobs)} batches in gangs of four, three gangs in flight: bit-exact")
+    if tabs_dev[2] is not None:
+        # ... and with every batch serving its own misses from the stand-in (S6 as a role of the last launch)
+        got = gangs_in_flight(helios, g.offsets, g.indices, g.order, n_hbm, n_host, sp.row_bytes, tabs_dev, sp.batch,
+                              sp.fanouts, gang_jobs, members=4, n_gangs=2, served=True)
+        for b, res in zip(gang_order, got):
+            want = dict(wants[b])
+            del want["out_before_miss"]
+            assert_same(res, want)
+        say(f"  {sp.name}: {len(gang_jobs)} batches in gangs that serve their own misses: bit-exact")
 
 
 def test_workloads_2_and_4_full_size(helios, oracle):
