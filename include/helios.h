@@ -344,7 +344,8 @@ int helios_plan_destroy(helios_plan *plan);
  * (nullable, n_members entries) receives every member's own device-side
  * error code, the return value is the first that is not HELIOS_OK.
  * helios_gang_make_blocks: helios_plan_make_blocks for one member's batch.
- * Between launches of a gang its contexts may be used for other calls; the
+ * A call on a gang counts as a call on each of its contexts (one host thread
+ * at a time).  Between launches of a gang its contexts may be used for other calls; the
  * rules of a recorded batch apply to every member (scratch, cache and graph
  * unchanged since the recording; at most 255 launches without a wait).
  * Destroy the gang before its contexts. */
