@@ -1084,6 +1084,7 @@ int helios_plan_create(helios_ctx* c, int64_t n_seeds, const int32_t* fanouts, i
     if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&pl->exec, pl->graph, nullptr, nullptr, 0);
     if (e == hipSuccess && rc == HELIOS_OK) e = hipEventCreateWithFlags(&pl->done, hipEventDisableTiming);
     if (e != hipSuccess || rc != HELIOS_OK) {
+        reset_stamps(c);                             // whatever the failed recording took
         free_plan(pl);
         if (rc != HELIOS_OK) return rc;
         return fail(c, HELIOS_EHIP, "recording the batch failed: %s", hipGetErrorString(e));
@@ -1234,8 +1235,10 @@ int helios_gang_create(helios_ctx* const* ctxs, int32_t n_members, int64_t n_see
     if (e == hipSuccess && rc == HELIOS_OK) e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
     if (e == hipSuccess && rc == HELIOS_OK) e = hipEventCreateWithFlags(&g->done, hipEventDisableTiming);
     if (e != hipSuccess || rc != HELIOS_OK) {
-        for (int m = 0; m < n_members; ++m)
+        for (int m = 0; m < n_members; ++m) {
+            reset_stamps(ctxs[m]);                   // whatever the failed recording took
             if (g->member[m]) free_plan(g->member[m]);
+        }
         if (g->exec) (void)hipGraphExecDestroy(g->exec);
         if (g->graph) (void)hipGraphDestroy(g->graph);
         if (g->done) (void)hipEventDestroy(g->done);
