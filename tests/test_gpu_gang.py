@@ -328,7 +328,7 @@ def test_gang_of_small_and_odd_batches(helios, oracle, small):
             h.cache_build(cache.order, n_hbm, n_host, sp.row_bytes, cache.hbm, cache.host, cache.standin)
         ctxs.append(h)
     hub = int(g.order[0])
-    for n_seeds, fanouts in ((5, [3, 70, 2]), (1, [4, 0, 3]), (7, [2, 2, 2])):
+    for n_seeds, fanouts in ((5, [3, 70, 2]), (1, [4, 0, 3]), (0, [3, 2]), (7, [2, 2, 2])):
         class Shape:
             batch = n_seeds
             row_bytes = sp.row_bytes
