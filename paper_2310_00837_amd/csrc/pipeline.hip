@@ -16,7 +16,7 @@
 //   finish     host-tier copy of stage 1  |  HBM-tier copy of all stages  |  inverse  |  emptying of the next batch's table
 //              (|  the rows of the miss list from the storage stand-in, if the batch serves its own misses)
 //
-// Five launches; the host link is busy from the second compaction of hop 0 on, except while a
+// Five launches; the host link is busy from the end of the first compaction on, except while a
 // compaction runs.
 #include "kernels.hpp"
 
